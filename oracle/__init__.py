@@ -1,0 +1,17 @@
+"""CPU oracle for the LIEC-SGD compressed step.  TEST INFRASTRUCTURE ONLY.
+
+Only the tests, the smoke check and the bench's CPU-baseline leg may import
+this package; the product (``paper_2402_11857_amd``) never does.
+"""
+from .liec_oracle import (  # noqa: F401
+    IDENTITY,
+    SIGN,
+    TOPK,
+    Desc,
+    build,
+    compress,
+    error_update,
+    server_average,
+    step,
+    worker_update,
+)

@@ -1,0 +1,211 @@
+/*
+ * liec_oracle.c -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+ *
+ * A plain, slow, single-threaded CPU statement of one compressed iteration of
+ * LIEC-SGD (Algorithm 1, the ELSE branches) and of the compression operators
+ * it uses (Definition 2 top-k, Definition 4 scaled sign, and the identity
+ * operator that the uncompressed branch of Algorithm 1 amounts to).
+ *
+ * Nothing here is shared with the HIP library: no header, constant, helper or
+ * table is common to both.  Only tests, the smoke check and the bench's CPU
+ * baseline leg may call into this file.
+ *
+ * Build with -O2 -ffp-contract=off and never -ffast-math: every fp32
+ * expression below is meant to be one IEEE-754 operation, exactly as written.
+ *
+ * Readings taken where the paper leaves a choice (each is also listed in the
+ * design notes of the repository):
+ *   - Definition 4: the L1 norm is summed in extended precision (x86 long
+ *     double, 64-bit significand), rounded to fp64, divided by d in fp64 and
+ *     rounded once to fp32.  sign(.) is binary: v >= 0 (including both zeros)
+ *     maps to +1, v < 0 to -1, so that the message really is one bit per
+ *     element and ||C(v)||_1 = d * scale holds without exception.
+ *   - Definition 2: the permutation pi is not unique when magnitudes tie; the
+ *     lower index wins, and exactly k entries are kept even if some are zero.
+ *     Magnitudes are compared through the integer key (bits & 0x7fffffff),
+ *     which orders finite fp32 magnitudes exactly as |.| does.
+ *   - Algorithm 1, server average: the N messages are added in worker order
+ *     in fp32 starting from +0, then one fused multiply-add with 1/N adds the
+ *     global error.
+ *   - Algorithm 1, worker update: the cached local error g - p^i is formed
+ *     first and then added to the broadcast p (the order the prose after the
+ *     algorithm describes), then one fused multiply-add with -eta.
+ *
+ * Parity pins for every function in this file live in tests/test_oracle_*.py.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_IDENTITY = 0, ORACLE_SIGN = 1, ORACLE_TOPK = 2 };
+
+/* What a compressed message consists of besides the per-element part. */
+typedef struct {
+    float scale;          /* scaled sign: ||v||_1 / d                         */
+    double l1;            /* scaled sign: ||v||_1 rounded to fp64              */
+    uint32_t tau_key;     /* top-k: magnitude key of the k-th kept entry       */
+    int64_t cutoff;       /* top-k: index of the k-th kept entry (largest kept
+                             index among entries whose key equals tau_key)    */
+    int64_t count_above;  /* top-k: number of entries with key > tau_key       */
+} oracle_desc;
+
+static uint32_t abs_key(float v)
+{
+    uint32_t u;
+    memcpy(&u, &v, sizeof u);
+    return u & 0x7fffffffu;
+}
+
+/* Definition 4 (scaled sign). p may be NULL when only the scale is wanted. */
+static void compress_sign(const float *v, int64_t d, float *p, oracle_desc *desc)
+{
+    long double sum = 0.0L;
+    for (int64_t j = 0; j < d; ++j)
+        sum += fabsl((long double)v[j]);
+    double l1 = (double)sum;
+    float scale = (float)(l1 / (double)d);
+    if (p)
+        for (int64_t j = 0; j < d; ++j)
+            p[j] = (v[j] < 0.0f) ? -scale : scale;
+    desc->scale = scale;
+    desc->l1 = l1;
+}
+
+static int cmp_u64_desc(const void *a, const void *b)
+{
+    uint64_t x = *(const uint64_t *)a, y = *(const uint64_t *)b;
+    return (x < y) - (x > y);
+}
+
+/* Definition 2 (top-k), ties to the lower index.  Sort every index by
+ * (magnitude key descending, index ascending) and keep the first k. */
+static int compress_topk(const float *v, int64_t d, int64_t k, float *p, oracle_desc *desc)
+{
+    if (k < 1 || k > d || d > (int64_t)0x7fffffff)
+        return 1;
+    uint64_t *order = (uint64_t *)malloc((size_t)d * sizeof *order);
+    if (!order)
+        return 2;
+    for (int64_t j = 0; j < d; ++j)
+        order[j] = ((uint64_t)abs_key(v[j]) << 32) | (uint64_t)(0xffffffffu - (uint32_t)j);
+    qsort(order, (size_t)d, sizeof *order, cmp_u64_desc);
+    if (p) {
+        for (int64_t j = 0; j < d; ++j)
+            p[j] = 0.0f;
+        for (int64_t r = 0; r < k; ++r) {
+            int64_t j = (int64_t)(0xffffffffu - (uint32_t)(order[r] & 0xffffffffu));
+            p[j] = v[j];
+        }
+    }
+    uint32_t tau = (uint32_t)(order[k - 1] >> 32);
+    int64_t above = 0;
+    while (above < k && (uint32_t)(order[above] >> 32) > tau)
+        ++above;
+    desc->tau_key = tau;
+    desc->cutoff = (int64_t)(0xffffffffu - (uint32_t)(order[k - 1] & 0xffffffffu));
+    desc->count_above = above;
+    free(order);
+    return 0;
+}
+
+/* p = C(v) for the chosen operator.  Returns 0 on success. */
+int liec_oracle_compress(int comp, const float *v, int64_t d, int64_t k, float *p,
+                         oracle_desc *desc)
+{
+    oracle_desc local;
+    if (!desc)
+        desc = &local;
+    memset(desc, 0, sizeof *desc);
+    if (!v || d < 1)
+        return 1;
+    switch (comp) {
+    case ORACLE_IDENTITY:
+        if (p)
+            for (int64_t j = 0; j < d; ++j)
+                p[j] = v[j];
+        return 0;
+    case ORACLE_SIGN:
+        compress_sign(v, d, p, desc);
+        return 0;
+    case ORACLE_TOPK:
+        return compress_topk(v, d, k, p, desc);
+    default:
+        return 1;
+    }
+}
+
+/* Algorithm 1, server compensation: v = e + (1/N) sum_i p^i.
+ * P is [N, d] row-major (the N uplink messages, decompressed). */
+void liec_oracle_server_average(const float *P, int32_t N, int64_t d, const float *e, float *v)
+{
+    const float inv_n = 1.0f / (float)N;
+    for (int64_t j = 0; j < d; ++j) {
+        float acc = 0.0f;
+        for (int32_t i = 0; i < N; ++i)
+            acc = acc + P[(size_t)i * (size_t)d + (size_t)j];
+        v[j] = fmaf(acc, inv_n, e[j]);
+    }
+}
+
+/* Algorithm 1, global error update: e_{t+1} = v_t - p_t. */
+void liec_oracle_error_update(const float *v, const float *p, int64_t d, float *e_next)
+{
+    for (int64_t j = 0; j < d; ++j)
+        e_next[j] = v[j] - p[j];
+}
+
+/* Algorithm 1, worker update with local immediate compensation, one worker:
+ * x^i <- x^i - eta * (p + (g_i - p^i)). */
+void liec_oracle_worker_update(const float *g_i, const float *p_i, const float *p, int64_t d,
+                               float lr, float *x_i)
+{
+    for (int64_t j = 0; j < d; ++j) {
+        float local_err = g_i[j] - p_i[j];
+        float u = p[j] + local_err;
+        x_i[j] = fmaf(-lr, u, x_i[j]);
+    }
+}
+
+/* One compressed iteration of Algorithm 1 for all N workers and the server.
+ *   g [N,d] gradients (read only), x [N,d] local models (in/out),
+ *   e [d] global error (in/out).  Optional outputs (may be NULL):
+ *   wdesc [N], sdesc [1], v_out [d] (compensated average), p_out [d] (broadcast),
+ *   P_out [N,d] (uplink messages, decompressed).
+ * Returns 0 on success, 1 on bad arguments, 2 when out of memory. */
+int liec_oracle_step(int32_t N, int64_t d, int worker_comp, int64_t worker_k, int server_comp,
+                     int64_t server_k, float lr, const float *g, float *x, float *e,
+                     oracle_desc *wdesc, oracle_desc *sdesc, float *v_out, float *p_out,
+                     float *P_out)
+{
+    if (N < 1 || d < 1 || !g || !x || !e)
+        return 1;
+    size_t nd = (size_t)N * (size_t)d;
+    float *P = P_out ? P_out : (float *)malloc(nd * sizeof(float));
+    float *v = v_out ? v_out : (float *)malloc((size_t)d * sizeof(float));
+    float *p = p_out ? p_out : (float *)malloc((size_t)d * sizeof(float));
+    int rc = (!P || !v || !p) ? 2 : 0;
+
+    /* worker i: p^i = C(g_i) */
+    for (int32_t i = 0; rc == 0 && i < N; ++i)
+        rc = liec_oracle_compress(worker_comp, g + (size_t)i * (size_t)d, d, worker_k,
+                                  P + (size_t)i * (size_t)d, wdesc ? &wdesc[i] : NULL);
+    if (rc == 0) {
+        /* server: v = e + mean_i p^i ; p = C(v) ; e <- v - p */
+        liec_oracle_server_average(P, N, d, e, v);
+        rc = liec_oracle_compress(server_comp, v, d, server_k, p, sdesc);
+    }
+    if (rc == 0) {
+        liec_oracle_error_update(v, p, d, e);
+        /* worker i: x^i <- x^i - eta (p - p^i + g_i) */
+        for (int32_t i = 0; i < N; ++i)
+            liec_oracle_worker_update(g + (size_t)i * (size_t)d, P + (size_t)i * (size_t)d, p, d,
+                                      lr, x + (size_t)i * (size_t)d);
+    }
+    if (!P_out) free(P);
+    if (!v_out) free(v);
+    if (!p_out) free(p);
+    return rc;
+}
+
+int liec_oracle_desc_size(void) { return (int)sizeof(oracle_desc); }

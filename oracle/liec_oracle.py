@@ -1,0 +1,171 @@
+"""ctypes front end of ``liec_oracle.c``.  TEST INFRASTRUCTURE, NOT THE PRODUCT.
+
+Argument marshalling only: every number comes from the C file, which states
+Algorithm 1 (compressed iteration) and Definitions 2 and 4 of the paper as
+plain single-threaded loops.  Arrays are numpy float32, C-contiguous.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+IDENTITY, SIGN, TOPK = 0, 1, 2
+_NAMES = {"identity": IDENTITY, "sign": SIGN, "topk": TOPK}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "liec_oracle.c")
+_LIB = os.path.join(_HERE, "libliec_oracle.so")
+_lib = None
+
+
+class _CDesc(ctypes.Structure):
+    _fields_ = [
+        ("scale", ctypes.c_float),
+        ("l1", ctypes.c_double),
+        ("tau_key", ctypes.c_uint32),
+        ("cutoff", ctypes.c_int64),
+        ("count_above", ctypes.c_int64),
+    ]
+
+
+@dataclass
+class Desc:
+    """Non-elementwise part of a compressed message."""
+
+    scale: float = 0.0
+    l1: float = 0.0
+    tau_key: int = 0
+    cutoff: int = 0
+    count_above: int = 0
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (strict IEEE: no contraction, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        fp = ctypes.POINTER(ctypes.c_float)
+        dp = ctypes.POINTER(_CDesc)
+        lib.liec_oracle_compress.restype = ctypes.c_int
+        lib.liec_oracle_compress.argtypes = [ctypes.c_int, fp, ctypes.c_int64, ctypes.c_int64, fp, dp]
+        lib.liec_oracle_server_average.restype = None
+        lib.liec_oracle_server_average.argtypes = [fp, ctypes.c_int32, ctypes.c_int64, fp, fp]
+        lib.liec_oracle_error_update.restype = None
+        lib.liec_oracle_error_update.argtypes = [fp, fp, ctypes.c_int64, fp]
+        lib.liec_oracle_worker_update.restype = None
+        lib.liec_oracle_worker_update.argtypes = [fp, fp, fp, ctypes.c_int64, ctypes.c_float, fp]
+        lib.liec_oracle_step.restype = ctypes.c_int
+        lib.liec_oracle_step.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int, ctypes.c_int64,
+                                         ctypes.c_int, ctypes.c_int64, ctypes.c_float, fp, fp, fp,
+                                         dp, dp, fp, fp, fp]
+        lib.liec_oracle_desc_size.restype = ctypes.c_int
+        assert lib.liec_oracle_desc_size() == ctypes.sizeof(_CDesc)
+        _lib = lib
+    return _lib
+
+
+def _comp(c) -> int:
+    return _NAMES[c] if isinstance(c, str) else int(c)
+
+
+def _f32(a: np.ndarray, writable: bool = False) -> np.ndarray:
+    if not (isinstance(a, np.ndarray) and a.dtype == np.float32 and a.flags.c_contiguous):
+        raise TypeError("oracle arrays must be C-contiguous numpy float32")
+    if writable and not a.flags.writeable:
+        raise TypeError("oracle output array is read-only")
+    return a
+
+
+def _ptr(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _desc(c: _CDesc) -> Desc:
+    return Desc(float(c.scale), float(c.l1), int(c.tau_key), int(c.cutoff), int(c.count_above))
+
+
+def compress(comp, v: np.ndarray, k: int = 0, want_p: bool = True) -> Tuple[Optional[np.ndarray], Desc]:
+    """p = C(v) (Definition 2 or 4, or identity) and its descriptor."""
+    lib = _load()
+    v = _f32(v)
+    assert v.ndim == 1
+    p = np.empty_like(v) if want_p else None
+    c = _CDesc()
+    rc = lib.liec_oracle_compress(_comp(comp), _ptr(v), v.shape[0], int(k), _ptr(p), ctypes.byref(c))
+    if rc != 0:
+        raise ValueError(f"liec_oracle_compress failed with code {rc}")
+    return p, _desc(c)
+
+
+def server_average(P: np.ndarray, e: np.ndarray) -> np.ndarray:
+    """v = e + (1/N) sum_i p^i (Algorithm 1, server compensation)."""
+    lib = _load()
+    P, e = _f32(P), _f32(e)
+    N, d = P.shape
+    assert e.shape == (d,)
+    v = np.empty(d, dtype=np.float32)
+    lib.liec_oracle_server_average(_ptr(P), N, d, _ptr(e), _ptr(v))
+    return v
+
+
+def error_update(v: np.ndarray, p: np.ndarray) -> np.ndarray:
+    """e_{t+1} = v_t - p_t (Algorithm 1, global error update)."""
+    lib = _load()
+    v, p = _f32(v), _f32(p)
+    out = np.empty_like(v)
+    lib.liec_oracle_error_update(_ptr(v), _ptr(p), v.shape[0], _ptr(out))
+    return out
+
+
+def worker_update(g_i: np.ndarray, p_i: np.ndarray, p: np.ndarray, lr: float, x_i: np.ndarray) -> None:
+    """x^i <- x^i - eta (p + (g_i - p^i)), in place (Algorithm 1, worker update)."""
+    lib = _load()
+    g_i, p_i, p, x_i = _f32(g_i), _f32(p_i), _f32(p), _f32(x_i, True)
+    d = g_i.shape[0]
+    assert p_i.shape == (d,) and p.shape == (d,) and x_i.shape == (d,)
+    lib.liec_oracle_worker_update(_ptr(g_i), _ptr(p_i), _ptr(p), d, ctypes.c_float(lr), _ptr(x_i))
+
+
+@dataclass
+class StepTrace:
+    worker: List[Desc]
+    server: Desc
+    v: Optional[np.ndarray]
+    p: Optional[np.ndarray]
+    P: Optional[np.ndarray]
+
+
+def step(g: np.ndarray, x: np.ndarray, e: np.ndarray, worker_comp, server_comp, lr: float,
+         worker_k: int = 0, server_k: int = 0, trace: bool = False) -> StepTrace:
+    """One compressed iteration of Algorithm 1; x [N,d] and e [d] are updated in place."""
+    lib = _load()
+    g, x, e = _f32(g), _f32(x, True), _f32(e, True)
+    N, d = g.shape
+    assert x.shape == (N, d) and e.shape == (d,)
+    wd = (_CDesc * N)()
+    sd = _CDesc()
+    v = np.empty(d, dtype=np.float32) if trace else None
+    p = np.empty(d, dtype=np.float32) if trace else None
+    P = np.empty((N, d), dtype=np.float32) if trace else None
+    rc = lib.liec_oracle_step(N, d, _comp(worker_comp), int(worker_k), _comp(server_comp), int(server_k),
+                              ctypes.c_float(lr), _ptr(g), _ptr(x), _ptr(e), wd, ctypes.byref(sd),
+                              _ptr(v), _ptr(p), _ptr(P))
+    if rc != 0:
+        raise ValueError(f"liec_oracle_step failed with code {rc}")
+    return StepTrace([_desc(c) for c in wd], _desc(sd), v, p, P)

@@ -1,0 +1,6 @@
+"""Seeded synthetic inputs (layer-size tables and gradient generators).
+
+Shared by the tests of the HIP path and of the CPU oracle; contains no part of
+the method itself.
+"""
+from .gradients import GradientSource, Workload, inject_ties, scaled, workloads  # noqa: F401
