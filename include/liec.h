@@ -1,0 +1,159 @@
+/*
+ * liec.h -- C ABI of the MI355X (gfx950) implementation of one compressed
+ * iteration of LIEC-SGD (Algorithm 1 of the paper, the branches taken when the
+ * iteration is not an averaging iteration), with N simulated workers batched
+ * as the rows of an [N, d] fp32 tensor on one GPU.
+ *
+ * Per call of liec_step, for worker i = 0..N-1 and column j = 0..d-1:
+ *   p^i  = C_w(g_i)                           worker compression (Alg. 1, worker part)
+ *   v    = e + (1/N) sum_i p^i                server compensation
+ *   p    = C_s(v)                             server compression, broadcast
+ *   e   <- v - p                              global error update
+ *   x^i <- x^i - lr * (p + (g_i - p^i))       local immediate error compensation
+ * C_w / C_s are the scaled-sign operator (Definition 4), top-k (Definition 2)
+ * or the identity.  Conventions the definitions leave open:
+ *   - scaled sign: scale = fp32(sum_j |v_j| / d) with the sum carried in fp64;
+ *     sign is binary, v >= 0 (both zeros included) -> +scale, v < 0 -> -scale;
+ *   - top-k: magnitudes compare through the integer key (bits & 0x7fffffff);
+ *     among equal keys the lower index wins; exactly k entries are kept;
+ *   - the N messages are added in worker order in fp32, then one fused
+ *     multiply-add by 1/N adds e; the update is one fused multiply-add by -lr.
+ *
+ * All tensor arguments are DEVICE pointers to fp32, contiguous, row-major and
+ * owned by the caller; nothing here takes or returns torch types.  The library
+ * owns only scratch memory (allocated by liec_create*, released by
+ * liec_destroy).  No entry point throws; every failure is a status code.
+ * A context serves one caller thread at a time.
+ */
+#ifndef LIEC_H
+#define LIEC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct liec_ctx liec_ctx; /* opaque */
+
+typedef enum {
+    LIEC_OK = 0,
+    LIEC_EINVAL = 1,     /* bad argument (null pointer, size, k, lr, overlap)   */
+    LIEC_ENOMEM = 2,     /* host or device allocation failed                    */
+    LIEC_EDEVICE = 3,    /* a HIP call failed; sticky until liec_destroy        */
+    LIEC_ENONFINITE = 4  /* liec_get_info only: last step saw a NaN or Inf      */
+} liec_status;
+
+typedef enum {
+    LIEC_COMP_IDENTITY = 0, /* C(v) = v; with it on both sides the step is P-SGD */
+    LIEC_COMP_SIGN = 1,     /* Definition 4 */
+    LIEC_COMP_TOPK = 2      /* Definition 2 */
+} liec_comp;
+
+/* Scalars describing the LAST completed step (filled by liec_get_info). */
+typedef struct {
+    int32_t N;
+    int64_t d;
+    int32_t worker_comp, server_comp;
+    int64_t worker_k, server_k;
+    float lr;
+    int64_t steps_done;
+    float server_scale;       /* scaled sign on the server: ||v||_1 / d            */
+    double server_l1;         /* scaled sign on the server: ||v||_1 (fp64 sum)     */
+    uint32_t server_tau_key;  /* top-k on the server: magnitude key of k-th entry  */
+    int64_t server_cutoff;    /* top-k on the server: largest kept index among
+                                 entries whose key equals server_tau_key           */
+    int32_t nonfinite;        /* 1 if a NaN/Inf reached an L1 sum or a top-k key   */
+} liec_info;
+
+/*
+ * liec_create: same operator C and same k on the worker and the server side
+ * (the form Algorithm 1 is written in), launching on the default (null) stream.
+ *   out         receives the context (host pointer to a host pointer)
+ *   N >= 1      number of simulated workers (rows)
+ *   1 <= d < 2^31 - 2^20   model dimension (columns)
+ *   k           kept entries for LIEC_COMP_TOPK, 1 <= k <= d; ignored otherwise
+ *   lr          learning rate eta, finite
+ * Allocates O(N * d / 8 + d) bytes of device scratch.  Uses the current HIP device.
+ */
+liec_status liec_create(liec_ctx **out, int32_t N, int64_t d, liec_comp compressor, int64_t k,
+                        float lr);
+
+/*
+ * liec_create_ex: different operators / k on the two sides, and the HIP stream
+ * (a hipStream_t passed as void*, NULL = null stream) all work is enqueued on.
+ * The stream must outlive the context.
+ */
+liec_status liec_create_ex(liec_ctx **out, int32_t N, int64_t d, liec_comp worker_comp,
+                           int64_t worker_k, liec_comp server_comp, int64_t server_k, float lr,
+                           void *hip_stream);
+
+/*
+ * liec_step: one compressed iteration of Algorithm 1 as stated at the top.
+ *   grads      [N, d] device, read only   stochastic gradients g_i of this iteration
+ *   x          [N, d] device, in/out      local models x^i (they differ between workers)
+ *   server_err [d]    device, in/out      global error e_t on entry, e_{t+1} on return
+ * The three buffers must not overlap.  Any alignment is accepted; rows that are
+ * 16-byte aligned (base pointers 16-byte aligned and d % 4 == 0) take the
+ * 128-bit load path, anything else a slower element-wise path.
+ * Asynchronous: work is enqueued on the context's stream and the call returns
+ * without synchronising, allocating or copying to the host.  Inputs must be
+ * finite; otherwise results are unspecified and liec_get_info reports it.
+ */
+liec_status liec_step(liec_ctx *ctx, const float *grads, float *x, float *server_err);
+
+/* Learning-rate schedules (the paper decays eta during training): takes effect
+ * from the next liec_step. */
+liec_status liec_set_lr(liec_ctx *ctx, float lr);
+
+/* Synchronises the stream and copies the scalars of the last step to the host
+ * struct `info`.  Returns LIEC_ENONFINITE (with `info` filled) if that step met
+ * a NaN or Inf. */
+liec_status liec_get_info(liec_ctx *ctx, liec_info *info);
+
+/*
+ * Synchronises the stream and copies the per-worker message descriptors of the
+ * last step into HOST arrays of length N; any pointer may be NULL.
+ *   scales  scaled sign: ||g_i||_1 / d
+ *   l1      scaled sign: ||g_i||_1 as summed in fp64
+ *   tau     top-k: magnitude key of the k-th kept entry of g_i
+ *   cutoff  top-k: largest kept index among entries of g_i whose key equals tau
+ * Arrays that do not apply to the worker operator are zero-filled.
+ */
+liec_status liec_get_worker_desc(liec_ctx *ctx, float *scales, double *l1, uint32_t *tau,
+                                 int64_t *cutoff);
+
+/*
+ * Per-kernel timing with HIP events on the context's stream, for measurement.
+ * liec_profile_begin(ctx, max_steps) makes every following liec_step record an
+ * event before and after each kernel it launches (at most max_steps steps are
+ * recorded, later ones run unrecorded).  liec_profile_end synchronises, stops
+ * recording and fills HOST arrays: names[s] (static strings), total_ms[s] and
+ * launches[s] for s < *n_slots (in: capacity of the arrays, out: slots used).
+ */
+liec_status liec_profile_begin(liec_ctx *ctx, int32_t max_steps);
+liec_status liec_profile_end(liec_ctx *ctx, int32_t *n_slots, const char **names, double *total_ms,
+                             int64_t *launches);
+
+/* Releases the scratch memory and the context.  NULL is accepted. */
+void liec_destroy(liec_ctx *ctx);
+
+/* Static description of a status code. */
+const char *liec_status_string(liec_status s);
+
+/* Bytes of device scratch the context holds. */
+int64_t liec_scratch_bytes(const liec_ctx *ctx);
+
+/*
+ * Measurement aid, not part of the method: a plain 128-bit device-to-device
+ * copy kernel enqueued on `hip_stream` (hipStream_t as void*, NULL = null
+ * stream).  dst and src are DEVICE pointers, 16-byte aligned, non-overlapping;
+ * bytes must be a multiple of 16.  It gives the achievable streaming bandwidth
+ * to quote next to the step's kernels and calibrates hardware byte counters.
+ */
+liec_status liec_device_copy(void *dst, const void *src, int64_t bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIEC_H */

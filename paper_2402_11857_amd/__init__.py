@@ -1,0 +1,24 @@
+"""MI355X-native LIEC-SGD compressed step: thin Python binding over the C-ABI HIP library.
+
+The binding marshals arguments only; every step of the method runs in the HIP
+kernels of ``libliec.so``.  There is no CPU fallback: if the library is missing
+the first use raises.
+"""
+from .binding import (  # noqa: F401
+    COMP_IDENTITY,
+    COMP_SIGN,
+    COMP_TOPK,
+    LiecContext,
+    LiecError,
+    LiecInfo,
+    device_copy,
+    lib,
+    library_path,
+    liec_create,
+    liec_create_ex,
+    liec_destroy,
+    liec_get_info,
+    liec_get_worker_desc,
+    liec_set_lr,
+    liec_step,
+)

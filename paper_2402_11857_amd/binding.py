@@ -1,0 +1,221 @@
+"""ctypes binding of include/liec.h (same names, argument marshalling only).
+
+torch is imported before the library is loaded so that the HIP runtime torch
+ships is the one both sides share; tensors are passed as raw device pointers.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional, Tuple
+
+import torch
+
+COMP_IDENTITY, COMP_SIGN, COMP_TOPK = 0, 1, 2
+_COMP_NAMES = {"identity": COMP_IDENTITY, "sign": COMP_SIGN, "topk": COMP_TOPK}
+OK, EINVAL, ENOMEM, EDEVICE, ENONFINITE = 0, 1, 2, 3, 4
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libliec.so")
+_lib = None
+
+
+class LiecError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().liec_status_string(status).decode() if _lib is not None else str(status)
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+class LiecInfo(ctypes.Structure):
+    _fields_ = [
+        ("N", ctypes.c_int32),
+        ("d", ctypes.c_int64),
+        ("worker_comp", ctypes.c_int32),
+        ("server_comp", ctypes.c_int32),
+        ("worker_k", ctypes.c_int64),
+        ("server_k", ctypes.c_int64),
+        ("lr", ctypes.c_float),
+        ("steps_done", ctypes.c_int64),
+        ("server_scale", ctypes.c_float),
+        ("server_l1", ctypes.c_double),
+        ("server_tau_key", ctypes.c_uint32),
+        ("server_cutoff", ctypes.c_int64),
+        ("nonfinite", ctypes.c_int32),
+    ]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """Loads libliec.so (built by ``__graft_entry__.build()``); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                f"{_LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`. "
+                "There is no fallback path.")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+        L.liec_create.restype = ctypes.c_int
+        L.liec_create.argtypes = [ctypes.POINTER(vp), i32, i64, ctypes.c_int, i64, f32]
+        L.liec_create_ex.restype = ctypes.c_int
+        L.liec_create_ex.argtypes = [ctypes.POINTER(vp), i32, i64, ctypes.c_int, i64, ctypes.c_int, i64, f32, vp]
+        L.liec_step.restype = ctypes.c_int
+        L.liec_step.argtypes = [vp, vp, vp, vp]
+        L.liec_set_lr.restype = ctypes.c_int
+        L.liec_set_lr.argtypes = [vp, f32]
+        L.liec_get_info.restype = ctypes.c_int
+        L.liec_get_info.argtypes = [vp, ctypes.POINTER(LiecInfo)]
+        L.liec_get_worker_desc.restype = ctypes.c_int
+        L.liec_get_worker_desc.argtypes = [vp, ctypes.POINTER(f32), ctypes.POINTER(ctypes.c_double),
+                                           ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(i64)]
+        L.liec_profile_begin.restype = ctypes.c_int
+        L.liec_profile_begin.argtypes = [vp, i32]
+        L.liec_profile_end.restype = ctypes.c_int
+        L.liec_profile_end.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_char_p),
+                                       ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+        L.liec_destroy.restype = None
+        L.liec_destroy.argtypes = [vp]
+        L.liec_status_string.restype = ctypes.c_char_p
+        L.liec_status_string.argtypes = [ctypes.c_int]
+        L.liec_scratch_bytes.restype = i64
+        L.liec_scratch_bytes.argtypes = [vp]
+        L.liec_device_copy.restype = ctypes.c_int
+        L.liec_device_copy.argtypes = [vp, vp, i64, vp]
+        _lib = L
+    return _lib
+
+
+def _comp(c) -> int:
+    return _COMP_NAMES[c] if isinstance(c, str) else int(c)
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise LiecError(status, where)
+
+
+def _dev_ptr(t: torch.Tensor, shape: Tuple[int, ...], name: str) -> int:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous float32 tensor on the GPU")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return t.data_ptr()
+
+
+# ---- the C entry points, one to one -----------------------------------------------------------
+def liec_create(N: int, d: int, compressor, k: int, lr: float) -> int:
+    h = ctypes.c_void_p()
+    _check(lib().liec_create(ctypes.byref(h), N, d, _comp(compressor), int(k), lr), "liec_create")
+    return h.value
+
+
+def liec_create_ex(N: int, d: int, worker_comp, worker_k: int, server_comp, server_k: int, lr: float,
+                   stream: Optional[int] = None) -> int:
+    h = ctypes.c_void_p()
+    _check(lib().liec_create_ex(ctypes.byref(h), N, d, _comp(worker_comp), int(worker_k), _comp(server_comp),
+                                int(server_k), lr, stream), "liec_create_ex")
+    return h.value
+
+
+def liec_step(ctx: int, grads_ptr: int, x_ptr: int, server_err_ptr: int) -> None:
+    _check(lib().liec_step(ctx, grads_ptr, x_ptr, server_err_ptr), "liec_step")
+
+
+def liec_set_lr(ctx: int, lr: float) -> None:
+    _check(lib().liec_set_lr(ctx, lr), "liec_set_lr")
+
+
+def liec_get_info(ctx: int) -> Tuple[LiecInfo, int]:
+    info = LiecInfo()
+    st = lib().liec_get_info(ctx, ctypes.byref(info))
+    if st not in (OK, ENONFINITE):
+        raise LiecError(st, "liec_get_info")
+    return info, st
+
+
+def liec_get_worker_desc(ctx: int, N: int) -> Dict[str, list]:
+    sc = (ctypes.c_float * N)()
+    l1 = (ctypes.c_double * N)()
+    tau = (ctypes.c_uint32 * N)()
+    cut = (ctypes.c_int64 * N)()
+    _check(lib().liec_get_worker_desc(ctx, sc, l1, tau, cut), "liec_get_worker_desc")
+    return {"scale": list(sc), "l1": list(l1), "tau_key": list(tau), "cutoff": list(cut)}
+
+
+def liec_destroy(ctx: Optional[int]) -> None:
+    if ctx:
+        lib().liec_destroy(ctx)
+
+
+def device_copy(dst: torch.Tensor, src: torch.Tensor, stream: Optional[int] = None) -> None:
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes and dst.is_cuda and src.is_cuda
+    _check(lib().liec_device_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream), "liec_device_copy")
+
+
+# ---- convenience wrapper: owns the handle, checks tensor shapes, nothing else ----------------
+class LiecContext:
+    """One LIEC-SGD context bound to torch's current stream (or the one given)."""
+
+    def __init__(self, N: int, d: int, worker_comp, server_comp=None, worker_k: int = 0, server_k: int = 0,
+                 lr: float = 0.1, stream: Optional[torch.cuda.Stream] = None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("LiecContext needs a GPU; there is no CPU path")
+        server_comp = worker_comp if server_comp is None else server_comp
+        self.N, self.d = int(N), int(d)
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        self._h = None
+        self._h = liec_create_ex(self.N, self.d, worker_comp, worker_k, server_comp, server_k, lr,
+                                 self.stream.cuda_stream)
+
+    def step(self, grads: torch.Tensor, x: torch.Tensor, server_err: torch.Tensor) -> None:
+        liec_step(self._h, _dev_ptr(grads, (self.N, self.d), "grads"), _dev_ptr(x, (self.N, self.d), "x"),
+                  _dev_ptr(server_err, (self.d,), "server_err"))
+
+    def set_lr(self, lr: float) -> None:
+        liec_set_lr(self._h, lr)
+
+    def info(self) -> LiecInfo:
+        return liec_get_info(self._h)[0]
+
+    def info_status(self) -> Tuple[LiecInfo, int]:
+        return liec_get_info(self._h)
+
+    def worker_desc(self) -> Dict[str, list]:
+        return liec_get_worker_desc(self._h, self.N)
+
+    def scratch_bytes(self) -> int:
+        return int(lib().liec_scratch_bytes(self._h))
+
+    def profile_begin(self, max_steps: int) -> None:
+        _check(lib().liec_profile_begin(self._h, max_steps), "liec_profile_begin")
+
+    def profile_end(self) -> Dict[str, Tuple[float, int]]:
+        cap = 32
+        n = ctypes.c_int32(cap)
+        names = (ctypes.c_char_p * cap)()
+        ms = (ctypes.c_double * cap)()
+        cnt = (ctypes.c_int64 * cap)()
+        _check(lib().liec_profile_end(self._h, ctypes.byref(n), names, ms, cnt), "liec_profile_end")
+        return {names[i].decode(): (ms[i], cnt[i]) for i in range(n.value)}
+
+    def close(self) -> None:
+        if self._h:
+            liec_destroy(self._h)
+            self._h = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

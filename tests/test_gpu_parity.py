@@ -1,0 +1,308 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI (via the thin binding).
+
+Integer-valued results (top-k index sets, sign bits, thresholds, cut-offs) must be bit-exact;
+fp32 state (x, server error, scales) must agree within 1e-5 relative after one step and 1e-4
+after a chain.  With the conventions both sides follow the expected outcome is bit identity.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+sys.path.insert(0, os.path.dirname(__file__))
+import _harness as H  # noqa: E402
+
+import workloads  # noqa: E402
+
+pytestmark = [pytest.mark.gpu,
+              pytest.mark.skipif(not torch.cuda.is_available(), reason="needs an MI355X")]
+
+DEV = "cuda:0"
+WL = workloads.workloads()
+
+
+def _ctx(w, **kw):
+    from paper_2402_11857_amd import LiecContext
+
+    return LiecContext(w.N, w.d, w.worker_comp, w.server_comp, w.worker_k, w.server_k, w.lr, **kw)
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _check_descs(ctx, w, wdesc, sdesc, g_host, v_host, label):
+    """Scales, thresholds and cut-offs of the last step against the oracle's."""
+    got = ctx.worker_desc()
+    info = ctx.info()
+    if w.worker_comp == "sign":
+        for i in range(w.N):
+            assert got["scale"][i] == np.float32(wdesc[i].scale), f"{label}: worker {i} scale"
+            assert abs(got["l1"][i] - wdesc[i].l1) <= 1e-12 * wdesc[i].l1
+    if w.worker_comp == "topk":
+        for i in range(w.N):
+            assert got["tau_key"][i] == wdesc[i].tau_key, f"{label}: worker {i} threshold key"
+            assert got["cutoff"][i] == wdesc[i].cutoff, f"{label}: worker {i} tie cut-off"
+    if w.server_comp == "sign":
+        assert info.server_scale == np.float32(sdesc.scale), f"{label}: server scale"
+    if w.server_comp == "topk":
+        assert info.server_tau_key == sdesc.tau_key, f"{label}: server threshold key"
+        assert info.server_cutoff == sdesc.cutoff, f"{label}: server tie cut-off"
+    assert info.nonfinite == 0
+
+
+def _run_chain(w, steps, seed=0, teacher_forced=False, mutate=None, check_descs=True, tol_end=H.TOL_CHAIN):
+    """Runs `steps` chained steps on both sides and compares after every step."""
+    src = workloads.GradientSource(w, seed=seed, device=DEV)
+    x = torch.zeros((w.N, w.d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    xo = np.zeros((w.N, w.d), dtype=np.float32)
+    eo = np.zeros(w.d, dtype=np.float32)
+    exact = True
+    with _ctx(w) as ctx:
+        for t in range(steps):
+            g = src.grads(t)
+            if mutate is not None:
+                g = mutate(g, t)
+            gh = g.cpu().numpy()
+            if teacher_forced and t > 0:
+                x.copy_(torch.from_numpy(xo))
+                e.copy_(torch.from_numpy(eo))
+            ctx.step(g, x, e)
+            wdesc, sdesc, v, p, P = H.oracle_step_rows(gh, xo, eo, w.worker_comp, w.server_comp, w.lr,
+                                                       w.worker_k, w.server_k)
+            xg, eg = x.cpu().numpy(), e.cpu().numpy()
+            label = f"{w.name} N={w.N} d={w.d} step {t}"
+            if check_descs:
+                _check_descs(ctx, w, wdesc, sdesc, gh, v, label)
+            tol = H.TOL_STEP if (t == 0 or teacher_forced) else tol_end
+            assert H.rel_err(eg, eo) <= tol, f"{label}: server error"
+            assert H.rel_err(xg, xo) <= tol, f"{label}: models"
+            # integer-valued parts of the state: the sign pattern / support of the new error
+            if w.server_comp == "topk":
+                assert np.array_equal(eg == 0, eo == 0), f"{label}: server index set"
+            exact = exact and H.bit_equal(xg, xo) and H.bit_equal(eg, eo)
+    return exact
+
+
+SMALL_SHAPES = [(1, 1), (2, 3), (3, 255), (4, 1024), (2, 1025), (5, 4100), (3, 50_003), (8, 70_000)]
+PAIRS = [("sign", "sign"), ("topk", "topk"), ("topk", "sign"), ("sign", "topk"), ("identity", "identity"),
+         ("identity", "sign"), ("topk", "identity"), ("sign", "identity"), ("identity", "topk")]
+
+
+@pytest.mark.parametrize("wc,sc", PAIRS)
+@pytest.mark.parametrize("N,d", SMALL_SHAPES)
+def test_small_shapes_all_operator_pairs(N, d, wc, sc):
+    _say(f"case small N={N} d={d} {wc}/{sc}")
+    base = WL["c2_topk_mid"]
+    k = max(1, d // 50)
+    w = workloads.scaled(base, N=N, d=d, worker_comp=wc, server_comp=sc,
+                         worker_k=k if wc == "topk" else 0, server_k=max(1, d // 20) if sc == "topk" else 0,
+                         lr=0.05)
+    assert _run_chain(w, steps=3, seed=N * 1000 + d), "expected bit identity with the oracle"
+
+
+@pytest.mark.parametrize("wc,sc", [("topk", "topk"), ("topk", "sign"), ("sign", "topk")])
+def test_ties_zeros_and_negative_zeros(wc, sc):
+    _say(f"case ties {wc}/{sc}")
+    base = WL["c2_topk_mid"]
+    w = workloads.scaled(base, N=4, d=33_000, worker_comp=wc, server_comp=sc,
+                         worker_k=3000 if wc == "topk" else 0, server_k=5000 if sc == "topk" else 0)
+
+    def mutate(g, t):
+        return workloads.inject_ties(g, seed=t, frac_zero=0.3, frac_dup=0.5)
+
+    assert _run_chain(w, steps=4, seed=5, mutate=mutate)
+
+
+@pytest.mark.parametrize("kind", ["all_zero", "all_equal", "one_hot", "k_equals_d", "k_equals_1"])
+def test_degenerate_topk_inputs(kind):
+    _say(f"case degenerate {kind}")
+    base = WL["c2_topk_mid"]
+    d = 5000
+    k = {"k_equals_d": d, "k_equals_1": 1}.get(kind, 100)
+    w = workloads.scaled(base, N=3, d=d, worker_comp="topk", server_comp="topk", worker_k=k, server_k=k)
+
+    def mutate(g, t):
+        if kind == "all_zero":
+            g.zero_()
+        elif kind == "all_equal":
+            g.fill_(0.125)
+            g[:, ::3] *= -1
+        elif kind == "one_hot":
+            g.zero_()
+            g[:, 4321] = -7.0
+        return g
+
+    assert _run_chain(w, steps=3, seed=1, mutate=mutate)
+
+
+def test_sign_with_zero_gradient_rows():
+    _say("case sign zero rows")
+    w = workloads.scaled(WL["c1_tiny_sign"], N=3, d=2048)
+
+    def mutate(g, t):
+        g[1].zero_()
+        g[2, ::2] = -0.0
+        return g
+
+    assert _run_chain(w, steps=3, seed=2, mutate=mutate)
+
+
+def test_c1_tiny_full_chain():
+    w = WL["c1_tiny_sign"]
+    _say(f"case {w.name} {w.steps} chained steps")
+    assert _run_chain(w, steps=w.steps, seed=0)
+
+
+def test_c2_topk_mid_full_chain():
+    w = WL["c2_topk_mid"]
+    _say(f"case {w.name} {w.steps} chained steps")
+    assert _run_chain(w, steps=w.steps, seed=0)
+
+
+def test_c2_teacher_forced():
+    w = WL["c2_topk_mid"]
+    _say(f"case {w.name} teacher forced")
+    _run_chain(w, steps=5, seed=3, teacher_forced=True)
+
+
+def test_unaligned_pointers_take_the_elementwise_path():
+    _say("case unaligned pointers")
+    from paper_2402_11857_amd import LiecContext
+
+    N, d = 3, 6000
+    w = workloads.scaled(WL["c2_topk_mid"], N=N, d=d, worker_comp="topk", server_comp="sign", worker_k=77)
+    src = workloads.GradientSource(w, seed=9, device=DEV)
+    g = src.grads(0)
+    pad = torch.zeros(N * d + 1, dtype=torch.float32, device=DEV)
+    x = pad[1:].view(N, d)              # 4-byte aligned only
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    xo, eo = np.zeros((N, d), dtype=np.float32), np.zeros(d, dtype=np.float32)
+    with LiecContext(N, d, "topk", "sign", 77, 0, 0.1) as ctx:
+        for t in range(2):
+            g = src.grads(t)
+            ctx.step(g, x, e)
+            H.oracle_step_rows(g.cpu().numpy(), xo, eo, "topk", "sign", 0.1, 77, 0)
+    assert H.bit_equal(x.cpu().numpy(), xo) and H.bit_equal(e.cpu().numpy(), eo)
+
+
+def test_runs_are_bit_reproducible_and_resumable():
+    _say("case determinism / resume")
+    w = workloads.scaled(WL["c2_topk_mid"], N=4, d=300_000, worker_comp="topk", server_comp="sign", worker_k=3000)
+    src = workloads.GradientSource(w, seed=4, device=DEV)
+    gs = [src.grads(t) for t in range(6)]
+
+    def run(split):
+        x = torch.zeros((w.N, w.d), dtype=torch.float32, device=DEV)
+        e = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+        ctx = _ctx(w)
+        for t, g in enumerate(gs):
+            if t == split:          # all algorithm state lives in x and e: a new context resumes
+                ctx.close()
+                ctx = _ctx(w)
+            ctx.step(g, x, e)
+        torch.cuda.synchronize()
+        ctx.close()
+        return x.cpu().numpy(), e.cpu().numpy()
+
+    a, b, c = run(None), run(None), run(3)
+    assert H.bit_equal(a[0], b[0]) and H.bit_equal(a[1], b[1])
+    assert H.bit_equal(a[0], c[0]) and H.bit_equal(a[1], c[1])
+
+
+def test_non_default_stream_and_lr_schedule():
+    _say("case stream / set_lr")
+    w = workloads.scaled(WL["c1_tiny_sign"], N=4, d=40_000)
+    src = workloads.GradientSource(w, seed=6, device=DEV)
+    s = torch.cuda.Stream()
+    x = torch.zeros((w.N, w.d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    xo, eo = np.zeros((w.N, w.d), dtype=np.float32), np.zeros(w.d, dtype=np.float32)
+    gs = [src.grads(t) for t in range(4)]
+    torch.cuda.synchronize()
+    with _ctx(w, stream=s) as ctx:
+        for t, g in enumerate(gs):
+            lr = 0.1 / (1 + t)
+            ctx.set_lr(lr)
+            ctx.step(g, x, e)
+            H.oracle_step_rows(g.cpu().numpy(), xo, eo, "sign", "sign", lr)
+        s.synchronize()
+    assert H.bit_equal(x.cpu().numpy(), xo) and H.bit_equal(e.cpu().numpy(), eo)
+
+
+def test_step_rejects_bad_buffers_and_reports_nonfinite_input():
+    _say("case errors")
+    from paper_2402_11857_amd import LiecContext, LiecError, liec_step
+
+    N, d = 2, 4096
+    g = torch.randn((N, d), device=DEV)
+    x = torch.zeros((N, d), device=DEV)
+    e = torch.zeros(d, device=DEV)
+    with LiecContext(N, d, "sign", "topk", 0, 10, 0.1) as ctx:
+        with pytest.raises(LiecError):
+            liec_step(ctx._h, g.data_ptr(), g.data_ptr(), e.data_ptr())      # x overlaps grads
+        with pytest.raises(LiecError):
+            liec_step(ctx._h, g.data_ptr(), x.data_ptr(), x.data_ptr())      # e overlaps x
+        with pytest.raises(LiecError):
+            liec_step(ctx._h, g.data_ptr(), None, e.data_ptr())
+        with pytest.raises((TypeError, ValueError)):
+            ctx.step(g[:, :100], x, e)
+        ctx.step(g, x, e)
+        assert ctx.info_status()[1] == 0
+        g[1, 17] = float("inf")
+        ctx.step(g, x, e)
+        info, st = ctx.info_status()
+        assert st == 4 and info.nonfinite == 1
+    with LiecContext(N, d, "topk", "sign", 10, 0, 0.1) as ctx:
+        x.zero_(), e.zero_()
+        g[1, 17] = float("nan")
+        ctx.step(g, x, e)
+        assert ctx.info_status()[1] == 4
+
+
+# ---- full-size configurations, in the launch configuration the bench times -------------------
+def _full_size_steps(name, steps, seed=0):
+    w = WL[name]
+    _say(f"case full size {name} N={w.N} d={w.d} steps={steps}")
+    src = workloads.GradientSource(w, seed=seed, device=DEV)
+    x = torch.zeros((w.N, w.d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    xo = np.zeros((w.N, w.d), dtype=np.float32)
+    eo = np.zeros(w.d, dtype=np.float32)
+    with _ctx(w) as ctx:
+        for t in range(steps):
+            g = src.grads(t)
+            ctx.step(g, x, e)
+            gh = g.cpu().numpy()
+            del g
+            wdesc, sdesc, v, p, P = H.oracle_step_rows(gh, xo, eo, w.worker_comp, w.server_comp, w.lr,
+                                                       w.worker_k, w.server_k)
+            _say(f"  oracle step {t} done")
+            _check_descs(ctx, w, wdesc, sdesc, gh, v, f"{name} step {t}")
+            del P, gh
+            eg = e.cpu().numpy()
+            assert H.rel_err(eg, eo) <= (H.TOL_STEP if t == 0 else H.TOL_CHAIN)
+            assert H.bit_equal(eg, eo), f"{name} step {t}: server error not bit-identical"
+            for i in range(w.N):     # row at a time keeps the host copies small
+                xi = x[i].cpu().numpy()
+                assert H.rel_err(xi, xo[i]) <= (H.TOL_STEP if t == 0 else H.TOL_CHAIN), f"{name} step {t} row {i}"
+                assert H.bit_equal(xi, xo[i]), f"{name} step {t} row {i}: model not bit-identical"
+
+
+def test_full_size_c3_resnet18_sign():
+    _full_size_steps("c3_resnet18_sign", steps=3)
+
+
+def test_full_size_c4_resnet50_topk():
+    _full_size_steps("c4_resnet50_topk", steps=2)
+
+
+def test_full_size_c5_vgg16_mixed():
+    _full_size_steps("c5_vgg16_mixed", steps=1)
+
+
+def test_full_size_c5_vgg16_sign():
+    _full_size_steps("c5_vgg16_sign", steps=2)

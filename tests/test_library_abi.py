@@ -1,0 +1,87 @@
+"""The C-ABI library loads and exports every symbol include/liec.h declares; argument checks
+that need no GPU return the documented status codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "liec.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(liec_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2402_11857_amd as pkg
+
+    if not os.path.exists(pkg.library_path()):
+        from paper_2402_11857_amd import _build
+
+        _build.build_library()
+    return pkg.lib()
+
+
+def test_header_declares_the_north_star_calls():
+    names = _declared_functions()
+    for required in ("liec_create", "liec_step", "liec_destroy"):
+        assert required in names
+
+
+def test_every_declared_symbol_is_exported(lib):
+    for name in _declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in liec.h but not exported"
+
+
+def test_status_strings(lib):
+    assert lib.liec_status_string(0) == b"ok"
+    assert b"invalid" in lib.liec_status_string(1)
+
+
+@pytest.mark.parametrize("args", [
+    (0, 16, 1, 0, 0.1),          # N < 1
+    (2, 0, 1, 0, 0.1),           # d < 1
+    (2, 1 << 31, 1, 0, 0.1),     # d too large
+    (2, 16, 7, 0, 0.1),          # unknown operator
+    (2, 16, 2, 0, 0.1),          # top-k with k = 0
+    (2, 16, 2, 17, 0.1),         # top-k with k > d
+    (2, 16, 1, 0, float("nan")), # lr not finite
+])
+def test_create_rejects_bad_arguments_before_touching_the_device(lib, args):
+    h = ctypes.c_void_p()
+    N, d, comp, k, lr = args
+    assert lib.liec_create(ctypes.byref(h), N, d, comp, k, lr) == 1
+    assert not h.value
+
+
+def test_null_handles_are_rejected_or_ignored(lib):
+    assert lib.liec_step(None, None, None, None) == 1
+    assert lib.liec_set_lr(None, 0.1) == 1
+    assert lib.liec_scratch_bytes(None) == 0
+    lib.liec_destroy(None)
+    assert lib.liec_create(None, 1, 1, 0, 0, 0.1) == 1
+
+
+def test_binding_refuses_to_run_without_a_gpu():
+    import torch
+
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    from paper_2402_11857_amd import LiecContext
+
+    with pytest.raises(RuntimeError):
+        LiecContext(2, 16, "sign")
+
+
+def test_product_never_imports_the_oracle():
+    pkg_dir = os.path.join(ROOT, "paper_2402_11857_amd")
+    for base, _, files in os.walk(pkg_dir):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                src = open(os.path.join(base, f)).read()
+                assert "oracle" not in src.lower(), f"{f} mentions the oracle"
