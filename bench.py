@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Throughput of the LIEC-SGD compressed step on one MI355X.
+
+A "step" is one pass of the whole hot path (worker compression, server compensation and
+recompression, error update, broadcast + local immediate compensation + model update) over one
+[N, d] batch of synthetic gradients that is already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
+DEFAULT_WORKLOAD = "c5_vgg16_mixed"   # the largest configuration; fits one GPU (grads 8.25 GiB)
+ALSO = ["c3_resnet18_sign", "c4_resnet50_topk", "c5_vgg16_sign"]
+N_GRAD_BUFFERS = 4          # distinct gradient batches rotated through the timed steps
+
+
+def log(msg: str) -> None:
+    print(msg, file=sys.stderr, flush=True)
+
+
+def dominant_kernel_bytes(w) -> int:
+    """Algorithmic bytes of one launch of the update kernel: grads and x read, x written
+    (12 B per gradient element) plus v read and e written (8 B per column)."""
+    return 12 * w.N * w.d + 8 * w.d
+
+
+def run_workload(w, steps: int, warmup: int, seed: int = 0):
+    import torch
+
+    import workloads
+    from paper_2402_11857_amd import LiecContext
+
+    dev = "cuda:0"
+    src = workloads.GradientSource(w, seed=seed, device=dev)
+    nbuf = min(N_GRAD_BUFFERS, max(1, steps + warmup))
+    grads = [src.grads(t) for t in range(nbuf)]
+    x = torch.zeros((w.N, w.d), dtype=torch.float32, device=dev)
+    e = torch.zeros(w.d, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    with LiecContext(w.N, w.d, w.worker_comp, w.server_comp, w.worker_k, w.server_k, w.lr) as ctx:
+        for t in range(warmup):
+            ctx.step(grads[t % nbuf], x, e)
+        torch.cuda.synchronize()
+        ctx.profile_begin(steps)              # HIP events around every kernel, on the step's stream
+        t0 = time.perf_counter()
+        for t in range(steps):
+            ctx.step(grads[(warmup + t) % nbuf], x, e)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        kernels = ctx.profile_end()
+        info, status = ctx.info_status()
+        assert status == 0, "non-finite values met during the bench"
+        scratch = ctx.scratch_bytes()
+    ms_per_step = 1e3 * elapsed / steps
+    out = {
+        "ms_per_step": ms_per_step,
+        "elems_per_s": w.N * w.d * steps / elapsed,
+        "alg_gbps": w.alg_bytes_per_step * steps / elapsed / 1e9,
+        "kernels_ms_per_step": {k: v[0] / steps for k, v in kernels.items()},
+        "kernel_launches": {k: v[1] for k, v in kernels.items()},
+        "scratch_bytes": scratch,
+    }
+    upd_ms, upd_n = kernels["update"]
+    out["update_avg_ms"] = upd_ms / upd_n
+    out["update_gbps"] = dominant_kernel_bytes(w) / (upd_ms / upd_n * 1e-3) / 1e9
+    del grads, x, e
+    torch.cuda.empty_cache()
+    return out
+
+
+def copy_ceiling_gbps(nbytes: int = 1 << 30, reps: int = 10) -> float:
+    """Bytes read + written per second by a plain 128-bit device copy kernel."""
+    import torch
+
+    from paper_2402_11857_amd import device_copy
+
+    a = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda:0").normal_()
+    b = torch.empty_like(a)
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(2):
+        device_copy(b, a, stream)
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(reps):
+        device_copy(b, a, stream)
+    stop.record()
+    torch.cuda.synchronize()
+    ms = start.elapsed_time(stop) / reps
+    return 2 * nbytes / (ms * 1e-3) / 1e9
+
+
+def cpu_baseline(w, seed: int = 0):
+    """The CPU oracle as it stands, one thread, on a column slice of the same workload."""
+    import numpy as np
+
+    import oracle
+    import workloads
+
+    oracle.build()
+    d_s = min(w.d, 1 << 21)
+    ws = workloads.scaled(w, d=d_s)
+    g = workloads.GradientSource(ws, seed=seed, device="cpu").grads(0).numpy()
+    x = np.zeros((ws.N, ws.d), dtype=np.float32)
+    e = np.zeros(ws.d, dtype=np.float32)
+    steps, t0 = 0, time.perf_counter()
+    while True:
+        oracle.step(g, x, e, ws.worker_comp, ws.server_comp, ws.lr, ws.worker_k, ws.server_k)
+        steps += 1
+        el = time.perf_counter() - t0
+        if el > 10.0 or steps >= 50:
+            break
+    return {"value": ws.N * ws.d * steps / el, "unit": "elems/s", "cores": 1, "kind": "oracle",
+            "sample": f"{steps} step(s) of the same recipe cut to N={ws.N}, d={ws.d} columns "
+                      f"(k scaled with d), {el:.1f} s of one host thread"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-also", action="store_true", help="skip the secondary workloads")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the N workers are a batch axis on a single MI355X; "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (there is no CPU path)", file=sys.stderr)
+        return 2
+    import workloads
+
+    wl = workloads.workloads()
+    w = wl[args.workload]
+    torch.cuda.set_device(0)
+    log(f"workload {w.name}: N={w.N} d={w.d} {w.worker_comp}/{w.server_comp}")
+    copy_gbps = copy_ceiling_gbps()
+    log(f"copy kernel ceiling {copy_gbps:.0f} GB/s")
+    main_res = run_workload(w, args.steps, args.warmup)
+    log(f"{w.name}: {main_res['ms_per_step']:.3f} ms/step, {main_res['alg_gbps']:.0f} GB/s algorithmic")
+    also = {}
+    if not args.no_also:
+        for name in ALSO:
+            if name == w.name:
+                continue
+            r = run_workload(wl[name], args.steps, args.warmup)
+            also[name] = {"ms_per_step": round(r["ms_per_step"], 4), "elems_per_s": r["elems_per_s"],
+                          "alg_gbps": round(r["alg_gbps"], 1), "hbm_frac": round(r["alg_gbps"] / HBM_PEAK_GBPS, 4),
+                          "update_gbps": round(r["update_gbps"], 1),
+                          "kernels_ms_per_step": {k: round(v, 4) for k, v in r["kernels_ms_per_step"].items()}}
+            log(f"{name}: {r['ms_per_step']:.3f} ms/step, {r['alg_gbps']:.0f} GB/s algorithmic")
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w)
+        log(f"cpu oracle: {cpu['value']:.3e} elems/s on {cpu['cores']} core")
+
+    line = {
+        "metric": "LIEC step gradient elems/s (N*d)",
+        "value": main_res["elems_per_s"],
+        "unit": "elems/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "N": w.N, "d": w.d, "worker_comp": w.worker_comp,
+                   "server_comp": w.server_comp, "worker_k": w.worker_k, "server_k": w.server_k,
+                   "lr": w.lr, "grad_buffers_rotated": N_GRAD_BUFFERS},
+        "step_alg_bytes": w.alg_bytes_per_step,
+        "step_alg_gbps": main_res["alg_gbps"],
+        "step_hbm_frac": main_res["alg_gbps"] / HBM_PEAK_GBPS,
+        "copy_kernel_gbps": copy_gbps,
+        "roofline": {"bound": "hbm", "kernel": "update", "achieved": main_res["update_gbps"],
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": main_res["update_gbps"] / HBM_PEAK_GBPS,
+                     "traffic": None, "alg_bytes_per_launch": dominant_kernel_bytes(w),
+                     "avg_launch_ms": main_res["update_avg_ms"]},
+        "kernels_ms_per_step": {k: round(v, 4) for k, v in main_res["kernels_ms_per_step"].items()},
+        "scratch_bytes": main_res["scratch_bytes"],
+        "also": also,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
