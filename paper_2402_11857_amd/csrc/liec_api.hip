@@ -16,20 +16,33 @@ using namespace liec;
 
 namespace {
 
-constexpr int kMaxSlots = 24;
-
+// Kernel slots for per-kernel timing: worker side, aggregation, server side, update.
 enum Slot : int {
-    S_W_L1 = 0, S_W_L1_FINAL, S_W_HIST0, S_W_PICK0, S_W_HIST1, S_W_PICK1, S_W_HIST2, S_W_PICK2,
-    S_W_TIE_COUNT, S_W_TIE_PICK, S_AGGREGATE, S_S_L1_FINAL, S_S_HIST0, S_S_PICK0, S_S_HIST1,
-    S_S_PICK1, S_S_HIST2, S_S_PICK2, S_S_TIE_COUNT, S_S_TIE_PICK, S_UPDATE, S_COUNT
+    S_W_L1 = 0, S_W_L1_FINAL,
+    S_W_SEL,                       // 12 slots of the worker-side top-k search
+    S_AGGREGATE = S_W_SEL + 12,
+    S_S_L1_FINAL,
+    S_S_SEL,                       // 12 slots of the server-side top-k search
+    S_UPDATE = S_S_SEL + 12,
+    S_COUNT
 };
-static_assert(S_COUNT <= kMaxSlots, "slot table too small");
 
-const char* const kSlotNames[S_COUNT] = {
-    "worker_l1_bits", "worker_l1_final", "worker_hist0", "worker_pick0", "worker_hist1", "worker_pick1",
-    "worker_hist2", "worker_pick2", "worker_tie_count", "worker_tie_pick", "server_aggregate",
-    "server_l1_final", "server_hist0", "server_pick0", "server_hist1", "server_pick1", "server_hist2",
-    "server_pick2", "server_tie_count", "server_tie_pick", "update"};
+const char* const kWorkerSel[12] = {"worker_filter_warm", "worker_check_warm", "worker_hist0", "worker_pick_band",
+                                    "worker_filter_cold", "worker_check_cold", "worker_list_hist0", "worker_list_hist1",
+                                    "worker_list_hist2", "worker_list_ties", "worker_list_finish", "worker_slow_select"};
+const char* const kServerSel[12] = {"server_filter_warm", "server_check_warm", "server_hist0", "server_pick_band",
+                                    "server_filter_cold", "server_check_cold", "server_list_hist0", "server_list_hist1",
+                                    "server_list_hist2", "server_list_ties", "server_list_finish", "server_slow_select"};
+
+const char* slot_name(int s) {
+    if (s == S_W_L1) return "worker_l1_bits";
+    if (s == S_W_L1_FINAL) return "worker_l1_final";
+    if (s >= S_W_SEL && s < S_W_SEL + 12) return kWorkerSel[s - S_W_SEL];
+    if (s == S_AGGREGATE) return "server_aggregate";
+    if (s == S_S_L1_FINAL) return "server_l1_final";
+    if (s >= S_S_SEL && s < S_S_SEL + 12) return kServerSel[s - S_S_SEL];
+    return "update";
+}
 
 struct ProfEvent {
     hipEvent_t start, stop;
@@ -49,18 +62,27 @@ struct liec_ctx {
     bool broken = false;
     int64_t steps_done = 0;
 
-    uint32_t ntiles = 0, nchunks = 0;
-    uint32_t row_blocks = 0, row_tpb = 0;      // per-row kernels over grads: grid (row_blocks, N)
-    uint32_t srv_blocks = 0, srv_tpb = 0;      // kernels over one length-d vector
+    uint32_t nwt = 0;                          // wave tiles of 1024 columns per row
+    uint32_t ncol_tiles = 0;                   // column tiles of the update kernel
+    uint32_t row_blocks = 0;                   // streaming kernels over grads: grid (row_blocks, N)
+    uint32_t srv_blocks = 0;                   // streaming kernels over one length-d vector
+    uint32_t agg_blocks = 0;                   // aggregation kernel
+    uint32_t cold_row_blocks = 0, cold_srv_blocks = 0;   // first-digit histogram (rarely needed)
+    uint32_t list_blocks = 0;                  // kernels over the candidate lists
+    uint32_t part_stride = 0;                  // max(row_blocks, srv_blocks)
+    uint32_t cap = 0;                          // candidate list capacity per row
 
     // device scratch
     RowDesc* desc = nullptr;                   // [N + 1]
+    float* vbuf = nullptr;                     // [d]  compensated average v
     double* w_partial = nullptr;               // [N * row_blocks]
-    double* s_partial = nullptr;               // [srv_blocks]
-    uint64_t* bits = nullptr;                  // [N * nchunks * 4]
-    uint32_t* hist = nullptr;                  // [(N + 1) * kHistBins]
-    uint32_t* w_cnt = nullptr;                 // [N * row_blocks]
-    uint32_t* s_cnt = nullptr;                 // [srv_blocks]
+    double* s_partial = nullptr;               // [agg_blocks]
+    uint64_t* bits = nullptr;                  // [N * nwt * 16] sign bits or candidate bitmap
+    uint2* list = nullptr;                     // [(N + 1) * cap] candidates (key, index)
+    uint32_t* sure_partial = nullptr;          // [(N + 1) * part_stride]
+    uint32_t* ghist = nullptr;                 // [(N + 1) * kHistBins]
+    uint32_t* lhist = nullptr;                 // [(N + 1) * 3 * kHistBins]
+    uint32_t* tiebuf = nullptr;                // [(N + 1) * kTieCap]
     int64_t scratch_bytes = 0;
 
     // profiling
@@ -83,12 +105,15 @@ hipError_t dev_alloc(liec_ctx* c, T** p, size_t count) {
 
 void free_scratch(liec_ctx* c) {
     (void)hipFree(c->desc);
+    (void)hipFree(c->vbuf);
     (void)hipFree(c->w_partial);
     (void)hipFree(c->s_partial);
     (void)hipFree(c->bits);
-    (void)hipFree(c->hist);
-    (void)hipFree(c->w_cnt);
-    (void)hipFree(c->s_cnt);
+    (void)hipFree(c->list);
+    (void)hipFree(c->sure_partial);
+    (void)hipFree(c->ghist);
+    (void)hipFree(c->lhist);
+    (void)hipFree(c->tiebuf);
 }
 
 bool valid_comp(int c) { return c == LIEC_COMP_IDENTITY || c == LIEC_COMP_SIGN || c == LIEC_COMP_TOPK; }
@@ -113,69 +138,78 @@ struct Launcher {
     }
 };
 
-// Radix select of the rank-k magnitude in each of `rows` rows of `src` (Definition 2), leaving
-// tau / rank / cutoff in desc[0..rows).  Four passes over the data: three digits, then the tie order.
+// Top-k threshold search (Definition 2) of `rows` rows of `src`; per-row state lives at row0 + r.
+// The host enqueues the same twelve kernels every step; each one acts only on the rows whose mode
+// asks for it, so the warm path costs one pass over the data and the others return at once.
 template <bool VEC>
-void launch_topk_select(Launcher& L, const float* src, size_t row_stride, uint32_t rows, uint32_t d,
-                        uint32_t ntiles, uint32_t blocks, uint32_t tpb, uint32_t k, RowDesc* desc,
-                        uint32_t* hist, uint32_t* cnt, int slot0) {
+void launch_topk_select(Launcher& L, const float* src, size_t row_stride, uint32_t rows, uint32_t row0, uint32_t k,
+                        uint64_t* bits, uint32_t blocks, uint32_t cold_blocks, int slot0) {
     liec_ctx* c = L.c;
-    const dim3 grid(blocks, rows);
+    const uint32_t d = (uint32_t)c->d;
+    hipStream_t st = c->stream;
+    const dim3 grid(blocks, rows), cold_grid(cold_blocks, rows), list_grid(c->list_blocks, rows);
     L.begin(slot0 + 0);
-    k_hist<VEC><<<grid, kBlock, 0, c->stream>>>(src, row_stride, d, ntiles, tpb, desc, 0, hist);
+    k_filter<VEC><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kWarm, bits, c->list, c->cap,
+                                            c->sure_partial);
     L.end();
     L.begin(slot0 + 1);
-    k_pick<0><<<rows, kBlock, 0, c->stream>>>(desc, hist, k);
+    k_check<<<rows, kBlock, 0, st>>>(row0, c->desc, kWarm, c->sure_partial, blocks, c->cap, k);
     L.end();
     L.begin(slot0 + 2);
-    k_hist<VEC><<<grid, kBlock, 0, c->stream>>>(src, row_stride, d, ntiles, tpb, desc, 1, hist);
+    k_hist0<VEC><<<cold_grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, c->ghist);
     L.end();
     L.begin(slot0 + 3);
-    k_pick<1><<<rows, kBlock, 0, c->stream>>>(desc, hist, k);
+    k_pick_band<<<rows, kBlock, 0, st>>>(row0, c->desc, c->ghist, c->cap, k);
     L.end();
     L.begin(slot0 + 4);
-    k_hist<VEC><<<grid, kBlock, 0, c->stream>>>(src, row_stride, d, ntiles, tpb, desc, 2, hist);
+    k_filter<VEC><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kColdBand, bits, c->list, c->cap,
+                                            c->sure_partial);
     L.end();
     L.begin(slot0 + 5);
-    k_pick<2><<<rows, kBlock, 0, c->stream>>>(desc, hist, k);
+    k_check<<<rows, kBlock, 0, st>>>(row0, c->desc, kColdBand, c->sure_partial, blocks, c->cap, k);
     L.end();
     L.begin(slot0 + 6);
-    k_tie_count<VEC><<<grid, kBlock, 0, c->stream>>>(src, row_stride, d, ntiles, tpb, desc, cnt);
+    k_list_hist<0><<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, c->lhist);
     L.end();
     L.begin(slot0 + 7);
-    k_tie_pick<VEC><<<rows, kBlock, 0, c->stream>>>(src, row_stride, d, ntiles, tpb, blocks, desc, cnt);
+    k_list_hist<1><<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, c->lhist);
+    L.end();
+    L.begin(slot0 + 8);
+    k_list_hist<2><<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, c->lhist);
+    L.end();
+    L.begin(slot0 + 9);
+    k_list_ties<<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, c->lhist, c->tiebuf);
+    L.end();
+    L.begin(slot0 + 10);
+    k_list_finish<<<rows, kBlock, 0, st>>>(row0, c->desc, c->lhist, c->tiebuf);
+    L.end();
+    L.begin(slot0 + 11);
+    k_slow_select<VEC><<<rows, 1024, 0, st>>>(src, row_stride, d, row0, c->desc, k);
     L.end();
 }
 
 template <int WC, bool VEC>
-void launch_aggregate(Launcher& L, const float* grads, float* e, bool srv_l1) {
+void launch_aggregate(Launcher& L, const float* grads, const float* e, bool srv_l1) {
     liec_ctx* c = L.c;
     const float inv_n = 1.0f / (float)c->N;
     const uint32_t d = (uint32_t)c->d;
     L.begin(S_AGGREGATE);
-    if (WC == kSign) {
-        if (srv_l1)
-            k_aggregate<kSign, true, true, VEC><<<c->srv_blocks, kBlock, 0, c->stream>>>(
-                grads, c->bits, c->nchunks, c->N, d, c->ntiles, c->srv_tpb, inv_n, c->desc, e, c->s_partial);
-        else
-            k_aggregate<kSign, true, false, VEC><<<c->srv_blocks, kBlock, 0, c->stream>>>(
-                grads, c->bits, c->nchunks, c->N, d, c->ntiles, c->srv_tpb, inv_n, c->desc, e, c->s_partial);
-    } else {
-        if (srv_l1)
-            k_aggregate<WC, false, true, VEC><<<c->srv_blocks, kBlock, 0, c->stream>>>(
-                grads, c->bits, c->nchunks, c->N, d, c->ntiles, c->srv_tpb, inv_n, c->desc, e, c->s_partial);
-        else
-            k_aggregate<WC, false, false, VEC><<<c->srv_blocks, kBlock, 0, c->stream>>>(
-                grads, c->bits, c->nchunks, c->N, d, c->ntiles, c->srv_tpb, inv_n, c->desc, e, c->s_partial);
-    }
+    if (srv_l1)
+        k_aggregate<WC, true, VEC><<<c->agg_blocks, kBlock, 0, c->stream>>>(grads, c->bits, c->N, d, c->nwt, inv_n,
+                                                                             c->desc, e, c->vbuf, c->s_partial);
+    else
+        k_aggregate<WC, false, VEC><<<c->agg_blocks, kBlock, 0, c->stream>>>(grads, c->bits, c->N, d, c->nwt, inv_n,
+                                                                              c->desc, e, c->vbuf, c->s_partial);
     L.end();
 }
 
 template <int WC, int SC, bool VEC>
 void launch_update(Launcher& L, const float* grads, float* x, float* e) {
     liec_ctx* c = L.c;
+    const uint32_t rg = (uint32_t)((c->N + kUpdateRows - 1) / kUpdateRows);
     L.begin(S_UPDATE);
-    k_update<WC, SC, VEC><<<c->ntiles, kBlock, 0, c->stream>>>(grads, x, e, c->N, (uint32_t)c->d, -c->lr, c->desc);
+    k_update<WC, SC, VEC><<<c->ncol_tiles * rg, kBlock, 0, c->stream>>>(grads, x, c->vbuf, e, c->N, rg, (uint32_t)c->d,
+                                                                         -c->lr, c->desc);
     L.end();
 }
 
@@ -194,21 +228,21 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
     const uint32_t d = (uint32_t)c->d;
     const size_t stride = (size_t)c->d;
 
-    // ---- workers: p^i = C_w(g_i), reduced to a per-row descriptor --------------------------------
+    // ---- workers: p^i = C_w(g_i), reduced to a per-row descriptor (+ packed bits) ------------------
     if (c->worker_comp == kSign) {
         L.begin(S_W_L1);
-        k_l1_bits<VEC><<<dim3(c->row_blocks, c->N), kBlock, 0, c->stream>>>(
-            grads, stride, d, c->ntiles, c->row_tpb, c->w_partial, c->bits, c->nchunks);
+        k_l1_bits<VEC><<<dim3(c->row_blocks, c->N), kBlock, 0, c->stream>>>(grads, stride, d, c->nwt, c->w_partial,
+                                                                             c->bits);
         L.end();
         L.begin(S_W_L1_FINAL);
         k_l1_final<<<c->N, kBlock, 0, c->stream>>>(c->w_partial, c->row_blocks, d, c->desc);
         L.end();
     } else if (c->worker_comp == kTopk) {
-        launch_topk_select<VEC>(L, grads, stride, (uint32_t)c->N, d, c->ntiles, c->row_blocks, c->row_tpb,
-                                (uint32_t)c->worker_k, c->desc, c->hist, c->w_cnt, S_W_HIST0);
+        launch_topk_select<VEC>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, c->bits, c->row_blocks,
+                                c->cold_row_blocks, S_W_SEL);
     }
 
-    // ---- server: v = e + mean_i p^i (in place over e), then the descriptor of C_s(v) -------------
+    // ---- server: v = e + mean_i p^i, then the descriptor of C_s(v) ---------------------------------
     const bool srv_l1 = c->server_comp == kSign;
     switch (c->worker_comp) {
     case kIdentity: launch_aggregate<kIdentity, VEC>(L, grads, e, srv_l1); break;
@@ -217,11 +251,12 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
     }
     if (c->server_comp == kSign) {
         L.begin(S_S_L1_FINAL);
-        k_l1_final<<<1, kBlock, 0, c->stream>>>(c->s_partial, c->srv_blocks, d, c->desc + c->N);
+        k_l1_final<<<1, kBlock, 0, c->stream>>>(c->s_partial, c->agg_blocks, d, c->desc + c->N);
         L.end();
     } else if (c->server_comp == kTopk) {
-        launch_topk_select<VEC>(L, e, 0, 1u, d, c->ntiles, c->srv_blocks, c->srv_tpb, (uint32_t)c->server_k,
-                                c->desc + c->N, c->hist + (size_t)c->N * kHistBins, c->s_cnt, S_S_HIST0);
+        // v is always 16-byte aligned scratch, but d % 4 decides whether 128-bit loads stay in bounds
+        launch_topk_select<VEC>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, nullptr, c->srv_blocks,
+                                c->cold_srv_blocks, S_S_SEL);
     }
 
     // ---- p = C_s(v), e <- v - p, x^i <- x^i - lr (p + (g_i - p^i)) ---------------------------------
@@ -285,27 +320,40 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
         return LIEC_EDEVICE;
     }
 
-    c->ntiles = (uint32_t)((d + kTile - 1) / kTile);
-    c->nchunks = (uint32_t)((d + kChunk - 1) / kChunk);
-    // Per-row kernels: aim at about 4096 blocks over all rows, at least 4 tiles per block.
-    uint32_t want = 4096u / (uint32_t)N;
-    if (want < 1) want = 1;
-    c->row_tpb = (c->ntiles + want - 1) / want;
-    if (c->row_tpb < 4) c->row_tpb = 4;
-    c->row_blocks = (c->ntiles + c->row_tpb - 1) / c->row_tpb;
-    c->srv_tpb = (c->ntiles + 4095u) / 4096u;
-    if (c->srv_tpb < 1) c->srv_tpb = 1;
-    c->srv_blocks = (c->ntiles + c->srv_tpb - 1) / c->srv_tpb;
+    const bool any_topk = worker_comp == LIEC_COMP_TOPK || server_comp == LIEC_COMP_TOPK;
+    const uint32_t un = (uint32_t)N;
+    c->nwt = (uint32_t)((d + kWaveTile - 1) / kWaveTile);
+    c->ncol_tiles = (uint32_t)((d + kColTile - 1) / kColTile);
+    const uint32_t blk_iters = (c->nwt + 3) / 4;               // block iterations that cover one row
+    auto clampu = [](uint32_t v, uint32_t lo, uint32_t hi) { return v < lo ? lo : (v > hi ? hi : v); };
+    c->row_blocks = clampu(32768u / un, 1u, blk_iters);
+    c->srv_blocks = clampu(8192u, 1u, blk_iters);
+    c->agg_blocks = clampu(16384u, 1u, blk_iters);
+    c->cold_row_blocks = clampu(2048u / un, 1u, blk_iters);
+    c->cold_srv_blocks = clampu(2048u, 1u, blk_iters);
+    c->part_stride = c->row_blocks > c->srv_blocks ? c->row_blocks : c->srv_blocks;
+    c->cap = (uint32_t)((d / 16 + 4096 < d) ? d / 16 + 4096 : d);
+    c->list_blocks = clampu((c->cap + 2047u) / 2048u, 1u, 64u);
 
-    hipError_t e = dev_alloc(c, &c->desc, (size_t)N + 1);
+    const size_t rows = (size_t)N + 1;
+    hipError_t e = dev_alloc(c, &c->desc, rows);
+    if (e == hipSuccess) e = dev_alloc(c, &c->vbuf, (size_t)c->nwt * kWaveTile);
     if (e == hipSuccess) e = dev_alloc(c, &c->w_partial, (size_t)N * c->row_blocks);
-    if (e == hipSuccess) e = dev_alloc(c, &c->s_partial, (size_t)c->srv_blocks);
-    if (e == hipSuccess && worker_comp == LIEC_COMP_SIGN) e = dev_alloc(c, &c->bits, (size_t)N * c->nchunks * 4);
-    if (e == hipSuccess) e = dev_alloc(c, &c->hist, ((size_t)N + 1) * kHistBins);
-    if (e == hipSuccess) e = dev_alloc(c, &c->w_cnt, (size_t)N * c->row_blocks);
-    if (e == hipSuccess) e = dev_alloc(c, &c->s_cnt, (size_t)c->srv_blocks);
-    if (e == hipSuccess) e = hipMemsetAsync(c->desc, 0, ((size_t)N + 1) * sizeof(RowDesc), c->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(c->hist, 0, ((size_t)N + 1) * kHistBins * sizeof(uint32_t), c->stream);
+    if (e == hipSuccess) e = dev_alloc(c, &c->s_partial, (size_t)c->agg_blocks);
+    if (e == hipSuccess && worker_comp != LIEC_COMP_IDENTITY) e = dev_alloc(c, &c->bits, (size_t)N * c->nwt * 16);
+    if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->list, rows * c->cap);
+    if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->sure_partial, rows * c->part_stride);
+    if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->ghist, rows * kHistBins);
+    if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->lhist, rows * 3 * kHistBins);
+    if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->tiebuf, rows * kTieCap);
+    if (e == hipSuccess) {
+        std::vector<RowDesc> init(rows);
+        std::memset(init.data(), 0, rows * sizeof(RowDesc));
+        for (auto& r : init) r.mode = kCold;       // no prediction before the first step
+        e = hipMemcpy(c->desc, init.data(), rows * sizeof(RowDesc), hipMemcpyHostToDevice);
+    }
+    if (e == hipSuccess && any_topk) e = hipMemsetAsync(c->ghist, 0, rows * kHistBins * sizeof(uint32_t), c->stream);
+    if (e == hipSuccess && any_topk) e = hipMemsetAsync(c->lhist, 0, rows * 3 * kHistBins * sizeof(uint32_t), c->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -439,7 +487,7 @@ liec_status liec_profile_end(liec_ctx* c, int32_t* n_slots, const char** names, 
     for (int s = 0; s < S_COUNT; ++s) {
         if (!cnt[s]) continue;
         if (used >= *n_slots) return LIEC_EINVAL;
-        names[used] = kSlotNames[s];
+        names[used] = slot_name(s);
         total_ms[used] = ms[s];
         launches[used] = cnt[s];
         ++used;

@@ -1,11 +1,12 @@
 // Device kernels of the LIEC-SGD compressed step for gfx950 (CDNA4, wave64).
 //
-// Element ownership is the same in every kernel: a block of 256 threads walks
-// "tiles" of 1024 consecutive columns; inside a tile, wave w owns the 256-column
-// "chunk" 4*tile + w and lane l owns columns 4l..4l+3 of that chunk (one 128-bit
-// access per lane, 1 KiB contiguous per wave).  All fp32 arithmetic that reaches
-// the outputs is written as single IEEE operations (__fadd_rn / __fsub_rn /
-// __fmaf_rn) so that the result does not depend on compiler contraction.
+// Element ownership in the streaming kernels: a wave walks "wave tiles" of 1024 consecutive
+// columns (4 chunks of 256); in chunk u, lane l owns columns 256u + 4l .. 256u + 4l + 3 (one
+// 128-bit access per lane, 1 KiB contiguous per wave and instruction).  A block of 256 threads
+// (4 waves) covers 4096 consecutive columns per iteration.  All fp32 arithmetic that reaches the
+// outputs is written as single IEEE operations (__fadd_rn / __fsub_rn / __fmaf_rn) so that the
+// result does not depend on compiler contraction.  Streams that are read or written once are
+// accessed with non-temporal hints.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -13,22 +14,44 @@
 namespace liec {
 
 constexpr int kBlock = 256;             // threads per block (4 waves)
-constexpr int kTile = kBlock * 4;       // columns per block iteration
-constexpr int kChunk = 256;             // columns per wave iteration
+constexpr int kChunk = 256;             // columns per wave and load instruction
+constexpr int kWaveTile = 1024;         // columns per wave iteration
+constexpr int kColTile = 1024;          // columns per block of the update kernel
 constexpr int kHistBins = 4096;         // widest radix digit (12 bits)
+constexpr int kStage = 512;             // per-wave LDS staging slots of the candidate filter
+constexpr int kTieCap = 4096;           // ties at the threshold the fast path resolves
+constexpr uint32_t kBandMargin = 1u << 18;   // half width, in key units, of the predicted band
+constexpr int kUpdateRows = 4;          // rows per block of the update kernel
 
 enum Comp : int { kIdentity = 0, kSign = 1, kTopk = 2 };
+
+// Progress of a row's top-k threshold search within one step.
+enum SelMode : uint32_t {
+    kWarm = 0,      // a band [lo, hi) predicted from the previous step is to be filtered
+    kCold = 1,      // no usable prediction: the first radix digit of the whole row is needed
+    kColdBand = 2,  // band = the first-digit bin holding rank k; to be filtered
+    kList = 3,      // candidates of the band are listed; select among them
+    kSlow = 4       // needs the general (single block, multi pass) search over the row
+};
 
 // One per worker row, plus one (index N) for the server's vector v.
 struct RowDesc {
     double l1;             // scaled sign: sum |v_j| (fp64)
     float scale;           // scaled sign: fp32(l1 / d)
-    uint32_t tau;          // top-k: key prefix while the digits are being resolved, then the k-th key
-    uint32_t rank;         // top-k: rank still to be located inside the current prefix (1-based);
-                           //        after the last digit: how many entries with key == tau are kept
+    uint32_t tau;          // top-k: key of the k-th kept entry
+    uint32_t rank;         // top-k: how many entries with key == tau are kept
     uint32_t ties;         // top-k: how many entries have key == tau
     uint32_t cutoff;       // top-k: largest kept index among entries with key == tau
-    uint32_t nonfinite;    // a NaN/Inf reached the L1 sum or a key
+    uint32_t nonfinite;    // a NaN/Inf reached the L1 sum or a key (last step)
+    uint32_t nonfinite_acc;
+    uint32_t lo, hi;       // candidate band: keys in [lo, hi) are listed, keys >= hi are surely kept
+    uint32_t mode;         // SelMode
+    uint32_t n_cand;       // candidates appended so far (may exceed the capacity: overflow)
+    uint32_t n_ties;       // ties collected
+    uint32_t dense;        // the row's candidate bitmap is not valid: test every column
+    uint32_t sel_prefix[3];  // list select: key prefix before digit p
+    uint32_t sel_rank[3];    // list select: rank inside the prefix before digit p
+    uint32_t pad;
 };
 
 // Radix digits of the 31-bit magnitude key, most significant first.
@@ -37,12 +60,21 @@ __host__ __device__ constexpr int digit_bits(int pass) { return pass == 0 ? 12 :
 
 __device__ __forceinline__ uint32_t key_of(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 
+typedef float v4f __attribute__((ext_vector_type(4)));
+
 // 4 consecutive floats starting at column j of a row of length d; zero beyond d.
-template <bool VEC>
+template <bool VEC, bool NT = false>
 __device__ __forceinline__ float4 ld4(const float* __restrict__ row, uint32_t j, uint32_t d) {
     float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
     if (VEC) {
-        if (j < d) r = *reinterpret_cast<const float4*>(row + j);
+        if (j < d) {
+            if (NT) {
+                const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(row + j));
+                r = make_float4(t.x, t.y, t.z, t.w);
+            } else {
+                r = *reinterpret_cast<const float4*>(row + j);
+            }
+        }
     } else {
         if (j < d) r.x = row[j];
         if (j + 1 < d) r.y = row[j + 1];
@@ -52,10 +84,17 @@ __device__ __forceinline__ float4 ld4(const float* __restrict__ row, uint32_t j,
     return r;
 }
 
-template <bool VEC>
+template <bool VEC, bool NT = false>
 __device__ __forceinline__ void st4(float* __restrict__ row, uint32_t j, uint32_t d, float4 v) {
     if (VEC) {
-        if (j < d) *reinterpret_cast<float4*>(row + j) = v;
+        if (j < d) {
+            if (NT) {
+                const v4f t = {v.x, v.y, v.z, v.w};
+                __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(row + j));
+            } else {
+                *reinterpret_cast<float4*>(row + j) = v;
+            }
+        }
     } else {
         if (j < d) row[j] = v.x;
         if (j + 1 < d) row[j + 1] = v.y;
@@ -64,56 +103,134 @@ __device__ __forceinline__ void st4(float* __restrict__ row, uint32_t j, uint32_
     }
 }
 
-// Sum over the block in a fixed order (lanes by halving, then waves 0..3).
-// The result is valid on thread 0 only.
-__device__ __forceinline__ double block_sum_f64(double v, double* lds4) {
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {   // set bits of mask below this lane
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// Sum over the block in a fixed order (lanes by halving, then waves in order).  Valid on thread 0.
+__device__ __forceinline__ double block_sum_f64(double v, double* lds_waves) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    if (lane == 0) lds4[wave] = v;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+    if (lane == 0) lds_waves[wave] = v;
     __syncthreads();
     double r = 0.0;
-    if (threadIdx.x == 0) r = ((lds4[0] + lds4[1]) + lds4[2]) + lds4[3];
+    if (threadIdx.x == 0)
+        for (int w = 0; w < nw; ++w) r += lds_waves[w];
     return r;
 }
 
-// ---------------------------------------------------------------------------------------------
-// Scaled sign, worker side (Definition 4): per-row partial sums of |g| in fp64 and, optionally,
-// the sign bits of the row.  Bit layout: for chunk c of row i, four 64-bit words
-// bits[(i*nchunks + c)*4 + q], q = 0..3; bit l of word q is (g[256c + 4l + q] < 0).
-// grid = (blocks per row, rows); block b of a row handles tiles b*tpb .. (b+1)*tpb - 1.
-// ---------------------------------------------------------------------------------------------
-template <bool VEC>
-__global__ __launch_bounds__(kBlock) void k_l1_bits(const float* __restrict__ src, size_t row_stride,
-                                                     uint32_t d, uint32_t ntiles, uint32_t tpb,
-                                                     double* __restrict__ partial,
-                                                     uint64_t* __restrict__ bits, uint32_t nchunks) {
-    __shared__ double lds4[4];
-    const uint32_t row = blockIdx.y;
-    const float* __restrict__ g = src + (size_t)row * row_stride;
-    const uint32_t t0 = blockIdx.x * tpb;
-    const uint32_t t1 = min(t0 + tpb, ntiles);
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    double acc = 0.0;
-#pragma unroll 4
-    for (uint32_t t = t0; t < t1; ++t) {
-        const uint32_t j = t * kTile + threadIdx.x * 4;
-        const float4 a = ld4<VEC>(g, j, d);
-        acc += (double)fabsf(a.x);
-        acc += (double)fabsf(a.y);
-        acc += (double)fabsf(a.z);
-        acc += (double)fabsf(a.w);
-        if (bits) {
-            const uint64_t b0 = __ballot(a.x < 0.f), b1 = __ballot(a.y < 0.f);
-            const uint64_t b2 = __ballot(a.z < 0.f), b3 = __ballot(a.w < 0.f);
-            const uint32_t chunk = t * 4 + wave;
-            if (lane < 4 && chunk < nchunks) {
-                const uint64_t w = lane == 0 ? b0 : (lane == 1 ? b1 : (lane == 2 ? b2 : b3));
-                bits[((size_t)row * nchunks + chunk) * 4 + lane] = w;
-            }
+__device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* lds_waves) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+    if (lane == 0) lds_waves[wave] = v;
+    __syncthreads();
+    uint32_t r = 0;
+    if (threadIdx.x == 0)
+        for (int w = 0; w < nw; ++w) r += lds_waves[w];
+    return r;
+}
+
+// Walks a histogram of nbins (512, 1024 or 4096) counts from the top bin down to the bin that
+// holds the entry of rank `rank` (1-based, largest first).  Needs blockDim.x >= 256; every thread
+// of the block must call it.  part: 256 words of LDS, res: 3 words of LDS.
+struct Pick {
+    uint32_t bin, rank_in, count;
+};
+__device__ __forceinline__ Pick block_pick(const uint32_t* __restrict__ h, int nbins, uint32_t rank,
+                                           uint32_t* part, uint32_t* res) {
+    const int per = nbins >> 8;   // 2, 4 or 16 bins per thread
+    const uint32_t tid = threadIdx.x;
+    uint32_t local[16];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        local[q] = (tid < 256 && q < per) ? h[tid * per + q] : 0u;
+        sum += local[q];
+    }
+    if (tid < 256) part[tid] = sum;
+    if (tid == 0) {
+        res[0] = 0;
+        res[1] = 1;
+        res[2] = 0;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t run = 0;
+        for (int t = 255; t >= 0; --t) {
+            const uint32_t s = part[t];
+            part[t] = run;            // count in the bins above thread t's range
+            run += s;
         }
     }
-    const double s = block_sum_f64(acc, lds4);
+    __syncthreads();
+    if (tid < 256) {
+        const uint32_t above = part[tid];
+        if (above < rank && rank <= above + sum) {   // true for exactly one thread
+            uint32_t run = above, bin = tid * per, cnt = local[0];
+            bool done = false;
+#pragma unroll
+            for (int q = 15; q >= 0; --q) {
+                if (q < per) {
+                    if (!done && run + local[q] >= rank) {
+                        bin = tid * per + q;
+                        cnt = local[q];
+                        done = true;
+                    }
+                    if (!done) run += local[q];
+                }
+            }
+            res[0] = bin;
+            res[1] = rank - run;
+            res[2] = cnt;
+        }
+    }
+    __syncthreads();
+    Pick p;
+    p.bin = res[0];
+    p.rank_in = res[1];
+    p.count = res[2];
+    __syncthreads();
+    return p;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Scaled sign, worker side (Definition 4): per-row partial sums of |g| in fp64 and the sign bits
+// of the row.  Bit layout: wave tile t of row i owns 16 words bits[(i*nwt + t)*16 + 4u + q];
+// bit l of that word is (g[1024t + 256u + 4l + q] < 0).
+// grid = (blocks per row, rows); waves stride over the row's wave tiles.
+// ---------------------------------------------------------------------------------------------
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_l1_bits(const float* __restrict__ src, size_t row_stride, uint32_t d,
+                                                     uint32_t nwt, double* __restrict__ partial,
+                                                     uint64_t* __restrict__ bits) {
+    __shared__ double lds_w[4];
+    const uint32_t row = blockIdx.y;
+    const float* __restrict__ g = src + (size_t)row * row_stride;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    double acc = 0.0;
+    for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
+        float4 a[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
+        uint64_t word = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            acc += (double)fabsf(a[u].x);
+            acc += (double)fabsf(a[u].y);
+            acc += (double)fabsf(a[u].z);
+            acc += (double)fabsf(a[u].w);
+            const uint64_t b0 = __ballot(a[u].x < 0.f), b1 = __ballot(a[u].y < 0.f);
+            const uint64_t b2 = __ballot(a[u].z < 0.f), b3 = __ballot(a[u].w < 0.f);
+            word = lane == 4 * u ? b0 : word;
+            word = lane == 4 * u + 1 ? b1 : word;
+            word = lane == 4 * u + 2 ? b2 : word;
+            word = lane == 4 * u + 3 ? b3 : word;
+        }
+        if (lane < 16) bits[((size_t)row * nwt + t) * 16 + lane] = word;
+    }
+    const double s = block_sum_f64(acc, lds_w);
     if (threadIdx.x == 0) partial[(size_t)row * gridDim.x + blockIdx.x] = s;
 }
 
@@ -121,204 +238,397 @@ __global__ __launch_bounds__(kBlock) void k_l1_bits(const float* __restrict__ sr
 // grid = rows, desc points at the first row's descriptor.
 __global__ __launch_bounds__(kBlock) void k_l1_final(const double* __restrict__ partial, uint32_t nparts,
                                                       uint32_t d, RowDesc* __restrict__ desc) {
-    __shared__ double lds4[4];
+    __shared__ double lds_w[4];
     const uint32_t row = blockIdx.x;
     const double* __restrict__ p = partial + (size_t)row * nparts;
     double acc = 0.0;
     for (uint32_t q = threadIdx.x; q < nparts; q += kBlock) acc += p[q];
-    const double s = block_sum_f64(acc, lds4);
+    const double s = block_sum_f64(acc, lds_w);
     if (threadIdx.x == 0) {
         desc[row].l1 = s;
         desc[row].scale = (float)(s / (double)d);
-        desc[row].nonfinite = (s - s == 0.0) ? 0u : 1u;   // false for NaN and Inf
+        desc[row].nonfinite = (s - s == 0.0) ? 0u : 1u;   // s - s is NaN for NaN and Inf
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Top-k (Definition 2) threshold search: radix select on the 31-bit magnitude key.
-// k_hist counts, per row, the current digit of every key whose higher digits equal the prefix
-// found so far; k_pick walks the counts from the top to the bin holding the wanted rank.
+// Top-k (Definition 2).  The k-th largest magnitude key tau of a row and the index cut-off
+// among its ties are found without sorting:
+//   1. k_filter streams the row once against a band [lo, hi) of keys expected to hold tau:
+//      keys >= hi are only counted, keys inside the band are appended to a candidate list
+//      (key, index), and a bitmap of "key >= lo" is written for the aggregation kernel.
+//      The band is predicted from the previous step's tau (kWarm); when there is none, or the
+//      prediction fails (k_check), the band is the first-radix-digit bin holding rank k, found by
+//      k_hist0 + k_pick_band over the whole row (kCold -> kColdBand), and the row is filtered again.
+//   2. k_list_hist / k_list_ties / k_list_finish run a 3-digit radix select on the listed keys
+//      and order the ties by index.
+//   3. Rows the list cannot hold (massive ties, degenerate data) take k_slow_select.
+// All decisions are taken on the device per row; the host always enqueues the same kernels.
+// `row0` is added to blockIdx.y to address per-row state (the server's vector uses row N).
 // ---------------------------------------------------------------------------------------------
 template <bool VEC>
-__global__ __launch_bounds__(kBlock) void k_hist(const float* __restrict__ src, size_t row_stride, uint32_t d,
-                                                  uint32_t ntiles, uint32_t tpb, const RowDesc* __restrict__ desc,
-                                                  int pass, uint32_t* __restrict__ hist) {
-    __shared__ uint32_t h[kHistBins];
-    const uint32_t row = blockIdx.y;
-    const float* __restrict__ g = src + (size_t)row * row_stride;
-    const int shift = digit_shift(pass), nbins = 1 << digit_bits(pass);
-    const int hi_shift = pass == 0 ? 31 : digit_shift(pass - 1);   // bits above this digit
-    const uint32_t prefix = pass == 0 ? 0u : desc[row].tau;
-    for (int b = threadIdx.x; b < nbins; b += kBlock) h[b] = 0;
-    __syncthreads();
-    const uint32_t t0 = blockIdx.x * tpb;
-    const uint32_t t1 = min(t0 + tpb, ntiles);
-#pragma unroll 2
-    for (uint32_t t = t0; t < t1; ++t) {
-        const uint32_t j = t * kTile + threadIdx.x * 4;
-        const float4 a = ld4<VEC>(g, j, d);
-        const float av[4] = {a.x, a.y, a.z, a.w};
+__global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src, size_t row_stride, uint32_t d,
+                                                    uint32_t nwt, uint32_t row0, RowDesc* __restrict__ desc,
+                                                    uint32_t expect_mode, uint64_t* __restrict__ bits,
+                                                    uint2* __restrict__ list, uint32_t cap,
+                                                    uint32_t* __restrict__ sure_partial) {
+    __shared__ uint2 stage[4][kStage];
+    __shared__ uint32_t wsure[4];
+    const uint32_t row = row0 + blockIdx.y;
+    if (desc[row].mode != expect_mode) return;                 // uniform for the block
+    const uint32_t lo = desc[row].lo, hi = desc[row].hi;
+    const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
+    uint2* __restrict__ out = list + (size_t)row * cap;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    uint2* st = stage[wave];
+    uint32_t cnt = 0, nsure = 0;
+    bool bad = false;
+    for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
+        float4 a[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const uint32_t key = key_of(av[c]);
-            const bool match = (j + c < d) && (((key ^ prefix) >> hi_shift) == 0);
-            if (match) atomicAdd(&h[(key >> shift) & (nbins - 1)], 1u);
+        for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
+        uint64_t word = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
+            const float av[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
+            uint32_t keys[4];
+            uint64_t bc[4];
+            uint32_t m = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t key = key_of(av[q]);
+                const bool valid = j + q < d;
+                keys[q] = key;
+                bad |= valid && key >= 0x7f800000u;
+                const uint64_t bl = __ballot(valid && key >= lo);
+                const uint64_t bh = __ballot(valid && key >= hi);
+                word = lane == 4 * u + q ? bl : word;
+                nsure += __popcll(bh);
+                bc[q] = bl & ~bh;
+                m += __popcll(bc[q]);
+            }
+            if (m) {                                            // wave-uniform
+                if (cnt + m > kStage) {                         // flush the staged candidates
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    uint32_t base = 0;
+                    if (lane == 0) base = atomicAdd(&desc[row].n_cand, cnt);
+                    base = __builtin_amdgcn_readfirstlane(base);
+                    for (uint32_t s = lane; s < cnt; s += 64)
+                        if (base + s < cap) out[base + s] = st[s];
+                    cnt = 0;
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                }
+                uint32_t off = cnt;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if ((bc[q] >> lane) & 1) st[off + lanes_below(bc[q])] = make_uint2(keys[q], j + q);
+                    off += __popcll(bc[q]);
+                }
+                cnt += m;
+            }
+        }
+        if (bits && lane < 16) bits[((size_t)blockIdx.y * nwt + t) * 16 + lane] = word;
+    }
+    if (cnt) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(&desc[row].n_cand, cnt);
+        base = __builtin_amdgcn_readfirstlane(base);
+        for (uint32_t s = lane; s < cnt; s += 64)
+            if (base + s < cap) out[base + s] = st[s];
+    }
+    if (__ballot(bad) && lane == 0) atomicOr(&desc[row].nonfinite_acc, 1u);
+    if (lane == 0) wsure[wave] = nsure;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        sure_partial[(size_t)row * gridDim.x + blockIdx.x] = wsure[0] + wsure[1] + wsure[2] + wsure[3];
+}
+
+// grid = rows.  After a filter pass over rows in `expect_mode`: the band is usable when the list did
+// not overflow and rank k falls inside it.
+__global__ __launch_bounds__(kBlock) void k_check(uint32_t row0, RowDesc* __restrict__ desc, uint32_t expect_mode,
+                                                   const uint32_t* __restrict__ sure_partial, uint32_t nparts,
+                                                   uint32_t cap, uint32_t k) {
+    __shared__ uint32_t lds_w[4];
+    const uint32_t row = row0 + blockIdx.x;
+    if (desc[row].mode != expect_mode) return;
+    uint32_t acc = 0;
+    for (uint32_t q = threadIdx.x; q < nparts; q += kBlock) acc += sure_partial[(size_t)row * nparts + q];
+    const uint32_t n_sure = block_sum_u32(acc, lds_w);
+    if (threadIdx.x == 0) {
+        RowDesc r = desc[row];
+        const bool ok = r.n_cand <= cap && n_sure < k && (uint64_t)k <= (uint64_t)n_sure + r.n_cand;
+        if (ok) {
+            r.mode = kList;
+            r.sel_prefix[0] = 0;
+            r.sel_rank[0] = k - n_sure;
+        } else {
+            r.mode = expect_mode == kWarm ? kCold : kSlow;
+            r.n_cand = 0;
+        }
+        desc[row] = r;
+    }
+}
+
+// First radix digit (12 bits) of every key of the rows in kCold mode.  grid = (blocks, rows).
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_hist0(const float* __restrict__ src, size_t row_stride, uint32_t d,
+                                                   uint32_t nwt, uint32_t row0, const RowDesc* __restrict__ desc,
+                                                   uint32_t* __restrict__ hist) {
+    __shared__ uint32_t h[kHistBins];
+    const uint32_t row = row0 + blockIdx.y;
+    if (desc[row].mode != kCold) return;
+    const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
+    for (int b = threadIdx.x; b < kHistBins; b += kBlock) h[b] = 0;
+    __syncthreads();
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
+        float4 a[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
+            if (j < d) atomicAdd(&h[key_of(a[u].x) >> 19], 1u);
+            if (j + 1 < d) atomicAdd(&h[key_of(a[u].y) >> 19], 1u);
+            if (j + 2 < d) atomicAdd(&h[key_of(a[u].z) >> 19], 1u);
+            if (j + 3 < d) atomicAdd(&h[key_of(a[u].w) >> 19], 1u);
         }
     }
     __syncthreads();
     uint32_t* __restrict__ out = hist + (size_t)row * kHistBins;
+    for (int b = threadIdx.x; b < kHistBins; b += kBlock) {
+        const uint32_t c = h[b];
+        if (c) atomicAdd(&out[b], c);
+    }
+}
+
+// grid = rows.  For rows in kCold mode: the band becomes the first-digit bin that holds rank k.
+__global__ __launch_bounds__(kBlock) void k_pick_band(uint32_t row0, RowDesc* __restrict__ desc,
+                                                       uint32_t* __restrict__ hist, uint32_t cap, uint32_t k) {
+    __shared__ uint32_t part[256], res[3];
+    const uint32_t row = row0 + blockIdx.x;
+    if (desc[row].mode != kCold) return;
+    uint32_t* __restrict__ h = hist + (size_t)row * kHistBins;
+    const Pick p = block_pick(h, kHistBins, k, part, res);
+    for (int b = threadIdx.x; b < kHistBins; b += kBlock) h[b] = 0;
+    if (threadIdx.x == 0) {
+        RowDesc r = desc[row];
+        r.lo = p.bin << 19;
+        r.hi = (p.bin + 1) << 19;            // 0x80000000 for the top bin: no key reaches it
+        r.n_cand = 0;
+        r.mode = p.count <= cap ? kColdBand : kSlow;
+        desc[row] = r;
+    }
+}
+
+// Radix digit P (0, 1, 2) of the listed keys whose higher digits equal the prefix found so far.
+// Each block first redoes the pick of digit P - 1 from that digit's finished histogram.
+// grid = (blocks, rows); lhist holds 3 histograms of kHistBins per row: [row][P][bin].
+template <int P>
+__global__ __launch_bounds__(kBlock) void k_list_hist(uint32_t row0, RowDesc* __restrict__ desc,
+                                                       const uint2* __restrict__ list, uint32_t cap,
+                                                       uint32_t* __restrict__ lhist) {
+    __shared__ uint32_t h[kHistBins];
+    __shared__ uint32_t part[256], res[3];
+    const uint32_t row = row0 + blockIdx.y;
+    if (desc[row].mode != kList) return;
+    uint32_t* __restrict__ hrow = lhist + (size_t)row * 3 * kHistBins;
+    uint32_t prefix = 0;
+    if (P > 0) {
+        const Pick p = block_pick(hrow + (P - 1) * kHistBins, 1 << digit_bits(P - 1), desc[row].sel_rank[P - 1], part,
+                                  res);
+        prefix = desc[row].sel_prefix[P - 1] | (p.bin << digit_shift(P - 1));
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            desc[row].sel_prefix[P] = prefix;
+            desc[row].sel_rank[P] = p.rank_in;
+        }
+    }
+    constexpr int nbins = 1 << digit_bits(P);
+    constexpr int shift = digit_shift(P);
+    constexpr int hi_shift = P == 0 ? 31 : digit_shift(P - 1);
+    for (int b = threadIdx.x; b < nbins; b += kBlock) h[b] = 0;
+    __syncthreads();
+    const uint32_t n = min(desc[row].n_cand, cap);
+    const uint2* __restrict__ in = list + (size_t)row * cap;
+    for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < n; e += gridDim.x * kBlock) {
+        const uint32_t key = in[e].x;
+        if (((key ^ prefix) >> hi_shift) == 0) atomicAdd(&h[(key >> shift) & (nbins - 1)], 1u);
+    }
+    __syncthreads();
+    uint32_t* __restrict__ out = hrow + P * kHistBins;
     for (int b = threadIdx.x; b < nbins; b += kBlock) {
         const uint32_t c = h[b];
         if (c) atomicAdd(&out[b], c);
     }
 }
 
-// grid = rows.  Finds the bin of the current digit that holds the entry of rank `rank`
-// (counting from the largest key), extends the prefix, and clears the histogram for reuse.
-template <int PASS>
-__global__ __launch_bounds__(kBlock) void k_pick(RowDesc* __restrict__ desc, uint32_t* __restrict__ hist, uint32_t k) {
-    constexpr int nbins = 1 << digit_bits(PASS);
-    constexpr int per = nbins / kBlock;                 // 16, 4 or 2 bins per thread
-    __shared__ uint32_t part[kBlock];
-    __shared__ uint32_t above_of[kBlock];               // count in the bins above the thread's range
-    const uint32_t row = blockIdx.x;
-    uint32_t* __restrict__ h = hist + (size_t)row * kHistBins;
-    const uint32_t rank = PASS == 0 ? k : desc[row].rank;
-    uint32_t local[per];
-    uint32_t sum = 0;
-    bool bad = false;
-#pragma unroll
-    for (int q = 0; q < per; ++q) {
-        local[q] = h[threadIdx.x * per + q];
-        sum += local[q];
-        // keys at or above 0x7f800000 are Inf/NaN: the top 8 of the 12 first-digit bits all ones
-        if (PASS == 0) bad |= (local[q] != 0) && ((threadIdx.x * per + q) >= 0xff0);
-        h[threadIdx.x * per + q] = 0;
+// Picks the last digit (-> tau, how many ties are kept, how many there are) and collects the
+// indices of the listed entries whose key equals tau.  grid = (blocks, rows).
+__global__ __launch_bounds__(kBlock) void k_list_ties(uint32_t row0, RowDesc* __restrict__ desc,
+                                                       const uint2* __restrict__ list, uint32_t cap,
+                                                       const uint32_t* __restrict__ lhist,
+                                                       uint32_t* __restrict__ tiebuf) {
+    __shared__ uint32_t part[256], res[3];
+    const uint32_t row = row0 + blockIdx.y;
+    if (desc[row].mode != kList) return;
+    const uint32_t* __restrict__ hrow = lhist + (size_t)row * 3 * kHistBins;
+    const Pick p = block_pick(hrow + 2 * kHistBins, 1 << digit_bits(2), desc[row].sel_rank[2], part, res);
+    const uint32_t tau = desc[row].sel_prefix[2] | p.bin;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        desc[row].tau = tau;
+        desc[row].rank = p.rank_in;
+        desc[row].ties = p.count;
     }
-    part[threadIdx.x] = sum;
-    const int any_bad = __syncthreads_or(bad ? 1 : 0);
+    const uint32_t n = min(desc[row].n_cand, cap);
+    const uint2* __restrict__ in = list + (size_t)row * cap;
+    uint32_t* __restrict__ tb = tiebuf + (size_t)row * kTieCap;
+    for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < n; e += gridDim.x * kBlock) {
+        const uint2 kv = in[e];
+        if (kv.x == tau) {
+            const uint32_t pos = atomicAdd(&desc[row].n_ties, 1u);
+            if (pos < kTieCap) tb[pos] = kv.y;
+        }
+    }
+}
+
+// grid = rows.  Orders the collected ties by index, sets the cut-off, clears the list state and
+// predicts the next step's band.  Rows with more ties than the buffer holds go to the slow search.
+__global__ __launch_bounds__(kBlock) void k_list_finish(uint32_t row0, RowDesc* __restrict__ desc,
+                                                         uint32_t* __restrict__ lhist,
+                                                         const uint32_t* __restrict__ tiebuf) {
+    __shared__ uint32_t t_idx[kTieCap];
+    __shared__ uint32_t s_cut;
+    const uint32_t row = row0 + blockIdx.x;
+    if (desc[row].mode != kList) return;
+    uint32_t* __restrict__ hrow = lhist + (size_t)row * 3 * kHistBins;
+    for (int b = threadIdx.x; b < 3 * kHistBins; b += kBlock) hrow[b] = 0;
+    const uint32_t ties = desc[row].ties, want = desc[row].rank;
+    const bool fits = ties <= (uint32_t)kTieCap;
+    if (fits) {
+        const uint32_t* __restrict__ tb = tiebuf + (size_t)row * kTieCap;
+        for (uint32_t q = threadIdx.x; q < ties; q += kBlock) t_idx[q] = tb[q];
+        if (threadIdx.x == 0) s_cut = 0xffffffffu;
+        __syncthreads();
+        for (uint32_t q = threadIdx.x; q < ties; q += kBlock) {
+            const uint32_t mine = t_idx[q];
+            uint32_t below = 0;
+            for (uint32_t r = 0; r < ties; ++r) below += t_idx[r] < mine;
+            if (below + 1 == want) s_cut = mine;            // indices are distinct: one writer
+        }
+        __syncthreads();
+    }
     if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (int t = kBlock - 1; t >= 0; --t) {
-            above_of[t] = run;
-            run += part[t];
-        }
-    }
-    __syncthreads();
-    const uint32_t above = above_of[threadIdx.x];
-    if (above < rank && rank <= above + sum) {           // true for exactly one thread
-        uint32_t run = above, bin = threadIdx.x * per, ties = local[0];
-        bool done = false;
-#pragma unroll
-        for (int q = per - 1; q >= 0; --q) {
-            if (!done && run + local[q] >= rank) {
-                bin = threadIdx.x * per + q;
-                ties = local[q];
-                done = true;
-            }
-            if (!done) run += local[q];
-        }
         RowDesc r = desc[row];
-        if (PASS == 0) {
-            r.tau = 0;
-            r.nonfinite = any_bad ? 1u : 0u;
+        r.n_cand = 0;
+        r.n_ties = 0;
+        if (fits) {
+            r.cutoff = s_cut;
+            r.dense = 0;
+            r.nonfinite = r.nonfinite_acc;
+            r.nonfinite_acc = 0;
+            r.lo = r.tau > kBandMargin ? r.tau - kBandMargin : 0u;
+            r.hi = r.tau + kBandMargin;                     // tau < 2^31, no overflow
+            r.mode = kWarm;
+        } else {
+            r.mode = kSlow;
         }
-        r.tau |= bin << digit_shift(PASS);
-        r.rank = rank - run;
-        r.ties = ties;
         desc[row] = r;
     }
 }
 
-// Ties at the threshold are admitted by increasing index.  k_tie_count counts, per block span of
-// a row, the entries whose key equals tau; k_tie_pick then locates the rank-th of them.
+// General search for rows in kSlow mode, one block of 1024 threads per row: three radix digits
+// over the whole row, then the ties in index order.  Slow by design; only degenerate rows (a
+// threshold shared by thousands of entries) come here.  grid = rows.
 template <bool VEC>
-__global__ __launch_bounds__(kBlock) void k_tie_count(const float* __restrict__ src, size_t row_stride, uint32_t d,
-                                                       uint32_t ntiles, uint32_t tpb,
-                                                       const RowDesc* __restrict__ desc, uint32_t* __restrict__ cnt) {
-    __shared__ uint32_t wsum[4];
-    const uint32_t row = blockIdx.y;
-    const float* __restrict__ g = src + (size_t)row * row_stride;
-    const uint32_t tau = desc[row].tau;
-    const uint32_t t0 = blockIdx.x * tpb;
-    const uint32_t t1 = min(t0 + tpb, ntiles);
-    uint32_t c = 0;
-#pragma unroll 4
-    for (uint32_t t = t0; t < t1; ++t) {
-        const uint32_t j = t * kTile + threadIdx.x * 4;
-        const float4 a = ld4<VEC>(g, j, d);
-        c += (j < d && key_of(a.x) == tau) + (j + 1 < d && key_of(a.y) == tau) +
-             (j + 2 < d && key_of(a.z) == tau) + (j + 3 < d && key_of(a.w) == tau);
-    }
+__global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ src, size_t row_stride, uint32_t d,
+                                                       uint32_t row0, RowDesc* __restrict__ desc, uint32_t k) {
+    __shared__ uint32_t h[kHistBins];
+    __shared__ uint32_t part[256], res[3];
+    __shared__ uint32_t wtot[16];
+    __shared__ uint32_t s_cut, s_bad;
+    const uint32_t row = row0 + blockIdx.x;
+    if (desc[row].mode != kSlow) return;
+    const float* __restrict__ g = src + (size_t)blockIdx.x * row_stride;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t prefix = 0, rank = k, ties = 0;
+    if (tid == 0) s_bad = 0;
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = digit_shift(pass), nbins = 1 << digit_bits(pass);
+        const int hi_shift = pass == 0 ? 31 : digit_shift(pass - 1);
+        for (int b = tid; b < nbins; b += 1024) h[b] = 0;
+        __syncthreads();
+        for (uint32_t j = tid * 4; j < d; j += 4096) {
+            const float4 a = ld4<VEC>(g, j, d);
+            const float av[4] = {a.x, a.y, a.z, a.w};
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) c += __shfl_down(c, o, 64);
-    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = c;
-    __syncthreads();
-    if (threadIdx.x == 0) cnt[(size_t)row * gridDim.x + blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
-}
-
-// grid = rows.
-template <bool VEC>
-__global__ __launch_bounds__(kBlock) void k_tie_pick(const float* __restrict__ src, size_t row_stride, uint32_t d,
-                                                      uint32_t ntiles, uint32_t tpb, uint32_t nblk,
-                                                      RowDesc* __restrict__ desc, const uint32_t* __restrict__ cnt) {
-    __shared__ uint32_t s_blk, s_rank;
-    __shared__ uint32_t scan[kBlock];
-    __shared__ uint32_t s_found;
-    const uint32_t row = blockIdx.x;
-    const float* __restrict__ g = src + (size_t)row * row_stride;
-    const uint32_t tau = desc[row].tau;
-    if (threadIdx.x == 0) {
-        uint32_t want = desc[row].rank, run = 0, b = 0;
-        for (; b + 1 < nblk; ++b) {
-            const uint32_t c = cnt[(size_t)row * nblk + b];
-            if (run + c >= want) break;
-            run += c;
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t key = key_of(av[q]);
+                if (j + q < d && ((key ^ prefix) >> hi_shift) == 0) atomicAdd(&h[(key >> shift) & (nbins - 1)], 1u);
+            }
         }
-        s_blk = b;
-        s_rank = want - run;
-        s_found = 0xffffffffu;
+        __syncthreads();
+        if (pass == 0) {                       // keys >= 0x7f800000 (Inf/NaN) sit in the bins from 0xff0 up
+            bool bad = false;
+            for (int b = 0xff0 + (int)tid; b < kHistBins; b += 1024) bad |= h[b] != 0;
+            if (bad) s_bad = 1;
+        }
+        const Pick p = block_pick(h, nbins, rank, part, res);
+        prefix |= p.bin << shift;
+        rank = p.rank_in;
+        ties = p.count;
     }
+    // the rank-th entry with key == prefix, in index order
+    if (tid == 0) s_cut = 0xffffffffu;
     __syncthreads();
-    const uint32_t t0 = s_blk * tpb;
-    const uint32_t t1 = min(t0 + tpb, ntiles);
-    uint32_t want = s_rank;
-    for (uint32_t t = t0; t < t1; ++t) {           // uniform trip count and exit for the whole block
-        const uint32_t j = t * kTile + threadIdx.x * 4;
+    uint32_t seen = 0;
+    for (uint32_t base = 0; base < d; base += 4096) {          // uniform trip count and exit
+        const uint32_t j = base + tid * 4;
         const float4 a = ld4<VEC>(g, j, d);
-        const bool m0 = j < d && key_of(a.x) == tau, m1 = j + 1 < d && key_of(a.y) == tau;
-        const bool m2 = j + 2 < d && key_of(a.z) == tau, m3 = j + 3 < d && key_of(a.w) == tau;
+        const bool m0 = j < d && key_of(a.x) == prefix, m1 = j + 1 < d && key_of(a.y) == prefix;
+        const bool m2 = j + 2 < d && key_of(a.z) == prefix, m3 = j + 3 < d && key_of(a.w) == prefix;
         const uint32_t mine = m0 + m1 + m2 + m3;
-        scan[threadIdx.x] = mine;
-        __syncthreads();
-        if (threadIdx.x == 0) {                    // exclusive scan of 256 small counts
-            uint32_t run = 0;
-            for (int q = 0; q < kBlock; ++q) {
-                const uint32_t c = scan[q];
-                scan[q] = run;
-                run += c;
-            }
-            s_rank = run;                          // total in this tile
+        uint32_t incl = mine;                                   // inclusive scan inside the wave
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t up = __shfl_up(incl, o, 64);
+            if ((int)lane >= o) incl += up;
         }
+        if (lane == 63) wtot[wave] = incl;
         __syncthreads();
-        const uint32_t before = scan[threadIdx.x], total = s_rank;
-        if (want <= total) {
-            if (before < want && want <= before + mine) {
-                uint32_t need = want - before;     // 1-based among this thread's matches
-                uint32_t idx = j;
-                if (m0 && --need == 0) idx = j;
-                else if (m1 && --need == 0) idx = j + 1;
-                else if (m2 && --need == 0) idx = j + 2;
-                else idx = j + 3;
-                s_found = idx;
-            }
-            break;                                 // `want` and `total` are block-uniform
+        uint32_t before = seen, total = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < (int)wave) before += wtot[w];
+            total += wtot[w];
         }
-        want -= total;
+        before += incl - mine;
+        if (before < rank && rank <= before + mine) {
+            uint32_t need = rank - before, idx = j + 3;
+            if (m0 && --need == 0) idx = j;
+            else if (m1 && --need == 0) idx = j + 1;
+            else if (m2 && --need == 0) idx = j + 2;
+            s_cut = idx;
+        }
+        seen += total;
         __syncthreads();
+        if (seen >= rank) break;
     }
     __syncthreads();
-    if (threadIdx.x == 0) desc[row].cutoff = s_found;
+    if (tid == 0) {
+        RowDesc r = desc[row];
+        r.tau = prefix;
+        r.rank = rank;
+        r.ties = ties;
+        r.cutoff = s_cut;
+        r.dense = 1;
+        r.nonfinite = s_bad | r.nonfinite_acc;
+        r.nonfinite_acc = 0;
+        r.n_cand = 0;
+        r.n_ties = 0;
+        r.mode = kCold;
+        desc[row] = r;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -336,64 +646,102 @@ __device__ __forceinline__ float message_of(float g, uint32_t j, float scale, ui
 
 // ---------------------------------------------------------------------------------------------
 // Server compensation (Algorithm 1): v_j = e_j + (1/N) sum_i p^i_j, messages added in worker
-// order.  v overwrites e in place.  With SRV_L1 the kernel also emits per-block partial sums of
-// |v| (fp64) for the server's scaled-sign operator.  grid = blocks, each handling tpb tiles.
-// FROM_BITS (scaled-sign workers only) reads the packed sign bits instead of the gradients.
+// order; v goes to its own buffer.  With SRV_L1 the kernel also emits per-block partial sums of
+// |v| (fp64) for the server's scaled-sign operator.  grid = blocks; waves stride over wave tiles.
+//   WC == kSign     reads the packed sign bits instead of the gradients;
+//   WC == kTopk     reads each row's candidate bitmap and fetches only the flagged gradients,
+//                   testing them against (tau, cut-off); per-lane sums live in LDS;
+//   WC == kIdentity reads the gradients.
 // ---------------------------------------------------------------------------------------------
-template <int WC, bool FROM_BITS, bool SRV_L1, bool VEC>
+template <int WC, bool SRV_L1, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ grads, const uint64_t* __restrict__ bits,
-                                                       uint32_t nchunks, int N, uint32_t d, uint32_t ntiles,
-                                                       uint32_t tpb, float inv_n, const RowDesc* __restrict__ desc,
-                                                       float* __restrict__ e_inout, double* __restrict__ srv_partial) {
-    __shared__ double lds4[4];
-    const uint32_t t0 = blockIdx.x * tpb;
-    const uint32_t t1 = min(t0 + tpb, ntiles);
+                                                       int N, uint32_t d, uint32_t nwt, float inv_n,
+                                                       const RowDesc* __restrict__ desc, const float* __restrict__ e_in,
+                                                       float* __restrict__ v_out, double* __restrict__ srv_partial) {
+    __shared__ double lds_w[4];
+    __shared__ float accs[WC == kTopk ? 16 * kBlock : 1];
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     double l1 = 0.0;
-    for (uint32_t t = t0; t < t1; ++t) {
-        const uint32_t j = t * kTile + threadIdx.x * 4;
-        const float4 e = ld4<VEC>(e_inout, j, d);
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (FROM_BITS) {
-            const uint32_t chunk = t * 4 + wave;               // wave-uniform
-            if (chunk < nchunks) {
-#pragma unroll 4
-                for (int i = 0; i < N; ++i) {
-                    const uint64_t* __restrict__ w = bits + ((size_t)i * nchunks + chunk) * 4;
-                    const float s = desc[i].scale;
-                    acc.x = __fadd_rn(acc.x, ((w[0] >> lane) & 1) ? -s : s);
-                    acc.y = __fadd_rn(acc.y, ((w[1] >> lane) & 1) ? -s : s);
-                    acc.z = __fadd_rn(acc.z, ((w[2] >> lane) & 1) ? -s : s);
-                    acc.w = __fadd_rn(acc.w, ((w[3] >> lane) & 1) ? -s : s);
+    for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
+        const uint32_t j0 = t * kWaveTile + lane * 4;
+        float4 acc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (WC == kSign) {
+            for (int i = 0; i < N; ++i) {
+                const uint64_t* __restrict__ w = bits + ((size_t)i * nwt + t) * 16;   // wave-uniform
+                const float s = desc[i].scale;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    acc[u].x = __fadd_rn(acc[u].x, ((w[4 * u + 0] >> lane) & 1) ? -s : s);
+                    acc[u].y = __fadd_rn(acc[u].y, ((w[4 * u + 1] >> lane) & 1) ? -s : s);
+                    acc[u].z = __fadd_rn(acc[u].z, ((w[4 * u + 2] >> lane) & 1) ? -s : s);
+                    acc[u].w = __fadd_rn(acc[u].w, ((w[4 * u + 3] >> lane) & 1) ? -s : s);
                 }
             }
-        } else {
-#pragma unroll 4
+        } else if (WC == kTopk) {
+            float* my = accs + threadIdx.x;                    // slot b of this lane: my[b * kBlock]
+#pragma unroll
+            for (int b = 0; b < 16; ++b) my[b * kBlock] = 0.f;
             for (int i = 0; i < N; ++i) {
-                const float4 g = ld4<VEC>(grads + (size_t)i * d, j, d);
-                const float s = desc[i].scale;
+                const uint64_t* __restrict__ w = bits + ((size_t)i * nwt + t) * 16;   // wave-uniform
+                const float* __restrict__ gi = grads + (size_t)i * d;
                 const uint32_t tau = desc[i].tau, cut = desc[i].cutoff;
-                acc.x = __fadd_rn(acc.x, message_of<WC>(g.x, j, s, tau, cut));
-                acc.y = __fadd_rn(acc.y, message_of<WC>(g.y, j + 1, s, tau, cut));
-                acc.z = __fadd_rn(acc.z, message_of<WC>(g.z, j + 2, s, tau, cut));
-                acc.w = __fadd_rn(acc.w, message_of<WC>(g.w, j + 3, s, tau, cut));
+                uint32_t mask = 0;
+                if (desc[i].dense) {
+                    mask = 0xffffu;
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 16; ++b) mask |= (uint32_t)((w[b] >> lane) & 1) << b;
+                }
+                while (mask) {
+                    const int b = __builtin_ctz(mask);
+                    mask &= mask - 1;
+                    const uint32_t j = j0 + (b >> 2) * kChunk + (b & 3);
+                    if (j < d) {
+                        const float g = gi[j];
+                        const uint32_t key = key_of(g);
+                        if (key > tau || (key == tau && j <= cut)) my[b * kBlock] = __fadd_rn(my[b * kBlock], g);
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                acc[u] = make_float4(my[(4 * u) * kBlock], my[(4 * u + 1) * kBlock], my[(4 * u + 2) * kBlock],
+                                     my[(4 * u + 3) * kBlock]);
+        } else {
+            for (int i = 0; i < N; ++i) {
+                const float* __restrict__ gi = grads + (size_t)i * d;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float4 g = ld4<VEC, true>(gi, j0 + u * kChunk, d);
+                    acc[u].x = __fadd_rn(acc[u].x, g.x);
+                    acc[u].y = __fadd_rn(acc[u].y, g.y);
+                    acc[u].z = __fadd_rn(acc[u].z, g.z);
+                    acc[u].w = __fadd_rn(acc[u].w, g.w);
+                }
             }
         }
-        float4 v;
-        v.x = __fmaf_rn(acc.x, inv_n, e.x);
-        v.y = __fmaf_rn(acc.y, inv_n, e.y);
-        v.z = __fmaf_rn(acc.z, inv_n, e.z);
-        v.w = __fmaf_rn(acc.w, inv_n, e.w);
-        st4<VEC>(e_inout, j, d, v);
-        if (SRV_L1) {
-            if (j < d) l1 += (double)fabsf(v.x);
-            if (j + 1 < d) l1 += (double)fabsf(v.y);
-            if (j + 2 < d) l1 += (double)fabsf(v.z);
-            if (j + 3 < d) l1 += (double)fabsf(v.w);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = j0 + u * kChunk;
+            const float4 e = ld4<VEC>(e_in, j, d);
+            float4 v;
+            v.x = __fmaf_rn(acc[u].x, inv_n, e.x);
+            v.y = __fmaf_rn(acc[u].y, inv_n, e.y);
+            v.z = __fmaf_rn(acc[u].z, inv_n, e.z);
+            v.w = __fmaf_rn(acc[u].w, inv_n, e.w);
+            st4<VEC>(v_out, j, d, v);
+            if (SRV_L1) {
+                if (j < d) l1 += (double)fabsf(v.x);
+                if (j + 1 < d) l1 += (double)fabsf(v.y);
+                if (j + 2 < d) l1 += (double)fabsf(v.z);
+                if (j + 3 < d) l1 += (double)fabsf(v.w);
+            }
         }
     }
     if (SRV_L1) {
-        const double s = block_sum_f64(l1, lds4);
+        const double s = block_sum_f64(l1, lds_w);
         if (threadIdx.x == 0) srv_partial[blockIdx.x] = s;
     }
 }
@@ -401,16 +749,18 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 // Server compression + error update + broadcast + local immediate compensation (Algorithm 1):
 //   p_j = C_s(v)_j ; e_j <- v_j - p_j ; x_ij <- x_ij - lr * (p_j + (g_ij - p^i_j)).
-// v is read from (and e written to) the same buffer.  grid = tiles; a block owns 1024 columns
-// of every row.
+// Block b owns columns 1024 * (b / RG) .. of the rows of group b % RG (kUpdateRows rows each);
+// the group-0 block also writes e.  grid = column tiles * RG.
 // ---------------------------------------------------------------------------------------------
 template <int WC, int SC, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ grads, float* __restrict__ x,
-                                                    float* __restrict__ e_inout, int N, uint32_t d, float neg_lr,
+                                                    const float* __restrict__ v_in, float* __restrict__ e_out, int N,
+                                                    uint32_t RG, uint32_t d, float neg_lr,
                                                     const RowDesc* __restrict__ desc) {
-    const uint32_t j = blockIdx.x * kTile + threadIdx.x * 4;
+    const uint32_t tile = blockIdx.x / RG, rg = blockIdx.x % RG;
+    const uint32_t j = tile * kColTile + threadIdx.x * 4;
     if (j >= d) return;
-    const float4 v = ld4<VEC>(e_inout, j, d);
+    const float4 v = ld4<VEC>(v_in, j, d);
     const RowDesc* __restrict__ sd = desc + N;
     const float ss = sd->scale;
     const uint32_t stau = sd->tau, scut = sd->cutoff;
@@ -419,18 +769,38 @@ __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ gra
     p.y = message_of<SC>(v.y, j + 1, ss, stau, scut);
     p.z = message_of<SC>(v.z, j + 2, ss, stau, scut);
     p.w = message_of<SC>(v.w, j + 3, ss, stau, scut);
-    float4 en;
-    en.x = __fsub_rn(v.x, p.x);
-    en.y = __fsub_rn(v.y, p.y);
-    en.z = __fsub_rn(v.z, p.z);
-    en.w = __fsub_rn(v.w, p.w);
-    st4<VEC>(e_inout, j, d, en);
-#pragma unroll 4
-    for (int i = 0; i < N; ++i) {
-        const float* __restrict__ gi = grads + (size_t)i * d;
-        float* __restrict__ xi = x + (size_t)i * d;
-        const float4 g = ld4<VEC>(gi, j, d);
-        const float4 xv = ld4<VEC>(xi, j, d);
+    if (rg == 0) {
+        float4 en;
+        en.x = __fsub_rn(v.x, p.x);
+        en.y = __fsub_rn(v.y, p.y);
+        en.z = __fsub_rn(v.z, p.z);
+        en.w = __fsub_rn(v.w, p.w);
+        st4<VEC>(e_out, j, d, en);
+    }
+    const int i0 = (int)rg * kUpdateRows, i1 = min(N, i0 + kUpdateRows);
+    int i = i0;
+    for (; i + 2 <= i1; i += 2) {
+        float4 g[2], xv[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            g[u] = ld4<VEC, true>(grads + (size_t)(i + u) * d, j, d);
+            xv[u] = ld4<VEC, true>(x + (size_t)(i + u) * d, j, d);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const float s = desc[i + u].scale;
+            const uint32_t tau = desc[i + u].tau, cut = desc[i + u].cutoff;
+            float4 o;
+            o.x = __fmaf_rn(neg_lr, __fadd_rn(p.x, __fsub_rn(g[u].x, message_of<WC>(g[u].x, j, s, tau, cut))), xv[u].x);
+            o.y = __fmaf_rn(neg_lr, __fadd_rn(p.y, __fsub_rn(g[u].y, message_of<WC>(g[u].y, j + 1, s, tau, cut))), xv[u].y);
+            o.z = __fmaf_rn(neg_lr, __fadd_rn(p.z, __fsub_rn(g[u].z, message_of<WC>(g[u].z, j + 2, s, tau, cut))), xv[u].z);
+            o.w = __fmaf_rn(neg_lr, __fadd_rn(p.w, __fsub_rn(g[u].w, message_of<WC>(g[u].w, j + 3, s, tau, cut))), xv[u].w);
+            st4<VEC, true>(x + (size_t)(i + u) * d, j, d, o);
+        }
+    }
+    for (; i < i1; ++i) {
+        const float4 g = ld4<VEC, true>(grads + (size_t)i * d, j, d);
+        const float4 xv = ld4<VEC, true>(x + (size_t)i * d, j, d);
         const float s = desc[i].scale;
         const uint32_t tau = desc[i].tau, cut = desc[i].cutoff;
         float4 o;
@@ -438,7 +808,7 @@ __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ gra
         o.y = __fmaf_rn(neg_lr, __fadd_rn(p.y, __fsub_rn(g.y, message_of<WC>(g.y, j + 1, s, tau, cut))), xv.y);
         o.z = __fmaf_rn(neg_lr, __fadd_rn(p.z, __fsub_rn(g.z, message_of<WC>(g.z, j + 2, s, tau, cut))), xv.z);
         o.w = __fmaf_rn(neg_lr, __fadd_rn(p.w, __fsub_rn(g.w, message_of<WC>(g.w, j + 3, s, tau, cut))), xv.w);
-        st4<VEC>(xi, j, d, o);
+        st4<VEC, true>(x + (size_t)i * d, j, d, o);
     }
 }
 
@@ -448,12 +818,6 @@ __global__ __launch_bounds__(kBlock) void k_copy16(const uint4* __restrict__ src
     size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * kBlock;
     for (; i < n16; i += stride) dst[i] = src[i];
-}
-
-__global__ void k_fill_u32(uint32_t* __restrict__ p, size_t n, uint32_t v) {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) p[i] = v;
 }
 
 }  // namespace liec
