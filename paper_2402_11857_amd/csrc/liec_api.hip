@@ -77,7 +77,7 @@ struct liec_ctx {
     float* vbuf = nullptr;                     // [d]  compensated average v
     double* w_partial = nullptr;               // [N * row_blocks]
     double* s_partial = nullptr;               // [agg_blocks]
-    uint64_t* bits = nullptr;                  // [N * nwt * 16] sign bits or candidate bitmap
+    uint16_t* bits = nullptr;                  // [N * nwt * 64] sign bits or candidate bitmap
     uint2* list = nullptr;                     // [(N + 1) * cap] candidates (key, index)
     uint32_t* sure_partial = nullptr;          // [(N + 1) * part_stride]
     uint32_t* ghist = nullptr;                 // [(N + 1) * kHistBins]
@@ -143,7 +143,7 @@ struct Launcher {
 // asks for it, so the warm path costs one pass over the data and the others return at once.
 template <bool VEC>
 void launch_topk_select(Launcher& L, const float* src, size_t row_stride, uint32_t rows, uint32_t row0, uint32_t k,
-                        uint64_t* bits, uint32_t blocks, uint32_t cold_blocks, int slot0) {
+                        uint16_t* bits, uint32_t blocks, uint32_t cold_blocks, int slot0) {
     liec_ctx* c = L.c;
     const uint32_t d = (uint32_t)c->d;
     hipStream_t st = c->stream;
@@ -206,10 +206,12 @@ void launch_aggregate(Launcher& L, const float* grads, const float* e, bool srv_
 template <int WC, int SC, bool VEC>
 void launch_update(Launcher& L, const float* grads, float* x, float* e) {
     liec_ctx* c = L.c;
-    const uint32_t rg = (uint32_t)((c->N + kUpdateRows - 1) / kUpdateRows);
+    const uint32_t panel = c->ncol_tiles < kUpdatePanel ? c->ncol_tiles : kUpdatePanel;
+    const uint32_t npanels = (c->ncol_tiles + panel - 1) / panel;
+    const uint64_t blocks = (uint64_t)npanels * panel * (uint64_t)c->N;
     L.begin(S_UPDATE);
-    k_update<WC, SC, VEC><<<c->ncol_tiles * rg, kBlock, 0, c->stream>>>(grads, x, c->vbuf, e, c->N, rg, (uint32_t)c->d,
-                                                                         -c->lr, c->desc);
+    k_update<WC, SC, VEC><<<(uint32_t)blocks, kBlock, 0, c->stream>>>(grads, x, c->vbuf, e, c->N, panel, c->ncol_tiles,
+                                                                       (uint32_t)c->d, -c->lr, c->desc);
     L.end();
 }
 
@@ -302,6 +304,8 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     *out = nullptr;
     if (N < 1 || d < 1 || d >= ((int64_t)1 << 31) - ((int64_t)1 << 20)) return LIEC_EINVAL;
     if (!valid_comp((int)worker_comp) || !valid_comp((int)server_comp) || !finite_f(lr)) return LIEC_EINVAL;
+    // the update kernel launches one block per (1024-column tile, row): keep that under 2^31
+    if (((d + kColTile - 1) / kColTile + kUpdatePanel) * (int64_t)N >= ((int64_t)1 << 31)) return LIEC_EINVAL;
     if (worker_comp == LIEC_COMP_TOPK && (worker_k < 1 || worker_k > d)) return LIEC_EINVAL;
     if (server_comp == LIEC_COMP_TOPK && (server_k < 1 || server_k > d)) return LIEC_EINVAL;
 
@@ -340,7 +344,7 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     if (e == hipSuccess) e = dev_alloc(c, &c->vbuf, (size_t)c->nwt * kWaveTile);
     if (e == hipSuccess) e = dev_alloc(c, &c->w_partial, (size_t)N * c->row_blocks);
     if (e == hipSuccess) e = dev_alloc(c, &c->s_partial, (size_t)c->agg_blocks);
-    if (e == hipSuccess && worker_comp != LIEC_COMP_IDENTITY) e = dev_alloc(c, &c->bits, (size_t)N * c->nwt * 16);
+    if (e == hipSuccess && worker_comp != LIEC_COMP_IDENTITY) e = dev_alloc(c, &c->bits, (size_t)N * c->nwt * 64);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->list, rows * c->cap);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->sure_partial, rows * c->part_stride);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->ghist, rows * kHistBins);

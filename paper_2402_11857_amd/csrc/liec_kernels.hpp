@@ -21,7 +21,7 @@ constexpr int kHistBins = 4096;         // widest radix digit (12 bits)
 constexpr int kStage = 512;             // per-wave LDS staging slots of the candidate filter
 constexpr int kTieCap = 4096;           // ties at the threshold the fast path resolves
 constexpr uint32_t kBandMargin = 1u << 18;   // half width, in key units, of the predicted band
-constexpr int kUpdateRows = 4;          // rows per block of the update kernel
+constexpr uint32_t kUpdatePanel = 2048; // column tiles per panel of the update kernel
 
 enum Comp : int { kIdentity = 0, kSign = 1, kTopk = 2 };
 
@@ -197,14 +197,15 @@ __device__ __forceinline__ Pick block_pick(const uint32_t* __restrict__ h, int n
 
 // ---------------------------------------------------------------------------------------------
 // Scaled sign, worker side (Definition 4): per-row partial sums of |g| in fp64 and the sign bits
-// of the row.  Bit layout: wave tile t of row i owns 16 words bits[(i*nwt + t)*16 + 4u + q];
-// bit l of that word is (g[1024t + 256u + 4l + q] < 0).
+// of the row.  Bit layout ("lane-major"): wave tile t of row i owns 64 half-words
+// bits[(i*nwt + t)*64 + l]; bit 4u + q of half-word l is (g[1024t + 256u + 4l + q] < 0), i.e. every
+// lane keeps the 16 bits of the 16 columns it owns, and a wave reads or writes 128 contiguous bytes.
 // grid = (blocks per row, rows); waves stride over the row's wave tiles.
 // ---------------------------------------------------------------------------------------------
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_l1_bits(const float* __restrict__ src, size_t row_stride, uint32_t d,
                                                      uint32_t nwt, double* __restrict__ partial,
-                                                     uint64_t* __restrict__ bits) {
+                                                     uint16_t* __restrict__ bits) {
     __shared__ double lds_w[4];
     const uint32_t row = blockIdx.y;
     const float* __restrict__ g = src + (size_t)row * row_stride;
@@ -214,21 +215,19 @@ __global__ __launch_bounds__(kBlock) void k_l1_bits(const float* __restrict__ sr
         float4 a[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
-        uint64_t word = 0;
+        uint32_t m = 0;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             acc += (double)fabsf(a[u].x);
             acc += (double)fabsf(a[u].y);
             acc += (double)fabsf(a[u].z);
             acc += (double)fabsf(a[u].w);
-            const uint64_t b0 = __ballot(a[u].x < 0.f), b1 = __ballot(a[u].y < 0.f);
-            const uint64_t b2 = __ballot(a[u].z < 0.f), b3 = __ballot(a[u].w < 0.f);
-            word = lane == 4 * u ? b0 : word;
-            word = lane == 4 * u + 1 ? b1 : word;
-            word = lane == 4 * u + 2 ? b2 : word;
-            word = lane == 4 * u + 3 ? b3 : word;
+            m |= (a[u].x < 0.f ? 1u : 0u) << (4 * u);
+            m |= (a[u].y < 0.f ? 1u : 0u) << (4 * u + 1);
+            m |= (a[u].z < 0.f ? 1u : 0u) << (4 * u + 2);
+            m |= (a[u].w < 0.f ? 1u : 0u) << (4 * u + 3);
         }
-        if (lane < 16) bits[((size_t)row * nwt + t) * 16 + lane] = word;
+        bits[((size_t)row * nwt + t) * 64 + lane] = (uint16_t)m;
     }
     const double s = block_sum_f64(acc, lds_w);
     if (threadIdx.x == 0) partial[(size_t)row * gridDim.x + blockIdx.x] = s;
@@ -256,7 +255,8 @@ __global__ __launch_bounds__(kBlock) void k_l1_final(const double* __restrict__ 
 // among its ties are found without sorting:
 //   1. k_filter streams the row once against a band [lo, hi) of keys expected to hold tau:
 //      keys >= hi are only counted, keys inside the band are appended to a candidate list
-//      (key, index), and a bitmap of "key >= lo" is written for the aggregation kernel.
+//      (key, index), and a bitmap of "key >= lo" (same layout as the sign bits) is written for
+//      the aggregation kernel.
 //      The band is predicted from the previous step's tau (kWarm); when there is none, or the
 //      prediction fails (k_check), the band is the first-radix-digit bin holding rank k, found by
 //      k_hist0 + k_pick_band over the whole row (kCold -> kColdBand), and the row is filtered again.
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(kBlock) void k_l1_final(const double* __restrict__ 
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src, size_t row_stride, uint32_t d,
                                                     uint32_t nwt, uint32_t row0, RowDesc* __restrict__ desc,
-                                                    uint32_t expect_mode, uint64_t* __restrict__ bits,
+                                                    uint32_t expect_mode, uint16_t* __restrict__ bits,
                                                     uint2* __restrict__ list, uint32_t cap,
                                                     uint32_t* __restrict__ sure_partial) {
     __shared__ uint2 stage[4][kStage];
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
         float4 a[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
-        uint64_t word = 0;
+        uint32_t word = 0;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
@@ -301,9 +301,10 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
                 const bool valid = j + q < d;
                 keys[q] = key;
                 bad |= valid && key >= 0x7f800000u;
-                const uint64_t bl = __ballot(valid && key >= lo);
+                const bool in_lo = valid && key >= lo;
+                const uint64_t bl = __ballot(in_lo);
                 const uint64_t bh = __ballot(valid && key >= hi);
-                word = lane == 4 * u + q ? bl : word;
+                word |= (in_lo ? 1u : 0u) << (4 * u + q);
                 nsure += __popcll(bh);
                 bc[q] = bl & ~bh;
                 m += __popcll(bc[q]);
@@ -328,7 +329,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
                 cnt += m;
             }
         }
-        if (bits && lane < 16) bits[((size_t)blockIdx.y * nwt + t) * 16 + lane] = word;
+        if (bits) bits[((size_t)blockIdx.y * nwt + t) * 64 + lane] = (uint16_t)word;
     }
     if (cnt) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -631,6 +632,21 @@ __global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ 
     }
 }
 
+// acc[u].{x,y,z,w} += (bit 4u + q of m) ? -s : s  -- one scaled-sign message, 16 columns of a lane.
+__device__ __forceinline__ float signed_scale(uint32_t m, int b, float s) {
+    // bit b of m moved to the sign position and merged over +s (s >= 0)
+    return __uint_as_float(((m << (31 - b)) & 0x80000000u) | __float_as_uint(s));
+}
+__device__ __forceinline__ void add_signed(float4 (&acc)[4], uint32_t m, float s) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        acc[u].x = __fadd_rn(acc[u].x, signed_scale(m, 4 * u + 0, s));
+        acc[u].y = __fadd_rn(acc[u].y, signed_scale(m, 4 * u + 1, s));
+        acc[u].z = __fadd_rn(acc[u].z, signed_scale(m, 4 * u + 2, s));
+        acc[u].w = __fadd_rn(acc[u].w, signed_scale(m, 4 * u + 3, s));
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Worker message element p^i_j rebuilt from g_ij and the row's descriptor.
 // ---------------------------------------------------------------------------------------------
@@ -654,7 +670,7 @@ __device__ __forceinline__ float message_of(float g, uint32_t j, float scale, ui
 //   WC == kIdentity reads the gradients.
 // ---------------------------------------------------------------------------------------------
 template <int WC, bool SRV_L1, bool VEC>
-__global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ grads, const uint64_t* __restrict__ bits,
+__global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ grads, const uint16_t* __restrict__ bits,
                                                        int N, uint32_t d, uint32_t nwt, float inv_n,
                                                        const RowDesc* __restrict__ desc, const float* __restrict__ e_in,
                                                        float* __restrict__ v_out, double* __restrict__ srv_partial) {
@@ -668,32 +684,27 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
 #pragma unroll
         for (int u = 0; u < 4; ++u) acc[u] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (WC == kSign) {
-            for (int i = 0; i < N; ++i) {
-                const uint64_t* __restrict__ w = bits + ((size_t)i * nwt + t) * 16;   // wave-uniform
-                const float s = desc[i].scale;
+            const uint16_t* __restrict__ bw = bits + (size_t)t * 64 + lane;
+            const size_t brow = (size_t)nwt * 64;
+            int i = 0;
+            for (; i + 8 <= N; i += 8) {                       // 8 rows of bits in flight
+                uint32_t m[8];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    acc[u].x = __fadd_rn(acc[u].x, ((w[4 * u + 0] >> lane) & 1) ? -s : s);
-                    acc[u].y = __fadd_rn(acc[u].y, ((w[4 * u + 1] >> lane) & 1) ? -s : s);
-                    acc[u].z = __fadd_rn(acc[u].z, ((w[4 * u + 2] >> lane) & 1) ? -s : s);
-                    acc[u].w = __fadd_rn(acc[u].w, ((w[4 * u + 3] >> lane) & 1) ? -s : s);
-                }
+                for (int r = 0; r < 8; ++r) m[r] = bw[(size_t)(i + r) * brow];
+#pragma unroll
+                for (int r = 0; r < 8; ++r) add_signed(acc, m[r], desc[i + r].scale);
             }
+            for (; i < N; ++i) add_signed(acc, bw[(size_t)i * brow], desc[i].scale);
         } else if (WC == kTopk) {
             float* my = accs + threadIdx.x;                    // slot b of this lane: my[b * kBlock]
 #pragma unroll
             for (int b = 0; b < 16; ++b) my[b * kBlock] = 0.f;
+            const uint16_t* __restrict__ bw = bits + (size_t)t * 64 + lane;
+            const size_t brow = (size_t)nwt * 64;
             for (int i = 0; i < N; ++i) {
-                const uint64_t* __restrict__ w = bits + ((size_t)i * nwt + t) * 16;   // wave-uniform
                 const float* __restrict__ gi = grads + (size_t)i * d;
                 const uint32_t tau = desc[i].tau, cut = desc[i].cutoff;
-                uint32_t mask = 0;
-                if (desc[i].dense) {
-                    mask = 0xffffu;
-                } else {
-#pragma unroll
-                    for (int b = 0; b < 16; ++b) mask |= (uint32_t)((w[b] >> lane) & 1) << b;
-                }
+                uint32_t mask = desc[i].dense ? 0xffffu : (uint32_t)bw[(size_t)i * brow];
                 while (mask) {
                     const int b = __builtin_ctz(mask);
                     mask &= mask - 1;
@@ -749,17 +760,26 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 // Server compression + error update + broadcast + local immediate compensation (Algorithm 1):
 //   p_j = C_s(v)_j ; e_j <- v_j - p_j ; x_ij <- x_ij - lr * (p_j + (g_ij - p^i_j)).
-// Block b owns columns 1024 * (b / RG) .. of the rows of group b % RG (kUpdateRows rows each);
-// the group-0 block also writes e.  grid = column tiles * RG.
+// One block = 1024 columns of one row.  Blocks are ordered panel by panel (a panel is `panel`
+// consecutive column tiles), inside a panel row by row, so every row is walked in long contiguous
+// runs while the panel's slice of v stays in cache for the N rows that reuse it; the row-0 block of
+// a tile also writes e.  grid = number of panels * panel * N.
 // ---------------------------------------------------------------------------------------------
 template <int WC, int SC, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ grads, float* __restrict__ x,
                                                     const float* __restrict__ v_in, float* __restrict__ e_out, int N,
-                                                    uint32_t RG, uint32_t d, float neg_lr,
+                                                    uint32_t panel, uint32_t ncol_tiles, uint32_t d, float neg_lr,
                                                     const RowDesc* __restrict__ desc) {
-    const uint32_t tile = blockIdx.x / RG, rg = blockIdx.x % RG;
+    const uint32_t per_panel = panel * (uint32_t)N;
+    const uint32_t pn = blockIdx.x / per_panel, r = blockIdx.x % per_panel;
+    const uint32_t i = r / panel, tile = pn * panel + r % panel;
+    if (tile >= ncol_tiles) return;
     const uint32_t j = tile * kColTile + threadIdx.x * 4;
     if (j >= d) return;
+    const float* __restrict__ gi = grads + (size_t)i * d;
+    float* __restrict__ xi = x + (size_t)i * d;
+    const float4 g = ld4<VEC, true>(gi, j, d);
+    const float4 xv = ld4<VEC, true>(xi, j, d);
     const float4 v = ld4<VEC>(v_in, j, d);
     const RowDesc* __restrict__ sd = desc + N;
     const float ss = sd->scale;
@@ -769,7 +789,7 @@ __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ gra
     p.y = message_of<SC>(v.y, j + 1, ss, stau, scut);
     p.z = message_of<SC>(v.z, j + 2, ss, stau, scut);
     p.w = message_of<SC>(v.w, j + 3, ss, stau, scut);
-    if (rg == 0) {
+    if (i == 0) {
         float4 en;
         en.x = __fsub_rn(v.x, p.x);
         en.y = __fsub_rn(v.y, p.y);
@@ -777,39 +797,14 @@ __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ gra
         en.w = __fsub_rn(v.w, p.w);
         st4<VEC>(e_out, j, d, en);
     }
-    const int i0 = (int)rg * kUpdateRows, i1 = min(N, i0 + kUpdateRows);
-    int i = i0;
-    for (; i + 2 <= i1; i += 2) {
-        float4 g[2], xv[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            g[u] = ld4<VEC, true>(grads + (size_t)(i + u) * d, j, d);
-            xv[u] = ld4<VEC, true>(x + (size_t)(i + u) * d, j, d);
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const float s = desc[i + u].scale;
-            const uint32_t tau = desc[i + u].tau, cut = desc[i + u].cutoff;
-            float4 o;
-            o.x = __fmaf_rn(neg_lr, __fadd_rn(p.x, __fsub_rn(g[u].x, message_of<WC>(g[u].x, j, s, tau, cut))), xv[u].x);
-            o.y = __fmaf_rn(neg_lr, __fadd_rn(p.y, __fsub_rn(g[u].y, message_of<WC>(g[u].y, j + 1, s, tau, cut))), xv[u].y);
-            o.z = __fmaf_rn(neg_lr, __fadd_rn(p.z, __fsub_rn(g[u].z, message_of<WC>(g[u].z, j + 2, s, tau, cut))), xv[u].z);
-            o.w = __fmaf_rn(neg_lr, __fadd_rn(p.w, __fsub_rn(g[u].w, message_of<WC>(g[u].w, j + 3, s, tau, cut))), xv[u].w);
-            st4<VEC, true>(x + (size_t)(i + u) * d, j, d, o);
-        }
-    }
-    for (; i < i1; ++i) {
-        const float4 g = ld4<VEC, true>(grads + (size_t)i * d, j, d);
-        const float4 xv = ld4<VEC, true>(x + (size_t)i * d, j, d);
-        const float s = desc[i].scale;
-        const uint32_t tau = desc[i].tau, cut = desc[i].cutoff;
-        float4 o;
-        o.x = __fmaf_rn(neg_lr, __fadd_rn(p.x, __fsub_rn(g.x, message_of<WC>(g.x, j, s, tau, cut))), xv.x);
-        o.y = __fmaf_rn(neg_lr, __fadd_rn(p.y, __fsub_rn(g.y, message_of<WC>(g.y, j + 1, s, tau, cut))), xv.y);
-        o.z = __fmaf_rn(neg_lr, __fadd_rn(p.z, __fsub_rn(g.z, message_of<WC>(g.z, j + 2, s, tau, cut))), xv.z);
-        o.w = __fmaf_rn(neg_lr, __fadd_rn(p.w, __fsub_rn(g.w, message_of<WC>(g.w, j + 3, s, tau, cut))), xv.w);
-        st4<VEC, true>(x + (size_t)i * d, j, d, o);
-    }
+    const float s = desc[i].scale;
+    const uint32_t tau = desc[i].tau, cut = desc[i].cutoff;
+    float4 o;
+    o.x = __fmaf_rn(neg_lr, __fadd_rn(p.x, __fsub_rn(g.x, message_of<WC>(g.x, j, s, tau, cut))), xv.x);
+    o.y = __fmaf_rn(neg_lr, __fadd_rn(p.y, __fsub_rn(g.y, message_of<WC>(g.y, j + 1, s, tau, cut))), xv.y);
+    o.z = __fmaf_rn(neg_lr, __fadd_rn(p.z, __fsub_rn(g.z, message_of<WC>(g.z, j + 2, s, tau, cut))), xv.z);
+    o.w = __fmaf_rn(neg_lr, __fadd_rn(p.w, __fsub_rn(g.w, message_of<WC>(g.w, j + 3, s, tau, cut))), xv.w);
+    st4<VEC, true>(xi, j, d, o);
 }
 
 // Plain device copy (128-bit), used to measure the achievable streaming bandwidth next to the
