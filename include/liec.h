@@ -125,13 +125,16 @@ liec_status liec_get_worker_desc(liec_ctx *ctx, float *scales, double *l1, uint3
 
 /*
  * Per-kernel timing with HIP events on the context's stream, for measurement.
- * liec_profile_begin(ctx, max_steps) makes every following liec_step record an
- * event before and after each kernel it launches (at most max_steps steps are
- * recorded, later ones run unrecorded).  liec_profile_end synchronises, stops
- * recording and fills HOST arrays: names[s] (static strings), total_ms[s] and
- * launches[s] for s < *n_slots (in: capacity of the arrays, out: slots used).
+ * liec_profile_begin(ctx, max_steps, update_only) makes every following
+ * liec_step record an event before and after each kernel it launches, or, with
+ * update_only != 0, around the update kernel alone (the kernel that moves most
+ * of the bytes; two events per step disturb the step least).  At most
+ * max_steps steps are recorded, later ones run unrecorded.  liec_profile_end
+ * synchronises, stops recording and fills HOST arrays: names[s] (static
+ * strings), total_ms[s] and launches[s] for s < *n_slots (in: capacity of the
+ * arrays, out: slots used).
  */
-liec_status liec_profile_begin(liec_ctx *ctx, int32_t max_steps);
+liec_status liec_profile_begin(liec_ctx *ctx, int32_t max_steps, int32_t update_only);
 liec_status liec_profile_end(liec_ctx *ctx, int32_t *n_slots, const char **names, double *total_ms,
                              int64_t *launches);
 

@@ -73,7 +73,7 @@ def lib():
         L.liec_get_worker_desc.argtypes = [vp, ctypes.POINTER(f32), ctypes.POINTER(ctypes.c_double),
                                            ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(i64)]
         L.liec_profile_begin.restype = ctypes.c_int
-        L.liec_profile_begin.argtypes = [vp, i32]
+        L.liec_profile_begin.argtypes = [vp, i32, i32]
         L.liec_profile_end.restype = ctypes.c_int
         L.liec_profile_end.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_char_p),
                                        ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
@@ -191,8 +191,8 @@ class LiecContext:
     def scratch_bytes(self) -> int:
         return int(lib().liec_scratch_bytes(self._h))
 
-    def profile_begin(self, max_steps: int) -> None:
-        _check(lib().liec_profile_begin(self._h, max_steps), "liec_profile_begin")
+    def profile_begin(self, max_steps: int, update_only: bool = False) -> None:
+        _check(lib().liec_profile_begin(self._h, max_steps, 1 if update_only else 0), "liec_profile_begin")
 
     def profile_end(self) -> Dict[str, Tuple[float, int]]:
         cap = 32

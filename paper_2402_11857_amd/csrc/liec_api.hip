@@ -87,6 +87,7 @@ struct liec_ctx {
 
     // profiling
     bool profiling = false;
+    bool prof_update_only = false;
     int32_t prof_steps_left = 0;
     std::vector<ProfEvent> prof;
 };
@@ -121,8 +122,10 @@ bool valid_comp(int c) { return c == LIEC_COMP_IDENTITY || c == LIEC_COMP_SIGN |
 struct Launcher {
     liec_ctx* c;
     bool ok = true;
+    bool recording = false;
     void begin(int slot) {
-        if (!c->profiling) return;
+        recording = c->profiling && (!c->prof_update_only || slot == S_UPDATE);
+        if (!recording) return;
         ProfEvent ev{nullptr, nullptr, slot};
         if (hipEventCreate(&ev.start) != hipSuccess || hipEventCreate(&ev.stop) != hipSuccess) {
             ok = false;
@@ -133,7 +136,7 @@ struct Launcher {
     }
     void end() {
         if (hipGetLastError() != hipSuccess) ok = false;
-        if (!c->profiling || c->prof.empty()) return;
+        if (!recording || c->prof.empty()) return;
         if (hipEventRecord(c->prof.back().stop, c->stream) != hipSuccess) ok = false;
     }
 };
@@ -458,11 +461,12 @@ liec_status liec_get_worker_desc(liec_ctx* c, float* scales, double* l1, uint32_
     return LIEC_OK;
 }
 
-liec_status liec_profile_begin(liec_ctx* c, int32_t max_steps) {
+liec_status liec_profile_begin(liec_ctx* c, int32_t max_steps, int32_t update_only) {
     if (!c || max_steps < 1) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
     drop_prof(c);
     c->profiling = true;
+    c->prof_update_only = update_only != 0;
     c->prof_steps_left = max_steps;
     return LIEC_OK;
 }

@@ -20,7 +20,7 @@ constexpr int kColTile = 1024;          // columns per block of the update kerne
 constexpr int kHistBins = 4096;         // widest radix digit (12 bits)
 constexpr int kStage = 512;             // per-wave LDS staging slots of the candidate filter
 constexpr int kTieCap = 4096;           // ties at the threshold the fast path resolves
-constexpr uint32_t kBandMargin = 1u << 18;   // half width, in key units, of the predicted band
+constexpr uint32_t kBandMargin = 1u << 18;   // least half width, in key units, of the predicted band (about 2 % in value)
 constexpr uint32_t kUpdatePanel = 2048; // column tiles per panel of the update kernel
 
 enum Comp : int { kIdentity = 0, kSign = 1, kTopk = 2 };
@@ -51,7 +51,9 @@ struct RowDesc {
     uint32_t dense;        // the row's candidate bitmap is not valid: test every column
     uint32_t sel_prefix[3];  // list select: key prefix before digit p
     uint32_t sel_rank[3];    // list select: rank inside the prefix before digit p
-    uint32_t pad;
+    uint32_t prev_tau;     // tau of the step before (valid when have_prev)
+    uint32_t have_prev;
+    uint32_t was_cold;     // this step's band came from the first-digit histogram, not from a prediction
 };
 
 // Radix digits of the 31-bit magnitude key, most significant first.
@@ -419,6 +421,7 @@ __global__ __launch_bounds__(kBlock) void k_pick_band(uint32_t row0, RowDesc* __
         r.lo = p.bin << 19;
         r.hi = (p.bin + 1) << 19;            // 0x80000000 for the top bin: no key reaches it
         r.n_cand = 0;
+        r.was_cold = 1;
         r.mode = p.count <= cap ? kColdBand : kSlow;
         desc[row] = r;
     }
@@ -437,10 +440,10 @@ __global__ __launch_bounds__(kBlock) void k_list_hist(uint32_t row0, RowDesc* __
     if (desc[row].mode != kList) return;
     uint32_t* __restrict__ hrow = lhist + (size_t)row * 3 * kHistBins;
     uint32_t prefix = 0;
-    if (P > 0) {
-        const Pick p = block_pick(hrow + (P - 1) * kHistBins, 1 << digit_bits(P - 1), desc[row].sel_rank[P - 1], part,
-                                  res);
-        prefix = desc[row].sel_prefix[P - 1] | (p.bin << digit_shift(P - 1));
+    if constexpr (P > 0) {
+        constexpr int Q = P - 1;
+        const Pick p = block_pick(hrow + Q * kHistBins, 1 << digit_bits(Q), desc[row].sel_rank[Q], part, res);
+        prefix = desc[row].sel_prefix[Q] | (p.bin << digit_shift(Q));
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             desc[row].sel_prefix[P] = prefix;
             desc[row].sel_rank[P] = p.rank_in;
@@ -494,6 +497,26 @@ __global__ __launch_bounds__(kBlock) void k_list_ties(uint32_t row0, RowDesc* __
     }
 }
 
+// Band for the next step: centred on tau extrapolated by its last change, at least kBandMargin wide
+// on either side, wider when tau is moving or when the last prediction failed.
+__device__ __forceinline__ void predict_band(RowDesc& r) {
+    const int64_t tau = (int64_t)r.tau;
+    const int64_t delta = r.have_prev ? tau - (int64_t)r.prev_tau : 0;
+    int64_t margin = 2 * (delta < 0 ? -delta : delta);
+    if (margin < (int64_t)kBandMargin) margin = kBandMargin;
+    if (r.was_cold && margin < 4 * (int64_t)kBandMargin) margin = 4 * (int64_t)kBandMargin;
+    if (margin > (int64_t)1 << 26) margin = (int64_t)1 << 26;
+    int64_t centre = tau + delta;
+    if (centre < 0) centre = 0;
+    if (centre > 0x7fffffffll) centre = 0x7fffffffll;
+    const int64_t lo = centre - margin, hi = centre + margin;
+    r.lo = lo < 0 ? 0u : (uint32_t)lo;
+    r.hi = hi > 0x80000000ll ? 0x80000000u : (uint32_t)hi;
+    r.prev_tau = r.tau;
+    r.have_prev = 1;
+    r.was_cold = 0;
+}
+
 // grid = rows.  Orders the collected ties by index, sets the cut-off, clears the list state and
 // predicts the next step's band.  Rows with more ties than the buffer holds go to the slow search.
 __global__ __launch_bounds__(kBlock) void k_list_finish(uint32_t row0, RowDesc* __restrict__ desc,
@@ -529,8 +552,7 @@ __global__ __launch_bounds__(kBlock) void k_list_finish(uint32_t row0, RowDesc* 
             r.dense = 0;
             r.nonfinite = r.nonfinite_acc;
             r.nonfinite_acc = 0;
-            r.lo = r.tau > kBandMargin ? r.tau - kBandMargin : 0u;
-            r.hi = r.tau + kBandMargin;                     // tau < 2^31, no overflow
+            predict_band(r);
             r.mode = kWarm;
         } else {
             r.mode = kSlow;
@@ -627,6 +649,8 @@ __global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ 
         r.nonfinite_acc = 0;
         r.n_cand = 0;
         r.n_ties = 0;
+        r.have_prev = 0;
+        r.was_cold = 0;
         r.mode = kCold;
         desc[row] = r;
     }
