@@ -71,7 +71,7 @@ typedef struct {
  * (the form Algorithm 1 is written in), launching on the default (null) stream.
  *   out         receives the context (host pointer to a host pointer)
  *   N >= 1      number of simulated workers (rows)
- *   1 <= d < 2^31 - 2^20   model dimension (columns); also N * (d / 1024 + 2049) < 2^31
+ *   1 <= d < 2^31 - 2^20   model dimension (columns); also N * (d / 1024 + 4097) < 2^31
  *   k           kept entries for LIEC_COMP_TOPK, 1 <= k <= d; ignored otherwise
  *   lr          learning rate eta, finite
  * Allocates O(N * d / 8 + d) bytes of device scratch.  Uses the current HIP device.

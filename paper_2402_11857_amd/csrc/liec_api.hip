@@ -64,12 +64,12 @@ struct liec_ctx {
 
     uint32_t nwt = 0;                          // wave tiles of 1024 columns per row
     uint32_t ncol_tiles = 0;                   // column tiles of the update kernel
-    uint32_t row_blocks = 0;                   // streaming kernels over grads: grid (row_blocks, N)
-    uint32_t srv_blocks = 0;                   // streaming kernels over one length-d vector
+    uint32_t row_blocks = 0;                   // scaled-sign pass over grads: grid (row_blocks, N)
+    uint32_t filter_row_blocks = 0, filter_srv_blocks = 0;   // top-k filter pass (fewer, longer-lived blocks)
     uint32_t agg_blocks = 0;                   // aggregation kernel
     uint32_t cold_row_blocks = 0, cold_srv_blocks = 0;   // first-digit histogram (rarely needed)
     uint32_t list_blocks = 0;                  // kernels over the candidate lists
-    uint32_t part_stride = 0;                  // max(row_blocks, srv_blocks)
+    uint32_t part_stride = 0;                  // max(filter_row_blocks, filter_srv_blocks)
     uint32_t cap = 0;                          // candidate list capacity per row
 
     // device scratch
@@ -243,8 +243,8 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
         k_l1_final<<<c->N, kBlock, 0, c->stream>>>(c->w_partial, c->row_blocks, d, c->desc);
         L.end();
     } else if (c->worker_comp == kTopk) {
-        launch_topk_select<VEC>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, c->bits, c->row_blocks,
-                                c->cold_row_blocks, S_W_SEL);
+        launch_topk_select<VEC>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, c->bits,
+                                c->filter_row_blocks, c->cold_row_blocks, S_W_SEL);
     }
 
     // ---- server: v = e + mean_i p^i, then the descriptor of C_s(v) ---------------------------------
@@ -260,8 +260,8 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
         L.end();
     } else if (c->server_comp == kTopk) {
         // v is always 16-byte aligned scratch, but d % 4 decides whether 128-bit loads stay in bounds
-        launch_topk_select<VEC>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, nullptr, c->srv_blocks,
-                                c->cold_srv_blocks, S_S_SEL);
+        launch_topk_select<VEC>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, nullptr,
+                                c->filter_srv_blocks, c->cold_srv_blocks, S_S_SEL);
     }
 
     // ---- p = C_s(v), e <- v - p, x^i <- x^i - lr (p + (g_i - p^i)) ---------------------------------
@@ -333,12 +333,19 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     c->ncol_tiles = (uint32_t)((d + kColTile - 1) / kColTile);
     const uint32_t blk_iters = (c->nwt + 3) / 4;               // block iterations that cover one row
     auto clampu = [](uint32_t v, uint32_t lo, uint32_t hi) { return v < lo ? lo : (v > hi ? hi : v); };
-    c->row_blocks = clampu(32768u / un, 1u, blk_iters);
-    c->srv_blocks = clampu(8192u, 1u, blk_iters);
-    c->agg_blocks = clampu(16384u, 1u, blk_iters);
+    // Many short-lived blocks stream best here; give every block the same whole number of iterations.
+    auto balanced = [&](uint32_t max_blocks) {
+        const uint32_t per = (blk_iters + max_blocks - 1) / max_blocks;
+        return (blk_iters + per - 1) / per;
+    };
+    c->row_blocks = balanced(clampu(262144u / un, 1u, 16384u));
+    // the filter pays one list flush (a global atomic) per wave: fewer, longer-lived blocks
+    c->filter_row_blocks = balanced(clampu(32768u / un, 1u, 8192u));
+    c->filter_srv_blocks = balanced(8192u);
+    c->agg_blocks = balanced(16384u);
     c->cold_row_blocks = clampu(2048u / un, 1u, blk_iters);
     c->cold_srv_blocks = clampu(2048u, 1u, blk_iters);
-    c->part_stride = c->row_blocks > c->srv_blocks ? c->row_blocks : c->srv_blocks;
+    c->part_stride = c->filter_row_blocks > c->filter_srv_blocks ? c->filter_row_blocks : c->filter_srv_blocks;
     c->cap = (uint32_t)((d / 16 + 4096 < d) ? d / 16 + 4096 : d);
     c->list_blocks = clampu((c->cap + 2047u) / 2048u, 1u, 64u);
 

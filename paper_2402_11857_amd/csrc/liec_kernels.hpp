@@ -21,7 +21,7 @@ constexpr int kHistBins = 4096;         // widest radix digit (12 bits)
 constexpr int kStage = 512;             // per-wave LDS staging slots of the candidate filter
 constexpr int kTieCap = 4096;           // ties at the threshold the fast path resolves
 constexpr uint32_t kBandMargin = 1u << 18;   // least half width, in key units, of the predicted band (about 2 % in value)
-constexpr uint32_t kUpdatePanel = 2048; // column tiles per panel of the update kernel
+constexpr uint32_t kUpdatePanel = 4096; // column tiles per panel of the update kernel
 
 enum Comp : int { kIdentity = 0, kSign = 1, kTopk = 2 };
 
@@ -242,8 +242,18 @@ __global__ __launch_bounds__(kBlock) void k_l1_final(const double* __restrict__ 
     __shared__ double lds_w[4];
     const uint32_t row = blockIdx.x;
     const double* __restrict__ p = partial + (size_t)row * nparts;
-    double acc = 0.0;
-    for (uint32_t q = threadIdx.x; q < nparts; q += kBlock) acc += p[q];
+    // four independent running sums per thread (fixed assignment, fixed combination order) keep
+    // four loads in flight
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    uint32_t q = threadIdx.x;
+    for (; q + 3 * kBlock < nparts; q += 4 * kBlock) {
+        a0 += p[q];
+        a1 += p[q + kBlock];
+        a2 += p[q + 2 * kBlock];
+        a3 += p[q + 3 * kBlock];
+    }
+    for (; q < nparts; q += kBlock) a0 += p[q];
+    const double acc = (a0 + a1) + (a2 + a3);
     const double s = block_sum_f64(acc, lds_w);
     if (threadIdx.x == 0) {
         desc[row].l1 = s;
