@@ -22,6 +22,10 @@ HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 DEFAULT_WORKLOAD = "c5_vgg16_mixed"   # the largest configuration; fits one GPU (grads 8.25 GiB)
 ALSO = ["c3_resnet18_sign", "c4_resnet50_topk", "c5_vgg16_sign"]
 N_GRAD_BUFFERS = 4          # distinct gradient batches rotated through the timed steps
+# HBM bytes one launch of the update kernel moves, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this script, each counter scaled by what it reads for the 1 GiB copy probe (profiles/liec_step_<workload>.md)
+UPDATE_TRAFFIC_BYTES = {"c5_vgg16_mixed": 28.427e9, "c5_vgg16_sign": 28.423e9, "c3_resnet18_sign": 2.395e9,
+                        "c4_resnet50_topk": 10.252e9}
 
 
 def log(msg: str) -> None:
@@ -195,7 +199,7 @@ def main() -> int:
         "copy_kernel_gbps": copy_gbps,
         "roofline": {"bound": "hbm", "kernel": "update", "achieved": main_res["update_gbps"],
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": main_res["update_gbps"] / HBM_PEAK_GBPS,
-                     "traffic": None, "alg_bytes_per_launch": dominant_kernel_bytes(w),
+                     "traffic": UPDATE_TRAFFIC_BYTES.get(w.name), "alg_bytes_per_launch": dominant_kernel_bytes(w),
                      "avg_launch_ms": main_res["update_avg_ms"]},
         "kernels_ms_per_step_untimed_pass": {k: round(v, 4) for k, v in main_res["kernels_ms_per_step"].items()},
         "scratch_bytes": main_res["scratch_bytes"],
