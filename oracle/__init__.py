@@ -13,5 +13,6 @@ from .liec_oracle import (  # noqa: F401
     error_update,
     server_average,
     step,
+    step_sync,
     worker_update,
 )

@@ -2,8 +2,8 @@
  * liec_oracle.c -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
  *
  * A plain, slow, single-threaded CPU statement of one compressed iteration of
- * LIEC-SGD (Algorithm 1, the ELSE branches) and of the compression operators
- * it uses (Definition 2 top-k, Definition 4 scaled sign, and the identity
+ * LIEC-SGD (Algorithm 1, the ELSE branches), of its averaging iteration (the IF
+ * branches) and of the compression operators it uses (Definition 2 top-k, Definition 4 scaled sign, and the identity
  * operator that the uncompressed branch of Algorithm 1 amounts to).
  *
  * Nothing here is shared with the HIP library: no header, constant, helper or
@@ -206,6 +206,44 @@ int liec_oracle_step(int32_t N, int64_t d, int worker_comp, int64_t worker_k, in
     if (!v_out) free(v);
     if (!p_out) free(p);
     return rc;
+}
+
+/* The averaging iteration of Algorithm 1 (the branches taken when (t+1) is a multiple of the
+ * averaging period): workers send the uncompressed gradient and their model, the server
+ * compensates v = e + mean_i g_i and sends it uncompressed together with the mean model, so the
+ * global error becomes v - v = 0 and every worker restarts from the same point
+ *   x^i <- mean_i x^i - eta * (p - p^i + g_i)  with p = v, p^i = g_i.
+ * Readings: both means add in worker order in fp32 from +0; the gradient mean enters v through one
+ * fused multiply-add with 1/N (as in the compressed iteration), the model mean is one multiply by
+ * 1/N; the cached local error g_i - p^i is formed first (it is exactly 0), then added to p, then one
+ * fused multiply-add with -eta onto the mean model.
+ *   g [N,d] (read only), x [N,d] (in/out), e [d] (in/out), v_out [d] optional. */
+int liec_oracle_step_sync(int32_t N, int64_t d, float lr, const float *g, float *x, float *e,
+                          float *v_out)
+{
+    if (N < 1 || d < 1 || !g || !x || !e)
+        return 1;
+    const float inv_n = 1.0f / (float)N;
+    for (int64_t j = 0; j < d; ++j) {
+        float acc_g = 0.0f, acc_x = 0.0f;
+        for (int32_t i = 0; i < N; ++i) {
+            acc_g = acc_g + g[(size_t)i * (size_t)d + (size_t)j];
+            acc_x = acc_x + x[(size_t)i * (size_t)d + (size_t)j];
+        }
+        const float v = fmaf(acc_g, inv_n, e[j]);
+        const float p = v;                       /* sent uncompressed */
+        const float x_mean = acc_x * inv_n;
+        e[j] = v - p;
+        if (v_out)
+            v_out[j] = v;
+        for (int32_t i = 0; i < N; ++i) {
+            const float g_ij = g[(size_t)i * (size_t)d + (size_t)j];
+            const float local_err = g_ij - g_ij;  /* p^i = g_i */
+            const float u = p + local_err;
+            x[(size_t)i * (size_t)d + (size_t)j] = fmaf(-lr, u, x_mean);
+        }
+    }
+    return 0;
 }
 
 int liec_oracle_desc_size(void) { return (int)sizeof(oracle_desc); }

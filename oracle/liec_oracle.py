@@ -72,6 +72,8 @@ def _load():
         lib.liec_oracle_step.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int, ctypes.c_int64,
                                          ctypes.c_int, ctypes.c_int64, ctypes.c_float, fp, fp, fp,
                                          dp, dp, fp, fp, fp]
+        lib.liec_oracle_step_sync.restype = ctypes.c_int
+        lib.liec_oracle_step_sync.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_float, fp, fp, fp, fp]
         lib.liec_oracle_desc_size.restype = ctypes.c_int
         assert lib.liec_oracle_desc_size() == ctypes.sizeof(_CDesc)
         _lib = lib
@@ -169,3 +171,16 @@ def step(g: np.ndarray, x: np.ndarray, e: np.ndarray, worker_comp, server_comp, 
     if rc != 0:
         raise ValueError(f"liec_oracle_step failed with code {rc}")
     return StepTrace([_desc(c) for c in wd], _desc(sd), v, p, P)
+
+
+def step_sync(g: np.ndarray, x: np.ndarray, e: np.ndarray, lr: float, want_v: bool = False) -> Optional[np.ndarray]:
+    """The averaging iteration of Algorithm 1; x [N,d] and e [d] are updated in place."""
+    lib = _load()
+    g, x, e = _f32(g), _f32(x, True), _f32(e, True)
+    N, d = g.shape
+    assert x.shape == (N, d) and e.shape == (d,)
+    v = np.empty(d, dtype=np.float32) if want_v else None
+    rc = lib.liec_oracle_step_sync(N, d, ctypes.c_float(lr), _ptr(g), _ptr(x), _ptr(e), _ptr(v))
+    if rc != 0:
+        raise ValueError(f"liec_oracle_step_sync failed with code {rc}")
+    return v
