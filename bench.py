@@ -70,6 +70,13 @@ def run_workload(w, steps: int, warmup: int, seed: int = 0):
         for t in range(nb):
             ctx.step(grads[t % nbuf], x, e)
         kernels = {k: (v[0] / nb, v[1]) for k, v in ctx.profile_end().items()}
+        # the averaging iteration of Algorithm 1 (one in every `period` steps), timed on its own
+        ns = 5
+        ctx.step_sync(grads[0], x, e)
+        ctx.profile_begin(ns)
+        for t in range(ns):
+            ctx.step_sync(grads[t % nbuf], x, e)
+        sync_ms = ctx.profile_end()["sync"][0] / ns
         scratch = ctx.scratch_bytes()
     ms_per_step = 1e3 * elapsed / steps
     out = {
@@ -78,6 +85,8 @@ def run_workload(w, steps: int, warmup: int, seed: int = 0):
         "alg_gbps": w.alg_bytes_per_step * steps / elapsed / 1e9,
         "kernels_ms_per_step": {k: v[0] for k, v in kernels.items()},
         "scratch_bytes": scratch,
+        "sync_ms": sync_ms,
+        "sync_gbps": dominant_kernel_bytes(w) / (sync_ms * 1e-3) / 1e9,   # same bytes: g, x in, x out, e in/out
     }
     out["update_avg_ms"] = upd_ms / upd_n
     out["update_gbps"] = dominant_kernel_bytes(w) / (upd_ms / upd_n * 1e-3) / 1e9
@@ -170,6 +179,7 @@ def main() -> int:
             also[name] = {"ms_per_step": round(r["ms_per_step"], 4), "elems_per_s": r["elems_per_s"],
                           "alg_gbps": round(r["alg_gbps"], 1), "hbm_frac": round(r["alg_gbps"] / HBM_PEAK_GBPS, 4),
                           "update_gbps": round(r["update_gbps"], 1),
+                          "averaging_iteration_ms": round(r["sync_ms"], 4),
                           "kernels_ms_per_step": {k: round(v, 4) for k, v in r["kernels_ms_per_step"].items()}}
             log(f"{name}: {r['ms_per_step']:.3f} ms/step, {r['alg_gbps']:.0f} GB/s algorithmic")
     cpu = None
@@ -203,6 +213,8 @@ def main() -> int:
                      "avg_launch_ms": main_res["update_avg_ms"]},
         "kernels_ms_per_step_untimed_pass": {k: round(v, 4) for k, v in main_res["kernels_ms_per_step"].items()},
         "scratch_bytes": main_res["scratch_bytes"],
+        "averaging_iteration": {"ms": round(main_res["sync_ms"], 4), "alg_gbps": round(main_res["sync_gbps"], 1),
+                                "note": "Algorithm 1's uncompressed iteration, one in every `period` steps; not part of value"},
         "also": also,
         "cpu_baseline": cpu,
     }

@@ -102,6 +102,17 @@ liec_status liec_create_ex(liec_ctx **out, int32_t N, int64_t d, liec_comp worke
  */
 liec_status liec_step(liec_ctx *ctx, const float *grads, float *x, float *server_err);
 
+/*
+ * liec_step_sync: the averaging iteration of Algorithm 1 (taken when (t+1) is a
+ * multiple of the averaging period, which the caller keeps): gradients and
+ * models are exchanged uncompressed, so
+ *   v = e + (1/N) sum_i g_i ;  e <- v - v = 0 ;  x^i <- (1/N) sum_i x^i - lr * v  for every i.
+ * Same buffers, layout, alignment rules, ownership, asynchrony and errors as
+ * liec_step; the context's operators play no part.  Both sums add in worker
+ * order in fp32.
+ */
+liec_status liec_step_sync(liec_ctx *ctx, const float *grads, float *x, float *server_err);
+
 /* Learning-rate schedules (the paper decays eta during training): takes effect
  * from the next liec_step. */
 liec_status liec_set_lr(liec_ctx *ctx, float lr);

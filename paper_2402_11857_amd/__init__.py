@@ -21,4 +21,5 @@ from .binding import (  # noqa: F401
     liec_get_worker_desc,
     liec_set_lr,
     liec_step,
+    liec_step_sync,
 )

@@ -65,6 +65,8 @@ def lib():
         L.liec_create_ex.argtypes = [ctypes.POINTER(vp), i32, i64, ctypes.c_int, i64, ctypes.c_int, i64, f32, vp]
         L.liec_step.restype = ctypes.c_int
         L.liec_step.argtypes = [vp, vp, vp, vp]
+        L.liec_step_sync.restype = ctypes.c_int
+        L.liec_step_sync.argtypes = [vp, vp, vp, vp]
         L.liec_set_lr.restype = ctypes.c_int
         L.liec_set_lr.argtypes = [vp, f32]
         L.liec_get_info.restype = ctypes.c_int
@@ -125,6 +127,10 @@ def liec_step(ctx: int, grads_ptr: int, x_ptr: int, server_err_ptr: int) -> None
     _check(lib().liec_step(ctx, grads_ptr, x_ptr, server_err_ptr), "liec_step")
 
 
+def liec_step_sync(ctx: int, grads_ptr: int, x_ptr: int, server_err_ptr: int) -> None:
+    _check(lib().liec_step_sync(ctx, grads_ptr, x_ptr, server_err_ptr), "liec_step_sync")
+
+
 def liec_set_lr(ctx: int, lr: float) -> None:
     _check(lib().liec_set_lr(ctx, lr), "liec_set_lr")
 
@@ -175,6 +181,10 @@ class LiecContext:
     def step(self, grads: torch.Tensor, x: torch.Tensor, server_err: torch.Tensor) -> None:
         liec_step(self._h, _dev_ptr(grads, (self.N, self.d), "grads"), _dev_ptr(x, (self.N, self.d), "x"),
                   _dev_ptr(server_err, (self.d,), "server_err"))
+
+    def step_sync(self, grads: torch.Tensor, x: torch.Tensor, server_err: torch.Tensor) -> None:
+        liec_step_sync(self._h, _dev_ptr(grads, (self.N, self.d), "grads"), _dev_ptr(x, (self.N, self.d), "x"),
+                       _dev_ptr(server_err, (self.d,), "server_err"))
 
     def set_lr(self, lr: float) -> None:
         liec_set_lr(self._h, lr)

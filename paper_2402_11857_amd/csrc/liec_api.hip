@@ -24,6 +24,7 @@ enum Slot : int {
     S_S_L1_FINAL,
     S_S_SEL,                       // 12 slots of the server-side top-k search
     S_UPDATE = S_S_SEL + 12,
+    S_SYNC,
     S_COUNT
 };
 
@@ -41,6 +42,7 @@ const char* slot_name(int s) {
     if (s == S_AGGREGATE) return "server_aggregate";
     if (s == S_S_L1_FINAL) return "server_l1_final";
     if (s >= S_S_SEL && s < S_S_SEL + 12) return kServerSel[s - S_S_SEL];
+    if (s == S_SYNC) return "sync";
     return "update";
 }
 
@@ -124,7 +126,7 @@ struct Launcher {
     bool ok = true;
     bool recording = false;
     void begin(int slot) {
-        recording = c->profiling && (!c->prof_update_only || slot == S_UPDATE);
+        recording = c->profiling && (!c->prof_update_only || slot == S_UPDATE || slot == S_SYNC);
         if (!recording) return;
         ProfEvent ev{nullptr, nullptr, slot};
         if (hipEventCreate(&ev.start) != hipSuccess || hipEventCreate(&ev.stop) != hipSuccess) {
@@ -400,6 +402,34 @@ liec_status liec_step(liec_ctx* c, const float* grads, float* x, float* server_e
         run_step<true>(L, grads, x, server_err);
     else
         run_step<false>(L, grads, x, server_err);
+    c->profiling = was_profiling;
+    if (!L.ok) {
+        c->broken = true;
+        return LIEC_EDEVICE;
+    }
+    ++c->steps_done;
+    return LIEC_OK;
+}
+
+liec_status liec_step_sync(liec_ctx* c, const float* grads, float* x, float* server_err) {
+    if (!c || !grads || !x || !server_err) return LIEC_EINVAL;
+    if (c->broken) return LIEC_EDEVICE;
+    const size_t nd = (size_t)c->N * (size_t)c->d * sizeof(float), db = (size_t)c->d * sizeof(float);
+    if (overlap(grads, nd, x, nd) || overlap(grads, nd, server_err, db) || overlap(x, nd, server_err, db))
+        return LIEC_EINVAL;
+    if (((uintptr_t)grads | (uintptr_t)x | (uintptr_t)server_err) & 3u) return LIEC_EINVAL;
+    const bool vec = (c->d % 4 == 0) && ((((uintptr_t)grads | (uintptr_t)x | (uintptr_t)server_err) & 15u) == 0);
+    Launcher L{c};
+    const bool was_profiling = c->profiling;
+    if (c->profiling && c->prof_steps_left <= 0) c->profiling = false;
+    if (c->profiling) --c->prof_steps_left;
+    const float inv_n = 1.0f / (float)c->N;
+    L.begin(S_SYNC);
+    if (vec)
+        k_sync<true><<<c->ncol_tiles, kBlock, 0, c->stream>>>(grads, x, server_err, c->N, (uint32_t)c->d, inv_n, -c->lr);
+    else
+        k_sync<false><<<c->ncol_tiles, kBlock, 0, c->stream>>>(grads, x, server_err, c->N, (uint32_t)c->d, inv_n, -c->lr);
+    L.end();
     c->profiling = was_profiling;
     if (!L.ok) {
         c->broken = true;
