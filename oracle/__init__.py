@@ -7,12 +7,15 @@ from .liec_oracle import (  # noqa: F401
     IDENTITY,
     SIGN,
     TOPK,
+    BLOCKSIGN,
     Desc,
     build,
     compress,
+    compress_blocksign,
     error_update,
     server_average,
     step,
+    step_blocks,
     step_sync,
     worker_update,
 )

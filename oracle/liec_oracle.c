@@ -3,7 +3,8 @@
  *
  * A plain, slow, single-threaded CPU statement of one compressed iteration of
  * LIEC-SGD (Algorithm 1, the ELSE branches), of its averaging iteration (the IF
- * branches) and of the compression operators it uses (Definition 2 top-k, Definition 4 scaled sign, and the identity
+ * branches) and of the compression operators it uses (Definition 2 top-k,
+ * Definition 4 scaled sign, Definition 5 blockwise scaled sign, and the identity
  * operator that the uncompressed branch of Algorithm 1 amounts to).
  *
  * Nothing here is shared with the HIP library: no header, constant, helper or
@@ -38,7 +39,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORACLE_IDENTITY = 0, ORACLE_SIGN = 1, ORACLE_TOPK = 2 };
+enum { ORACLE_IDENTITY = 0, ORACLE_SIGN = 1, ORACLE_TOPK = 2, ORACLE_BLOCKSIGN = 3 };
 
 /* What a compressed message consists of besides the per-element part. */
 typedef struct {
@@ -109,9 +110,37 @@ static int compress_topk(const float *v, int64_t d, int64_t k, float *p, oracle_
     return 0;
 }
 
+/* Definition 5 (Blockwise-SignSGD): Definition 4 applied independently to each of the B consecutive
+ * blocks [off[b], off[b+1]) of v, each with its own length d_b = off[b+1] - off[b] (off[0] = 0,
+ * off[B] = d, strictly increasing).  scales [B] receives the per-block scales. */
+static int compress_blocksign(const float *v, int64_t d, const int64_t *off, int32_t B, float *p,
+                              float *scales)
+{
+    if (!off || B < 1 || off[0] != 0 || off[B] != d)
+        return 1;
+    for (int32_t b = 0; b < B; ++b) {
+        if (off[b + 1] <= off[b])
+            return 1;
+        oracle_desc blk;
+        compress_sign(v + off[b], off[b + 1] - off[b], p ? p + off[b] : NULL, &blk);
+        if (scales)
+            scales[b] = blk.scale;
+    }
+    return 0;
+}
+
 /* p = C(v) for the chosen operator.  Returns 0 on success. */
+int liec_oracle_compress_ex(int comp, const float *v, int64_t d, int64_t k, const int64_t *off,
+                            int32_t B, float *p, oracle_desc *desc, float *block_scales);
+
 int liec_oracle_compress(int comp, const float *v, int64_t d, int64_t k, float *p,
                          oracle_desc *desc)
+{
+    return liec_oracle_compress_ex(comp, v, d, k, NULL, 0, p, desc, NULL);
+}
+
+int liec_oracle_compress_ex(int comp, const float *v, int64_t d, int64_t k, const int64_t *off,
+                            int32_t B, float *p, oracle_desc *desc, float *block_scales)
 {
     oracle_desc local;
     if (!desc)
@@ -130,6 +159,8 @@ int liec_oracle_compress(int comp, const float *v, int64_t d, int64_t k, float *
         return 0;
     case ORACLE_TOPK:
         return compress_topk(v, d, k, p, desc);
+    case ORACLE_BLOCKSIGN:
+        return compress_blocksign(v, d, off, B, p, block_scales);
     default:
         return 1;
     }
@@ -173,10 +204,27 @@ void liec_oracle_worker_update(const float *g_i, const float *p_i, const float *
  *   wdesc [N], sdesc [1], v_out [d] (compensated average), p_out [d] (broadcast),
  *   P_out [N,d] (uplink messages, decompressed).
  * Returns 0 on success, 1 on bad arguments, 2 when out of memory. */
+int liec_oracle_step_ex(int32_t N, int64_t d, int worker_comp, int64_t worker_k, int server_comp,
+                        int64_t server_k, float lr, const float *g, float *x, float *e,
+                        const int64_t *off, int32_t B, oracle_desc *wdesc, oracle_desc *sdesc,
+                        float *wscales, float *sscales, float *v_out, float *p_out, float *P_out);
+
 int liec_oracle_step(int32_t N, int64_t d, int worker_comp, int64_t worker_k, int server_comp,
                      int64_t server_k, float lr, const float *g, float *x, float *e,
                      oracle_desc *wdesc, oracle_desc *sdesc, float *v_out, float *p_out,
                      float *P_out)
+{
+    return liec_oracle_step_ex(N, d, worker_comp, worker_k, server_comp, server_k, lr, g, x, e, NULL, 0,
+                               wdesc, sdesc, NULL, NULL, v_out, p_out, P_out);
+}
+
+/* The same iteration with the block table of Definition 5 available to either side
+ * (off [B+1], used where the operator is the blockwise scaled sign); wscales [N*B] and sscales [B]
+ * optionally receive the per-block scales. */
+int liec_oracle_step_ex(int32_t N, int64_t d, int worker_comp, int64_t worker_k, int server_comp,
+                        int64_t server_k, float lr, const float *g, float *x, float *e,
+                        const int64_t *off, int32_t B, oracle_desc *wdesc, oracle_desc *sdesc,
+                        float *wscales, float *sscales, float *v_out, float *p_out, float *P_out)
 {
     if (N < 1 || d < 1 || !g || !x || !e)
         return 1;
@@ -188,12 +236,13 @@ int liec_oracle_step(int32_t N, int64_t d, int worker_comp, int64_t worker_k, in
 
     /* worker i: p^i = C(g_i) */
     for (int32_t i = 0; rc == 0 && i < N; ++i)
-        rc = liec_oracle_compress(worker_comp, g + (size_t)i * (size_t)d, d, worker_k,
-                                  P + (size_t)i * (size_t)d, wdesc ? &wdesc[i] : NULL);
+        rc = liec_oracle_compress_ex(worker_comp, g + (size_t)i * (size_t)d, d, worker_k, off, B,
+                                     P + (size_t)i * (size_t)d, wdesc ? &wdesc[i] : NULL,
+                                     wscales ? wscales + (size_t)i * (size_t)B : NULL);
     if (rc == 0) {
         /* server: v = e + mean_i p^i ; p = C(v) ; e <- v - p */
         liec_oracle_server_average(P, N, d, e, v);
-        rc = liec_oracle_compress(server_comp, v, d, server_k, p, sdesc);
+        rc = liec_oracle_compress_ex(server_comp, v, d, server_k, off, B, p, sdesc, sscales);
     }
     if (rc == 0) {
         liec_oracle_error_update(v, p, d, e);

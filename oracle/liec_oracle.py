@@ -14,8 +14,8 @@ from typing import List, Optional, Tuple
 
 import numpy as np
 
-IDENTITY, SIGN, TOPK = 0, 1, 2
-_NAMES = {"identity": IDENTITY, "sign": SIGN, "topk": TOPK}
+IDENTITY, SIGN, TOPK, BLOCKSIGN = 0, 1, 2, 3
+_NAMES = {"identity": IDENTITY, "sign": SIGN, "topk": TOPK, "blocksign": BLOCKSIGN}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "liec_oracle.c")
@@ -72,6 +72,14 @@ def _load():
         lib.liec_oracle_step.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int, ctypes.c_int64,
                                          ctypes.c_int, ctypes.c_int64, ctypes.c_float, fp, fp, fp,
                                          dp, dp, fp, fp, fp]
+        ip = ctypes.POINTER(ctypes.c_int64)
+        lib.liec_oracle_compress_ex.restype = ctypes.c_int
+        lib.liec_oracle_compress_ex.argtypes = [ctypes.c_int, fp, ctypes.c_int64, ctypes.c_int64, ip, ctypes.c_int32,
+                                                fp, dp, fp]
+        lib.liec_oracle_step_ex.restype = ctypes.c_int
+        lib.liec_oracle_step_ex.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int, ctypes.c_int64,
+                                            ctypes.c_int, ctypes.c_int64, ctypes.c_float, fp, fp, fp, ip,
+                                            ctypes.c_int32, dp, dp, fp, fp, fp, fp, fp]
         lib.liec_oracle_step_sync.restype = ctypes.c_int
         lib.liec_oracle_step_sync.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_float, fp, fp, fp, fp]
         lib.liec_oracle_desc_size.restype = ctypes.c_int
@@ -184,3 +192,54 @@ def step_sync(g: np.ndarray, x: np.ndarray, e: np.ndarray, lr: float, want_v: bo
     if rc != 0:
         raise ValueError(f"liec_oracle_step_sync failed with code {rc}")
     return v
+
+
+def _offsets(blocks) -> np.ndarray:
+    off = np.ascontiguousarray(np.asarray(blocks, dtype=np.int64))
+    assert off.ndim == 1 and off.size >= 2
+    return off
+
+
+def compress_blocksign(v: np.ndarray, blocks) -> Tuple[np.ndarray, np.ndarray]:
+    """Definition 5: scaled sign per block; `blocks` are the B+1 block offsets. Returns (p, scales[B])."""
+    lib = _load()
+    v = _f32(v)
+    off = _offsets(blocks)
+    B = off.size - 1
+    p = np.empty_like(v)
+    scales = np.empty(B, dtype=np.float32)
+    c = _CDesc()
+    rc = lib.liec_oracle_compress_ex(BLOCKSIGN, _ptr(v), v.shape[0], 0, off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                     B, _ptr(p), ctypes.byref(c), _ptr(scales))
+    if rc != 0:
+        raise ValueError(f"liec_oracle_compress_ex failed with code {rc}")
+    return p, scales
+
+
+@dataclass
+class BlockStepTrace:
+    worker: List[Desc]
+    server: Desc
+    worker_scales: np.ndarray
+    server_scales: np.ndarray
+
+
+def step_blocks(g: np.ndarray, x: np.ndarray, e: np.ndarray, worker_comp, server_comp, lr: float, blocks,
+                worker_k: int = 0, server_k: int = 0) -> BlockStepTrace:
+    """One compressed iteration of Algorithm 1 with Definition 5's block table available to both sides."""
+    lib = _load()
+    g, x, e = _f32(g), _f32(x, True), _f32(e, True)
+    N, d = g.shape
+    off = _offsets(blocks)
+    B = off.size - 1
+    wd = (_CDesc * N)()
+    sd = _CDesc()
+    ws = np.zeros((N, B), dtype=np.float32)
+    ss = np.zeros(B, dtype=np.float32)
+    rc = lib.liec_oracle_step_ex(N, d, _comp(worker_comp), int(worker_k), _comp(server_comp), int(server_k),
+                                 ctypes.c_float(lr), _ptr(g), _ptr(x), _ptr(e),
+                                 off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), B, wd, ctypes.byref(sd),
+                                 _ptr(ws), _ptr(ss), None, None, None)
+    if rc != 0:
+        raise ValueError(f"liec_oracle_step_ex failed with code {rc}")
+    return BlockStepTrace([_desc(c) for c in wd], _desc(sd), ws, ss)
