@@ -20,7 +20,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 DEFAULT_WORKLOAD = "c5_vgg16_mixed"   # the largest configuration; fits one GPU (grads 8.25 GiB)
-ALSO = ["c3_resnet18_sign", "c4_resnet50_topk", "c5_vgg16_sign"]
+ALSO = ["c3_resnet18_sign", "c3_resnet18_blocksign", "c4_resnet50_topk", "c5_vgg16_sign"]
 N_GRAD_BUFFERS = 4          # distinct gradient batches rotated through the timed steps
 # HBM bytes one launch of the update kernel moves, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this script, each counter scaled by what it reads for the 1 GiB copy probe (profiles/liec_step_<workload>.md)
@@ -52,6 +52,8 @@ def run_workload(w, steps: int, warmup: int, seed: int = 0):
     e = torch.zeros(w.d, dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
     with LiecContext(w.N, w.d, w.worker_comp, w.server_comp, w.worker_k, w.server_k, w.lr) as ctx:
+        if w.blocks is not None:
+            ctx.set_blocks(w.blocks)
         for t in range(warmup):
             ctx.step(grads[t % nbuf], x, e)
         torch.cuda.synchronize()

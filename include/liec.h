@@ -10,8 +10,8 @@
  *   p    = C_s(v)                             server compression, broadcast
  *   e   <- v - p                              global error update
  *   x^i <- x^i - lr * (p + (g_i - p^i))       local immediate error compensation
- * C_w / C_s are the scaled-sign operator (Definition 4), top-k (Definition 2)
- * or the identity.  Conventions the definitions leave open:
+ * C_w / C_s are the scaled-sign operator (Definition 4), its blockwise form
+ * (Definition 5), top-k (Definition 2) or the identity.  Conventions the definitions leave open:
  *   - scaled sign: scale = fp32(sum_j |v_j| / d) with the sum carried in fp64;
  *     sign is binary, v >= 0 (both zeros included) -> +scale, v < 0 -> -scale;
  *   - top-k: magnitudes compare through the integer key (bits & 0x7fffffff);
@@ -47,7 +47,8 @@ typedef enum {
 typedef enum {
     LIEC_COMP_IDENTITY = 0, /* C(v) = v; with it on both sides the step is P-SGD */
     LIEC_COMP_SIGN = 1,     /* Definition 4 */
-    LIEC_COMP_TOPK = 2      /* Definition 2 */
+    LIEC_COMP_TOPK = 2,     /* Definition 2 */
+    LIEC_COMP_BLOCKSIGN = 3 /* Definition 5: Definition 4 on each block of liec_set_blocks */
 } liec_comp;
 
 /* Scalars describing the LAST completed step (filled by liec_get_info). */
@@ -112,6 +113,27 @@ liec_status liec_step(liec_ctx *ctx, const float *grads, float *x, float *server
  * order in fp32.
  */
 liec_status liec_step_sync(liec_ctx *ctx, const float *grads, float *x, float *server_err);
+
+/*
+ * liec_set_blocks: the block table of Blockwise-SignSGD (Definition 5), needed
+ * before the first liec_step of a context that uses LIEC_COMP_BLOCKSIGN on
+ * either side (liec_step returns LIEC_EINVAL without it).
+ *   offsets  HOST array of nblocks + 1 column offsets, offsets[0] = 0,
+ *            offsets[nblocks] = d, strictly increasing (block b is the columns
+ *            offsets[b] .. offsets[b+1]-1 and has its own length d_b)
+ *   nblocks  1 .. 65536 (one block gives Definition 4)
+ * Synchronises the stream, replaces any earlier table and allocates
+ * O((N + 1) * (d / 4096 + nblocks)) bytes of device scratch.
+ */
+liec_status liec_set_blocks(liec_ctx *ctx, const int64_t *offsets, int32_t nblocks);
+
+/*
+ * Synchronises the stream and copies the per-block scales of the last step to
+ * HOST arrays: worker_scales [N * nblocks] (row-major) and server_scales
+ * [nblocks]; either may be NULL; a side that does not use LIEC_COMP_BLOCKSIGN
+ * gets zeros.  LIEC_EINVAL without a block table.
+ */
+liec_status liec_get_block_scales(liec_ctx *ctx, float *worker_scales, float *server_scales);
 
 /* Learning-rate schedules (the paper decays eta during training): takes effect
  * from the next liec_step. */

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     COMP_IDENTITY,
     COMP_SIGN,
     COMP_TOPK,
+    COMP_BLOCKSIGN,
     LiecContext,
     LiecError,
     LiecInfo,
@@ -20,6 +21,8 @@ from .binding import (  # noqa: F401
     liec_get_info,
     liec_get_worker_desc,
     liec_set_lr,
+    liec_set_blocks,
+    liec_get_block_scales,
     liec_step,
     liec_step_sync,
 )

@@ -11,8 +11,8 @@ from typing import Dict, List, Optional, Tuple
 
 import torch
 
-COMP_IDENTITY, COMP_SIGN, COMP_TOPK = 0, 1, 2
-_COMP_NAMES = {"identity": COMP_IDENTITY, "sign": COMP_SIGN, "topk": COMP_TOPK}
+COMP_IDENTITY, COMP_SIGN, COMP_TOPK, COMP_BLOCKSIGN = 0, 1, 2, 3
+_COMP_NAMES = {"identity": COMP_IDENTITY, "sign": COMP_SIGN, "topk": COMP_TOPK, "blocksign": COMP_BLOCKSIGN}
 OK, EINVAL, ENOMEM, EDEVICE, ENONFINITE = 0, 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -67,6 +67,10 @@ def lib():
         L.liec_step.argtypes = [vp, vp, vp, vp]
         L.liec_step_sync.restype = ctypes.c_int
         L.liec_step_sync.argtypes = [vp, vp, vp, vp]
+        L.liec_set_blocks.restype = ctypes.c_int
+        L.liec_set_blocks.argtypes = [vp, ctypes.POINTER(i64), i32]
+        L.liec_get_block_scales.restype = ctypes.c_int
+        L.liec_get_block_scales.argtypes = [vp, ctypes.POINTER(f32), ctypes.POINTER(f32)]
         L.liec_set_lr.restype = ctypes.c_int
         L.liec_set_lr.argtypes = [vp, f32]
         L.liec_get_info.restype = ctypes.c_int
@@ -131,6 +135,19 @@ def liec_step_sync(ctx: int, grads_ptr: int, x_ptr: int, server_err_ptr: int) ->
     _check(lib().liec_step_sync(ctx, grads_ptr, x_ptr, server_err_ptr), "liec_step_sync")
 
 
+def liec_set_blocks(ctx: int, offsets) -> None:
+    off = [int(o) for o in offsets]
+    arr = (ctypes.c_int64 * len(off))(*off)
+    _check(lib().liec_set_blocks(ctx, arr, len(off) - 1), "liec_set_blocks")
+
+
+def liec_get_block_scales(ctx: int, N: int, nblocks: int):
+    ws = (ctypes.c_float * (N * nblocks))()
+    ss = (ctypes.c_float * nblocks)()
+    _check(lib().liec_get_block_scales(ctx, ws, ss), "liec_get_block_scales")
+    return [list(ws[i * nblocks:(i + 1) * nblocks]) for i in range(N)], list(ss)
+
+
 def liec_set_lr(ctx: int, lr: float) -> None:
     _check(lib().liec_set_lr(ctx, lr), "liec_set_lr")
 
@@ -185,6 +202,13 @@ class LiecContext:
     def step_sync(self, grads: torch.Tensor, x: torch.Tensor, server_err: torch.Tensor) -> None:
         liec_step_sync(self._h, _dev_ptr(grads, (self.N, self.d), "grads"), _dev_ptr(x, (self.N, self.d), "x"),
                        _dev_ptr(server_err, (self.d,), "server_err"))
+
+    def set_blocks(self, offsets) -> None:
+        self._nblocks = len(list(offsets)) - 1
+        liec_set_blocks(self._h, offsets)
+
+    def block_scales(self):
+        return liec_get_block_scales(self._h, self.N, self._nblocks)
 
     def set_lr(self, lr: float) -> None:
         liec_set_lr(self._h, lr)

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -21,7 +22,7 @@ enum Slot : int {
     S_W_L1 = 0, S_W_L1_FINAL,
     S_W_SEL,                       // 12 slots of the worker-side top-k search
     S_AGGREGATE = S_W_SEL + 12,
-    S_S_L1_FINAL,
+    S_S_L1, S_S_L1_FINAL,
     S_S_SEL,                       // 12 slots of the server-side top-k search
     S_UPDATE = S_S_SEL + 12,
     S_SYNC,
@@ -40,6 +41,7 @@ const char* slot_name(int s) {
     if (s == S_W_L1_FINAL) return "worker_l1_final";
     if (s >= S_W_SEL && s < S_W_SEL + 12) return kWorkerSel[s - S_W_SEL];
     if (s == S_AGGREGATE) return "server_aggregate";
+    if (s == S_S_L1) return "server_l1";
     if (s == S_S_L1_FINAL) return "server_l1_final";
     if (s >= S_S_SEL && s < S_S_SEL + 12) return kServerSel[s - S_S_SEL];
     if (s == S_SYNC) return "sync";
@@ -87,6 +89,17 @@ struct liec_ctx {
     uint32_t* tiebuf = nullptr;                // [(N + 1) * kTieCap]
     int64_t scratch_bytes = 0;
 
+    // blockwise scaled sign (Definition 5): block table and its scratch, set by liec_set_blocks
+    uint32_t B = 0, nitems = 0;
+    uint32_t* blk_off = nullptr;               // [B + 1]
+    uint32_t* tile_blk = nullptr;              // [ncol_tiles]
+    uint32_t* item_start = nullptr;            // [B + 1]
+    L1Item* items = nullptr;                   // [nitems]
+    double* blk_partial = nullptr;             // [(N + 1) * nitems]
+    float* blk_scales = nullptr;               // [(N + 1) * B]
+    double* blk_l1 = nullptr;                  // [(N + 1) * B]
+    int64_t blk_bytes = 0;
+
     // profiling
     bool profiling = false;
     bool prof_update_only = false;
@@ -106,7 +119,27 @@ hipError_t dev_alloc(liec_ctx* c, T** p, size_t count) {
     return e;
 }
 
+void free_blocks(liec_ctx* c) {
+    (void)hipFree(c->blk_off);
+    (void)hipFree(c->tile_blk);
+    (void)hipFree(c->item_start);
+    (void)hipFree(c->items);
+    (void)hipFree(c->blk_partial);
+    (void)hipFree(c->blk_scales);
+    (void)hipFree(c->blk_l1);
+    c->blk_off = c->tile_blk = c->item_start = nullptr;
+    c->items = nullptr;
+    c->blk_partial = c->blk_l1 = nullptr;
+    c->blk_scales = nullptr;
+    c->scratch_bytes -= c->blk_bytes;
+    c->blk_bytes = 0;
+    c->B = c->nitems = 0;
+}
+
+BlockTable block_table(const liec_ctx* c) { return BlockTable{c->tile_blk, c->blk_off, c->blk_scales, c->B}; }
+
 void free_scratch(liec_ctx* c) {
+    free_blocks(c);
     (void)hipFree(c->desc);
     (void)hipFree(c->vbuf);
     (void)hipFree(c->w_partial);
@@ -119,7 +152,9 @@ void free_scratch(liec_ctx* c) {
     (void)hipFree(c->tiebuf);
 }
 
-bool valid_comp(int c) { return c == LIEC_COMP_IDENTITY || c == LIEC_COMP_SIGN || c == LIEC_COMP_TOPK; }
+bool valid_comp(int c) {
+    return c == LIEC_COMP_IDENTITY || c == LIEC_COMP_SIGN || c == LIEC_COMP_TOPK || c == LIEC_COMP_BLOCKSIGN;
+}
 
 struct Launcher {
     liec_ctx* c;
@@ -193,6 +228,22 @@ void launch_topk_select(Launcher& L, const float* src, size_t row_stride, uint32
     L.end();
 }
 
+// Blockwise scaled sign (Definition 5): per-block L1 norms of `rows` rows of `src` -> scales; for the
+// workers also the sign bits.  slot0 and slot0 + 1 time the two kernels.
+template <bool VEC>
+void launch_block_l1(Launcher& L, const float* src, size_t row_stride, uint32_t rows, uint32_t row0, uint16_t* bits,
+                     int slot0) {
+    liec_ctx* c = L.c;
+    L.begin(slot0);
+    k_l1_items<VEC><<<dim3(c->nitems, rows), kBlock, 0, c->stream>>>(src, row_stride, (uint32_t)c->d, c->nwt, row0, c->items,
+                                                                      c->blk_partial, bits);
+    L.end();
+    L.begin(slot0 + 1);
+    k_l1_items_final<<<dim3(c->B, rows), kBlock, 0, c->stream>>>(c->blk_partial, c->nitems, c->item_start, c->blk_off,
+                                                                  c->B, row0, c->blk_scales, c->blk_l1);
+    L.end();
+}
+
 template <int WC, bool VEC>
 void launch_aggregate(Launcher& L, const float* grads, const float* e, bool srv_l1) {
     liec_ctx* c = L.c;
@@ -201,10 +252,12 @@ void launch_aggregate(Launcher& L, const float* grads, const float* e, bool srv_
     L.begin(S_AGGREGATE);
     if (srv_l1)
         k_aggregate<WC, true, VEC><<<c->agg_blocks, kBlock, 0, c->stream>>>(grads, c->bits, c->N, d, c->nwt, inv_n,
-                                                                             c->desc, e, c->vbuf, c->s_partial);
+                                                                             c->desc, e, c->vbuf, c->s_partial,
+                                                                             block_table(c));
     else
         k_aggregate<WC, false, VEC><<<c->agg_blocks, kBlock, 0, c->stream>>>(grads, c->bits, c->N, d, c->nwt, inv_n,
-                                                                              c->desc, e, c->vbuf, c->s_partial);
+                                                                              c->desc, e, c->vbuf, c->s_partial,
+                                                                             block_table(c));
     L.end();
 }
 
@@ -216,7 +269,7 @@ void launch_update(Launcher& L, const float* grads, float* x, float* e) {
     const uint64_t blocks = (uint64_t)npanels * panel * (uint64_t)c->N;
     L.begin(S_UPDATE);
     k_update<WC, SC, VEC><<<(uint32_t)blocks, kBlock, 0, c->stream>>>(grads, x, c->vbuf, e, c->N, panel, c->ncol_tiles,
-                                                                       (uint32_t)c->d, -c->lr, c->desc);
+                                                                       (uint32_t)c->d, -c->lr, c->desc, block_table(c));
     L.end();
 }
 
@@ -225,6 +278,7 @@ void launch_update_sc(Launcher& L, int sc, const float* grads, float* x, float* 
     switch (sc) {
     case kIdentity: launch_update<WC, kIdentity, VEC>(L, grads, x, e); break;
     case kSign: launch_update<WC, kSign, VEC>(L, grads, x, e); break;
+    case kBlockSign: launch_update<WC, kBlockSign, VEC>(L, grads, x, e); break;
     default: launch_update<WC, kTopk, VEC>(L, grads, x, e); break;
     }
 }
@@ -244,6 +298,8 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
         L.begin(S_W_L1_FINAL);
         k_l1_final<<<c->N, kBlock, 0, c->stream>>>(c->w_partial, c->row_blocks, d, c->desc);
         L.end();
+    } else if (c->worker_comp == kBlockSign) {
+        launch_block_l1<VEC>(L, grads, stride, (uint32_t)c->N, 0u, c->bits, S_W_L1);
     } else if (c->worker_comp == kTopk) {
         launch_topk_select<VEC>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, c->bits,
                                 c->filter_row_blocks, c->cold_row_blocks, S_W_SEL);
@@ -254,12 +310,15 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
     switch (c->worker_comp) {
     case kIdentity: launch_aggregate<kIdentity, VEC>(L, grads, e, srv_l1); break;
     case kSign: launch_aggregate<kSign, VEC>(L, grads, e, srv_l1); break;
+    case kBlockSign: launch_aggregate<kBlockSign, VEC>(L, grads, e, srv_l1); break;
     default: launch_aggregate<kTopk, VEC>(L, grads, e, srv_l1); break;
     }
     if (c->server_comp == kSign) {
         L.begin(S_S_L1_FINAL);
         k_l1_final<<<1, kBlock, 0, c->stream>>>(c->s_partial, c->agg_blocks, d, c->desc + c->N);
         L.end();
+    } else if (c->server_comp == kBlockSign) {
+        launch_block_l1<VEC>(L, c->vbuf, 0, 1u, (uint32_t)c->N, nullptr, S_S_L1);
     } else if (c->server_comp == kTopk) {
         // v is always 16-byte aligned scratch, but d % 4 decides whether 128-bit loads stay in bounds
         launch_topk_select<VEC>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, nullptr,
@@ -270,6 +329,7 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
     switch (c->worker_comp) {
     case kIdentity: launch_update_sc<kIdentity, VEC>(L, c->server_comp, grads, x, e); break;
     case kSign: launch_update_sc<kSign, VEC>(L, c->server_comp, grads, x, e); break;
+    case kBlockSign: launch_update_sc<kBlockSign, VEC>(L, c->server_comp, grads, x, e); break;
     default: launch_update_sc<kTopk, VEC>(L, c->server_comp, grads, x, e); break;
     }
 }
@@ -394,6 +454,7 @@ liec_status liec_step(liec_ctx* c, const float* grads, float* x, float* server_e
     if (((uintptr_t)grads | (uintptr_t)x | (uintptr_t)server_err) & 3u) return LIEC_EINVAL;
     const bool vec = (c->d % 4 == 0) && ((((uintptr_t)grads | (uintptr_t)x | (uintptr_t)server_err) & 15u) == 0);
 
+    if ((c->worker_comp == kBlockSign || c->server_comp == kBlockSign) && c->B == 0) return LIEC_EINVAL;
     Launcher L{c};
     const bool was_profiling = c->profiling;
     if (c->profiling && c->prof_steps_left <= 0) c->profiling = false;
@@ -439,6 +500,91 @@ liec_status liec_step_sync(liec_ctx* c, const float* grads, float* x, float* ser
     return LIEC_OK;
 }
 
+liec_status liec_set_blocks(liec_ctx* c, const int64_t* offsets, int32_t nblocks) {
+    if (!c || !offsets || nblocks < 1 || nblocks > 65536) return LIEC_EINVAL;
+    if (c->broken) return LIEC_EDEVICE;
+    if (offsets[0] != 0 || offsets[nblocks] != c->d) return LIEC_EINVAL;
+    for (int32_t b = 0; b < nblocks; ++b)
+        if (offsets[b + 1] <= offsets[b]) return LIEC_EINVAL;
+    if (hipStreamSynchronize(c->stream) != hipSuccess) {
+        c->broken = true;
+        return LIEC_EDEVICE;
+    }
+    free_blocks(c);
+    const uint32_t B = (uint32_t)nblocks, d = (uint32_t)c->d;
+    std::vector<uint32_t> off(B + 1), tile_blk(c->ncol_tiles), item_start(B + 1);
+    for (uint32_t b = 0; b <= B; ++b) off[b] = (uint32_t)offsets[b];
+    for (uint32_t t = 0, b = 0; t < c->ncol_tiles; ++t) {
+        const uint32_t first = t * (uint32_t)kColTile, last = std::min(first + (uint32_t)kColTile, d) - 1;
+        while (first >= off[b + 1]) ++b;
+        tile_blk[t] = b | (last >= off[b + 1] ? 0x80000000u : 0u);
+    }
+    std::vector<L1Item> items;
+    const uint32_t big = 4u * (uint32_t)kWaveTile;                 // columns per block of k_l1_items
+    std::vector<uint32_t> owner((d + big - 1) / big, 0xffffffffu); // the first item of a tile writes its bits
+    for (uint32_t b = 0; b < B; ++b) {
+        item_start[b] = (uint32_t)items.size();
+        for (uint32_t t = off[b] / big; t <= (off[b + 1] - 1) / big; ++t) {
+            L1Item it;
+            it.tile = t;
+            it.lo = std::max(off[b], t * big);
+            it.hi = std::min(off[b + 1], (t + 1) * big);
+            it.write_bits = owner[t] == 0xffffffffu ? 1u : 0u;
+            owner[t] = b;
+            items.push_back(it);
+        }
+    }
+    item_start[B] = (uint32_t)items.size();
+    c->B = B;
+    c->nitems = (uint32_t)items.size();
+    const size_t rows = (size_t)c->N + 1;
+    const int64_t before = c->scratch_bytes;
+    hipError_t e = dev_alloc(c, &c->blk_off, (size_t)B + 1);
+    if (e == hipSuccess) e = dev_alloc(c, &c->tile_blk, (size_t)c->ncol_tiles);
+    if (e == hipSuccess) e = dev_alloc(c, &c->item_start, (size_t)B + 1);
+    if (e == hipSuccess) e = dev_alloc(c, &c->items, items.size());
+    if (e == hipSuccess) e = dev_alloc(c, &c->blk_partial, rows * items.size());
+    if (e == hipSuccess) e = dev_alloc(c, &c->blk_scales, rows * B);
+    if (e == hipSuccess) e = dev_alloc(c, &c->blk_l1, rows * B);
+    c->blk_bytes = c->scratch_bytes - before;
+    if (e == hipSuccess) e = hipMemcpy(c->blk_off, off.data(), off.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->tile_blk, tile_blk.data(), tile_blk.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->item_start, item_start.data(), item_start.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->items, items.data(), items.size() * sizeof(L1Item), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemset(c->blk_scales, 0, rows * B * sizeof(float));
+    if (e == hipSuccess) e = hipMemset(c->blk_l1, 0, rows * B * sizeof(double));
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        free_blocks(c);
+        return e == hipErrorOutOfMemory ? LIEC_ENOMEM : LIEC_EDEVICE;
+    }
+    return LIEC_OK;
+}
+
+liec_status liec_get_block_scales(liec_ctx* c, float* worker_scales, float* server_scales) {
+    if (!c || c->B == 0) return LIEC_EINVAL;
+    if (c->broken) return LIEC_EDEVICE;
+    hipError_t e = hipStreamSynchronize(c->stream);
+    const size_t nb = (size_t)c->N * c->B;
+    if (e == hipSuccess && worker_scales) {
+        if (c->worker_comp == kBlockSign)
+            e = hipMemcpy(worker_scales, c->blk_scales, nb * sizeof(float), hipMemcpyDeviceToHost);
+        else
+            std::memset(worker_scales, 0, nb * sizeof(float));
+    }
+    if (e == hipSuccess && server_scales) {
+        if (c->server_comp == kBlockSign)
+            e = hipMemcpy(server_scales, c->blk_scales + nb, (size_t)c->B * sizeof(float), hipMemcpyDeviceToHost);
+        else
+            std::memset(server_scales, 0, (size_t)c->B * sizeof(float));
+    }
+    if (e != hipSuccess) {
+        c->broken = true;
+        return LIEC_EDEVICE;
+    }
+    return LIEC_OK;
+}
+
 liec_status liec_set_lr(liec_ctx* c, float lr) {
     if (!c || !finite_f(lr)) return LIEC_EINVAL;
     c->lr = lr;
@@ -471,9 +617,21 @@ liec_status liec_get_info(liec_ctx* c, liec_info* info) {
         info->server_tau_key = s.tau;
         info->server_cutoff = (int64_t)s.cutoff;
     }
-    bool bad = c->server_comp != kIdentity && s.nonfinite;
-    if (c->worker_comp != kIdentity)
+    bool bad = (c->server_comp == kSign || c->server_comp == kTopk) && s.nonfinite;
+    if (c->worker_comp == kSign || c->worker_comp == kTopk)
         for (int32_t i = 0; i < c->N; ++i) bad = bad || h[(size_t)i].nonfinite;
+    if ((c->worker_comp == kBlockSign || c->server_comp == kBlockSign) && c->B) {
+        std::vector<double> l1((size_t)(c->N + 1) * c->B);
+        if (hipMemcpy(l1.data(), c->blk_l1, l1.size() * sizeof(double), hipMemcpyDeviceToHost) != hipSuccess) {
+            c->broken = true;
+            return LIEC_EDEVICE;
+        }
+        const size_t nb = (size_t)c->N * c->B;
+        for (size_t q = 0; q < l1.size(); ++q) {
+            const bool used = q < nb ? c->worker_comp == kBlockSign : c->server_comp == kBlockSign;
+            if (used && !std::isfinite(l1[q])) bad = true;
+        }
+    }
     info->nonfinite = bad ? 1 : 0;
     return bad ? LIEC_ENONFINITE : LIEC_OK;
 }

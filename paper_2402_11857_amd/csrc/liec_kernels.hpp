@@ -23,7 +23,7 @@ constexpr int kTieCap = 4096;           // ties at the threshold the fast path r
 constexpr uint32_t kBandMargin = 1u << 18;   // least half width, in key units, of the predicted band (about 2 % in value)
 constexpr uint32_t kUpdatePanel = 4096; // column tiles per panel of the update kernel
 
-enum Comp : int { kIdentity = 0, kSign = 1, kTopk = 2 };
+enum Comp : int { kIdentity = 0, kSign = 1, kTopk = 2, kBlockSign = 3 };
 
 // Progress of a row's top-k threshold search within one step.
 enum SelMode : uint32_t {
@@ -259,6 +259,90 @@ __global__ __launch_bounds__(kBlock) void k_l1_final(const double* __restrict__ 
         desc[row].l1 = s;
         desc[row].scale = (float)(s / (double)d);
         desc[row].nonfinite = (s - s == 0.0) ? 0u : 1u;   // s - s is NaN for NaN and Inf
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Blockwise scaled sign (Definition 5): Definition 4 on each of B consecutive column blocks
+// [off[b], off[b+1]) with its own length.  Sign bits are the same as for Definition 4; only the
+// scale depends on the column's block.
+// ---------------------------------------------------------------------------------------------
+struct BlockTable {
+    const uint32_t* tile_blk;   // [ceil(d/1024)] block of the tile's first column; bit 31: the tile spans a boundary
+    const uint32_t* off;        // [B + 1] block offsets, off[0] = 0, off[B] = d
+    const float* scales;        // [(N + 1) * B] scale of block b of row r at r*B + b (row N: the server's v)
+    uint32_t B;
+};
+
+__device__ __forceinline__ uint32_t block_of(const BlockTable& bt, uint32_t first, uint32_t j) {
+    uint32_t b = first;
+    while (b + 1 < bt.B && j >= bt.off[b + 1]) ++b;
+    return b;
+}
+
+// One unit of the blockwise L1 pass: the part [lo, hi) of one compression block that falls into the
+// 4096-column tile `tile`.  Items are ordered by block, then by tile.
+struct L1Item {
+    uint32_t tile, lo, hi, write_bits;
+};
+
+// grid = (items, rows).  Partial sum of |src| over the item's columns (fp64) and, for the item that
+// owns the tile's bits, the sign bits of the whole tile.
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_l1_items(const float* __restrict__ src, size_t row_stride, uint32_t d,
+                                                      uint32_t nwt, uint32_t row0, const L1Item* __restrict__ items,
+                                                      double* __restrict__ partial, uint16_t* __restrict__ bits) {
+    __shared__ double lds_w[4];
+    const L1Item it = items[blockIdx.x];
+    const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint32_t t = it.tile * 4 + wave;
+    double acc = 0.0;
+    if (t < nwt) {
+        float4 a[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
+        uint32_t m = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
+            if (j >= it.lo && j < it.hi) acc += (double)fabsf(a[u].x);
+            if (j + 1 >= it.lo && j + 1 < it.hi) acc += (double)fabsf(a[u].y);
+            if (j + 2 >= it.lo && j + 2 < it.hi) acc += (double)fabsf(a[u].z);
+            if (j + 3 >= it.lo && j + 3 < it.hi) acc += (double)fabsf(a[u].w);
+            m |= (a[u].x < 0.f ? 1u : 0u) << (4 * u);
+            m |= (a[u].y < 0.f ? 1u : 0u) << (4 * u + 1);
+            m |= (a[u].z < 0.f ? 1u : 0u) << (4 * u + 2);
+            m |= (a[u].w < 0.f ? 1u : 0u) << (4 * u + 3);
+        }
+        if (bits && it.write_bits) bits[((size_t)blockIdx.y * nwt + t) * 64 + lane] = (uint16_t)m;
+    }
+    const double s = block_sum_f64(acc, lds_w);
+    if (threadIdx.x == 0) partial[(size_t)(row0 + blockIdx.y) * gridDim.x + blockIdx.x] = s;
+}
+
+// grid = (B, rows).  Adds up the item partials of block b in a fixed order and sets its scale.
+__global__ __launch_bounds__(kBlock) void k_l1_items_final(const double* __restrict__ partial, uint32_t nitems,
+                                                            const uint32_t* __restrict__ item_start,
+                                                            const uint32_t* __restrict__ off, uint32_t B, uint32_t row0,
+                                                            float* __restrict__ scales, double* __restrict__ l1s) {
+    __shared__ double lds_w[4];
+    const uint32_t b = blockIdx.x, row = row0 + blockIdx.y;
+    const double* __restrict__ p = partial + (size_t)row * nitems;
+    const uint32_t q0 = item_start[b], q1 = item_start[b + 1];
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    uint32_t q = q0 + threadIdx.x;
+    for (; q + 3 * kBlock < q1; q += 4 * kBlock) {
+        a0 += p[q];
+        a1 += p[q + kBlock];
+        a2 += p[q + 2 * kBlock];
+        a3 += p[q + 3 * kBlock];
+    }
+    for (; q < q1; q += kBlock) a0 += p[q];
+    const double s = block_sum_f64((a0 + a1) + (a2 + a3), lds_w);
+    if (threadIdx.x == 0) {
+        l1s[(size_t)row * B + b] = s;
+        scales[(size_t)row * B + b] = (float)(s / (double)(off[b + 1] - off[b]));
     }
 }
 
@@ -686,7 +770,7 @@ __device__ __forceinline__ void add_signed(float4 (&acc)[4], uint32_t m, float s
 // ---------------------------------------------------------------------------------------------
 template <int WC>
 __device__ __forceinline__ float message_of(float g, uint32_t j, float scale, uint32_t tau, uint32_t cutoff) {
-    if (WC == kSign) return g < 0.f ? -scale : scale;
+    if (WC == kSign || WC == kBlockSign) return g < 0.f ? -scale : scale;
     if (WC == kTopk) {
         const uint32_t key = key_of(g);
         return (key > tau || (key == tau && j <= cutoff)) ? g : 0.f;
@@ -698,7 +782,8 @@ __device__ __forceinline__ float message_of(float g, uint32_t j, float scale, ui
 // Server compensation (Algorithm 1): v_j = e_j + (1/N) sum_i p^i_j, messages added in worker
 // order; v goes to its own buffer.  With SRV_L1 the kernel also emits per-block partial sums of
 // |v| (fp64) for the server's scaled-sign operator.  grid = blocks; waves stride over wave tiles.
-//   WC == kSign     reads the packed sign bits instead of the gradients;
+//   WC == kSign / kBlockSign  read the packed sign bits instead of the gradients (blockwise: the scale
+//                   comes from the column's block);
 //   WC == kTopk     reads each row's candidate bitmap and fetches only the flagged gradients,
 //                   testing them against (tau, cut-off); per-lane sums live in LDS;
 //   WC == kIdentity reads the gradients.
@@ -707,7 +792,8 @@ template <int WC, bool SRV_L1, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ grads, const uint16_t* __restrict__ bits,
                                                        int N, uint32_t d, uint32_t nwt, float inv_n,
                                                        const RowDesc* __restrict__ desc, const float* __restrict__ e_in,
-                                                       float* __restrict__ v_out, double* __restrict__ srv_partial) {
+                                                       float* __restrict__ v_out, double* __restrict__ srv_partial,
+                                                       BlockTable bt) {
     __shared__ double lds_w[4];
     __shared__ float accs[WC == kTopk ? 16 * kBlock : 1];
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -729,6 +815,39 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
                 for (int r = 0; r < 8; ++r) add_signed(acc, m[r], desc[i + r].scale);
             }
             for (; i < N; ++i) add_signed(acc, bw[(size_t)i * brow], desc[i].scale);
+        } else if (WC == kBlockSign) {
+            const uint16_t* __restrict__ bw = bits + (size_t)t * 64 + lane;
+            const size_t brow = (size_t)nwt * 64;
+            const uint32_t tb = bt.tile_blk[t], first = tb & 0x7fffffffu;
+            if (!(tb >> 31)) {                                  // the whole wave tile lies in one block
+                int i = 0;
+                for (; i + 8 <= N; i += 8) {
+                    uint32_t m[8];
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) m[r] = bw[(size_t)(i + r) * brow];
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) add_signed(acc, m[r], bt.scales[(size_t)(i + r) * bt.B + first]);
+                }
+                for (; i < N; ++i) add_signed(acc, bw[(size_t)i * brow], bt.scales[(size_t)i * bt.B + first]);
+            } else {
+                uint32_t bidx[16];
+#pragma unroll
+                for (int b = 0; b < 16; ++b) {
+                    const uint32_t j = j0 + (b >> 2) * kChunk + (b & 3);
+                    bidx[b] = block_of(bt, first, j < d ? j : d - 1);
+                }
+                for (int i = 0; i < N; ++i) {
+                    const uint32_t m = bw[(size_t)i * brow];
+                    const float* __restrict__ sc = bt.scales + (size_t)i * bt.B;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        acc[u].x = __fadd_rn(acc[u].x, signed_scale(m, 4 * u + 0, sc[bidx[4 * u + 0]]));
+                        acc[u].y = __fadd_rn(acc[u].y, signed_scale(m, 4 * u + 1, sc[bidx[4 * u + 1]]));
+                        acc[u].z = __fadd_rn(acc[u].z, signed_scale(m, 4 * u + 2, sc[bidx[4 * u + 2]]));
+                        acc[u].w = __fadd_rn(acc[u].w, signed_scale(m, 4 * u + 3, sc[bidx[4 * u + 3]]));
+                    }
+                }
+            }
         } else if (WC == kTopk) {
             float* my = accs + threadIdx.x;                    // slot b of this lane: my[b * kBlock]
 #pragma unroll
@@ -803,7 +922,7 @@ template <int WC, int SC, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ grads, float* __restrict__ x,
                                                     const float* __restrict__ v_in, float* __restrict__ e_out, int N,
                                                     uint32_t panel, uint32_t ncol_tiles, uint32_t d, float neg_lr,
-                                                    const RowDesc* __restrict__ desc) {
+                                                    const RowDesc* __restrict__ desc, BlockTable bt) {
     const uint32_t per_panel = panel * (uint32_t)N;
     const uint32_t pn = blockIdx.x / per_panel, r = blockIdx.x % per_panel;
     const uint32_t i = r / panel, tile = pn * panel + r % panel;
@@ -816,13 +935,28 @@ __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ gra
     const float4 xv = ld4<VEC, true>(xi, j, d);
     const float4 v = ld4<VEC>(v_in, j, d);
     const RowDesc* __restrict__ sd = desc + N;
-    const float ss = sd->scale;
     const uint32_t stau = sd->tau, scut = sd->cutoff;
+    float sw[4], ss[4];                                    // worker / server scale of each of the 4 columns
+    if (WC == kBlockSign || SC == kBlockSign) {
+        const uint32_t tb = bt.tile_blk[tile], first = tb & 0x7fffffffu;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t b = (tb >> 31) ? block_of(bt, first, j + c < d ? j + c : d - 1) : first;
+            sw[c] = WC == kBlockSign ? bt.scales[(size_t)i * bt.B + b] : desc[i].scale;
+            ss[c] = SC == kBlockSign ? bt.scales[(size_t)N * bt.B + b] : sd->scale;
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            sw[c] = desc[i].scale;
+            ss[c] = sd->scale;
+        }
+    }
     float4 p;
-    p.x = message_of<SC>(v.x, j, ss, stau, scut);
-    p.y = message_of<SC>(v.y, j + 1, ss, stau, scut);
-    p.z = message_of<SC>(v.z, j + 2, ss, stau, scut);
-    p.w = message_of<SC>(v.w, j + 3, ss, stau, scut);
+    p.x = message_of<SC>(v.x, j, ss[0], stau, scut);
+    p.y = message_of<SC>(v.y, j + 1, ss[1], stau, scut);
+    p.z = message_of<SC>(v.z, j + 2, ss[2], stau, scut);
+    p.w = message_of<SC>(v.w, j + 3, ss[3], stau, scut);
     if (i == 0) {
         float4 en;
         en.x = __fsub_rn(v.x, p.x);
@@ -831,13 +965,12 @@ __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ gra
         en.w = __fsub_rn(v.w, p.w);
         st4<VEC>(e_out, j, d, en);
     }
-    const float s = desc[i].scale;
     const uint32_t tau = desc[i].tau, cut = desc[i].cutoff;
     float4 o;
-    o.x = __fmaf_rn(neg_lr, __fadd_rn(p.x, __fsub_rn(g.x, message_of<WC>(g.x, j, s, tau, cut))), xv.x);
-    o.y = __fmaf_rn(neg_lr, __fadd_rn(p.y, __fsub_rn(g.y, message_of<WC>(g.y, j + 1, s, tau, cut))), xv.y);
-    o.z = __fmaf_rn(neg_lr, __fadd_rn(p.z, __fsub_rn(g.z, message_of<WC>(g.z, j + 2, s, tau, cut))), xv.z);
-    o.w = __fmaf_rn(neg_lr, __fadd_rn(p.w, __fsub_rn(g.w, message_of<WC>(g.w, j + 3, s, tau, cut))), xv.w);
+    o.x = __fmaf_rn(neg_lr, __fadd_rn(p.x, __fsub_rn(g.x, message_of<WC>(g.x, j, sw[0], tau, cut))), xv.x);
+    o.y = __fmaf_rn(neg_lr, __fadd_rn(p.y, __fsub_rn(g.y, message_of<WC>(g.y, j + 1, sw[1], tau, cut))), xv.y);
+    o.z = __fmaf_rn(neg_lr, __fadd_rn(p.z, __fsub_rn(g.z, message_of<WC>(g.z, j + 2, sw[2], tau, cut))), xv.z);
+    o.w = __fmaf_rn(neg_lr, __fadd_rn(p.w, __fsub_rn(g.w, message_of<WC>(g.w, j + 3, sw[3], tau, cut))), xv.w);
     st4<VEC, true>(xi, j, d, o);
 }
 

@@ -3,4 +3,4 @@
 Shared by the tests of the HIP path and of the CPU oracle; contains no part of
 the method itself.
 """
-from .gradients import GradientSource, Workload, inject_ties, scaled, workloads  # noqa: F401
+from .gradients import GradientSource, Workload, inject_ties, layer_blocks, scaled, workloads  # noqa: F401

@@ -32,6 +32,7 @@ class Workload:
     log10_sigma_lo: float     # sigma_l log-uniform in [10**lo, 10**hi]; lo == hi == 0 -> sigma = 1
     log10_sigma_hi: float
     outlier_prob: float       # fraction of elements replaced by a Student-t(nu=2) variate
+    blocks: Optional[List[int]] = field(default=None, repr=False)   # block offsets for the blockwise operator
 
     @property
     def alg_bytes_per_step(self) -> int:
@@ -58,7 +59,23 @@ def workloads() -> Dict[str, Workload]:
         # same shape and inputs as c5 with the scaled-sign operator in both directions
         _mk("c5_vgg16_sign", 16, d5, "sign", "sign", 0, 0, 0.01, 50, vgg, -5.0, -2.0, 0.0),
     ]
+    import dataclasses
+    # the operator of the paper's experiments: Blockwise-SignSGD with 10 blocks for ResNet-18; the
+    # paper does not say where the blocks are cut, so the 62 parameter tensors are grouped in order
+    w.append(dataclasses.replace(w[2], name="c3_resnet18_blocksign", worker_comp="blocksign",
+                                 server_comp="blocksign", blocks=layer_blocks(r18, 10)))
     return {x.name: x for x in w}
+
+
+def layer_blocks(sizes: List[int], nblocks: int) -> List[int]:
+    """Offsets of `nblocks` consecutive groups of whole layers, as even in layer count as possible."""
+    n = len(sizes)
+    assert 1 <= nblocks <= n
+    cuts = [round(i * n / nblocks) for i in range(nblocks + 1)]
+    pre = [0]
+    for sz in sizes:
+        pre.append(pre[-1] + sz)
+    return [pre[c] for c in cuts]
 
 
 def scaled(w: Workload, N: Optional[int] = None, d: Optional[int] = None, **kw) -> Workload:
@@ -73,7 +90,11 @@ def scaled(w: Workload, N: Optional[int] = None, d: Optional[int] = None, **kw) 
     sizes[sizes.index(max(sizes))] += d - sum(sizes)
     frac_w = w.worker_k / w.d
     frac_s = w.server_k / w.d
-    upd = dict(N=N, d=d, layer_sizes=sizes,
+    blocks = None
+    if w.blocks is not None:       # keep the number of blocks, cut at the rescaled positions
+        cuts = sorted({max(1, min(d - 1, o * d // w.d)) for o in w.blocks[1:-1]})
+        blocks = [0] + cuts + [d]
+    upd = dict(N=N, d=d, layer_sizes=sizes, blocks=blocks,
                worker_k=max(1, int(frac_w * d)) if w.worker_comp == "topk" else 0,
                server_k=max(1, int(frac_s * d)) if w.server_comp == "topk" else 0)
     upd.update(kw)
