@@ -13,6 +13,8 @@ from .liec_oracle import (  # noqa: F401
     compress,
     compress_blocksign,
     error_update,
+    pack_sign,
+    unpack_sign,
     server_average,
     step,
     step_blocks,

@@ -295,4 +295,30 @@ int liec_oracle_step_sync(int32_t N, int64_t d, float lr, const float *g, float 
     return 0;
 }
 
+/* Wire form of a scaled-sign message (Definition 4; the paper counts it as one bit per element):
+ * bit (j mod 8) of byte (j div 8) is 1 when v_j < 0; unused bits of the last byte are 0. */
+void liec_oracle_pack_sign(const float *v, int64_t d, uint8_t *bytes)
+{
+    for (int64_t b = 0; b < (d + 7) / 8; ++b)
+        bytes[b] = 0;
+    for (int64_t j = 0; j < d; ++j)
+        if (v[j] < 0.0f)
+            bytes[j / 8] |= (uint8_t)(1u << (j % 8));
+}
+
+/* Decompression of that message: p_j = -scale or +scale; with a block table (Definition 5) the scale
+ * of the block holding j.  off == NULL means one block. */
+void liec_oracle_unpack_sign(const uint8_t *bytes, int64_t d, const float *scales, const int64_t *off,
+                             int32_t B, float *p)
+{
+    int32_t b = 0;
+    for (int64_t j = 0; j < d; ++j) {
+        if (off)
+            while (b + 1 < B && j >= off[b + 1])
+                ++b;
+        const float s = scales[off ? b : 0];
+        p[j] = ((bytes[j / 8] >> (j % 8)) & 1u) ? -s : s;
+    }
+}
+
 int liec_oracle_desc_size(void) { return (int)sizeof(oracle_desc); }

@@ -80,6 +80,11 @@ def _load():
         lib.liec_oracle_step_ex.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int, ctypes.c_int64,
                                             ctypes.c_int, ctypes.c_int64, ctypes.c_float, fp, fp, fp, ip,
                                             ctypes.c_int32, dp, dp, fp, fp, fp, fp, fp]
+        u8p = ctypes.POINTER(ctypes.c_uint8)
+        lib.liec_oracle_pack_sign.restype = None
+        lib.liec_oracle_pack_sign.argtypes = [fp, ctypes.c_int64, u8p]
+        lib.liec_oracle_unpack_sign.restype = None
+        lib.liec_oracle_unpack_sign.argtypes = [u8p, ctypes.c_int64, fp, ip, ctypes.c_int32, fp]
         lib.liec_oracle_step_sync.restype = ctypes.c_int
         lib.liec_oracle_step_sync.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_float, fp, fp, fp, fp]
         lib.liec_oracle_desc_size.restype = ctypes.c_int
@@ -243,3 +248,27 @@ def step_blocks(g: np.ndarray, x: np.ndarray, e: np.ndarray, worker_comp, server
     if rc != 0:
         raise ValueError(f"liec_oracle_step_ex failed with code {rc}")
     return BlockStepTrace([_desc(c) for c in wd], _desc(sd), ws, ss)
+
+
+def pack_sign(v: np.ndarray) -> np.ndarray:
+    """Wire bits of a (blockwise) scaled-sign message: bit j%8 of byte j//8 set when v_j < 0."""
+    lib = _load()
+    v = _f32(v)
+    out = np.empty((v.shape[0] + 7) // 8, dtype=np.uint8)
+    lib.liec_oracle_pack_sign(_ptr(v), v.shape[0], out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)))
+    return out
+
+
+def unpack_sign(bits: np.ndarray, d: int, scales, blocks=None) -> np.ndarray:
+    """Dense message from wire bits and the scale (one) or per-block scales (with `blocks` offsets)."""
+    lib = _load()
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    sc = np.ascontiguousarray(np.atleast_1d(np.asarray(scales, dtype=np.float32)))
+    p = np.empty(d, dtype=np.float32)
+    if blocks is None:
+        offp, B = None, 1
+    else:
+        off = _offsets(blocks)
+        offp, B = off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), off.size - 1
+    lib.liec_oracle_unpack_sign(bits.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), d, _ptr(sc), offp, B, _ptr(p))
+    return p
