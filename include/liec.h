@@ -135,6 +135,47 @@ liec_status liec_set_blocks(liec_ctx *ctx, const int64_t *offsets, int32_t nbloc
  */
 liec_status liec_get_block_scales(liec_ctx *ctx, float *worker_scales, float *server_scales);
 
+/*
+ * Bytes of one message C(v) on the wire, as the paper counts communication
+ * (one bit per element for the sign operators, "32x"): identity 4d; scaled sign
+ * ceil(d/8) + 4 (bits + scale); blockwise ceil(d/8) + 4*nblocks; top-k 8k
+ * (32-bit index + fp32 value per kept entry).  -1 for bad arguments.  Host only.
+ */
+int64_t liec_message_bytes(liec_comp comp, int64_t d, int64_t k, int32_t nblocks);
+
+/*
+ * Average bytes moved per iteration of Algorithm 1 (the quantity of the paper's
+ * communication-cost table): a compressed iteration moves N worker messages up
+ * and the server message down to each of the N workers; every period-th
+ * iteration is an averaging iteration that moves N full gradients up and N full
+ * vectors down, plus the N models each way when count_model_exchange != 0 (the
+ * paper's table leaves them out).  period = 0 means compressed iterations only;
+ * period = 1 is rejected.  Host arithmetic only; writes *bytes_per_iteration.
+ */
+liec_status liec_comm_cost(int32_t N, int64_t d, liec_comp worker_comp, int64_t worker_k,
+                           liec_comp server_comp, int64_t server_k, int32_t nblocks, int32_t period,
+                           int32_t count_model_exchange, double *bytes_per_iteration);
+
+/*
+ * Wire bits of worker `worker`'s (blockwise) scaled-sign message of the last
+ * step: ceil(d/8) bytes written to the DEVICE buffer `out`, bit j % 8 of byte
+ * j / 8 set when g_j < 0, unused bits zero.  Enqueued on the context's stream.
+ * The scale(s) that complete the message come from liec_get_worker_desc /
+ * liec_get_block_scales.  LIEC_EINVAL unless the worker operator is a sign
+ * operator and a step has run.
+ */
+liec_status liec_pack_sign_bits(liec_ctx *ctx, int32_t worker, uint8_t *out);
+
+/*
+ * Decompression of such a message into the dense vector p (DEVICE, [d]):
+ * p_j = -s or +s, with s = scales[0] (blockwise == 0) or the scale of the block
+ * holding j (blockwise != 0; scales has nblocks entries, the context's block
+ * table applies).  bits: DEVICE, ceil(d/8) bytes.  scales: HOST.  Enqueued on
+ * the context's stream after a synchronous copy of the scales.
+ */
+liec_status liec_unpack_sign_message(liec_ctx *ctx, const uint8_t *bits, const float *scales,
+                                     int32_t blockwise, float *p_out);
+
 /* Learning-rate schedules (the paper decays eta during training): takes effect
  * from the next liec_step. */
 liec_status liec_set_lr(liec_ctx *ctx, float lr);

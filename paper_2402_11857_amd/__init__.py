@@ -21,6 +21,8 @@ from .binding import (  # noqa: F401
     liec_get_info,
     liec_get_worker_desc,
     liec_set_lr,
+    liec_message_bytes,
+    liec_comm_cost,
     liec_set_blocks,
     liec_get_block_scales,
     liec_step,

@@ -71,6 +71,15 @@ def lib():
         L.liec_set_blocks.argtypes = [vp, ctypes.POINTER(i64), i32]
         L.liec_get_block_scales.restype = ctypes.c_int
         L.liec_get_block_scales.argtypes = [vp, ctypes.POINTER(f32), ctypes.POINTER(f32)]
+        L.liec_message_bytes.restype = i64
+        L.liec_message_bytes.argtypes = [ctypes.c_int, i64, i64, i32]
+        L.liec_comm_cost.restype = ctypes.c_int
+        L.liec_comm_cost.argtypes = [i32, i64, ctypes.c_int, i64, ctypes.c_int, i64, i32, i32, i32,
+                                     ctypes.POINTER(ctypes.c_double)]
+        L.liec_pack_sign_bits.restype = ctypes.c_int
+        L.liec_pack_sign_bits.argtypes = [vp, i32, vp]
+        L.liec_unpack_sign_message.restype = ctypes.c_int
+        L.liec_unpack_sign_message.argtypes = [vp, vp, ctypes.POINTER(f32), i32, vp]
         L.liec_set_lr.restype = ctypes.c_int
         L.liec_set_lr.argtypes = [vp, f32]
         L.liec_get_info.restype = ctypes.c_int
@@ -148,6 +157,18 @@ def liec_get_block_scales(ctx: int, N: int, nblocks: int):
     return [list(ws[i * nblocks:(i + 1) * nblocks]) for i in range(N)], list(ss)
 
 
+def liec_message_bytes(comp, d: int, k: int = 0, nblocks: int = 0) -> int:
+    return int(lib().liec_message_bytes(_comp(comp), d, k, nblocks))
+
+
+def liec_comm_cost(N: int, d: int, worker_comp, worker_k: int, server_comp, server_k: int, nblocks: int = 0,
+                   period: int = 0, count_model_exchange: bool = False) -> float:
+    out = ctypes.c_double()
+    _check(lib().liec_comm_cost(N, d, _comp(worker_comp), worker_k, _comp(server_comp), server_k, nblocks, period,
+                                1 if count_model_exchange else 0, ctypes.byref(out)), "liec_comm_cost")
+    return out.value
+
+
 def liec_set_lr(ctx: int, lr: float) -> None:
     _check(lib().liec_set_lr(ctx, lr), "liec_set_lr")
 
@@ -209,6 +230,18 @@ class LiecContext:
 
     def block_scales(self):
         return liec_get_block_scales(self._h, self.N, self._nblocks)
+
+    def pack_sign_bits(self, worker: int, out: torch.Tensor) -> None:
+        assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous() and out.numel() == (self.d + 7) // 8
+        _check(lib().liec_pack_sign_bits(self._h, worker, out.data_ptr()), "liec_pack_sign_bits")
+
+    def unpack_sign_message(self, bits: torch.Tensor, scales, blockwise: bool, out: torch.Tensor) -> None:
+        assert bits.is_cuda and bits.dtype == torch.uint8 and bits.numel() == (self.d + 7) // 8
+        _dev_ptr(out, (self.d,), "out")
+        sc = [float(v) for v in scales]
+        arr = (ctypes.c_float * len(sc))(*sc)
+        _check(lib().liec_unpack_sign_message(self._h, bits.data_ptr(), arr, 1 if blockwise else 0, out.data_ptr()),
+               "liec_unpack_sign_message")
 
     def set_lr(self, lr: float) -> None:
         liec_set_lr(self._h, lr)

@@ -99,6 +99,8 @@ struct liec_ctx {
     float* blk_scales = nullptr;               // [(N + 1) * B]
     double* blk_l1 = nullptr;                  // [(N + 1) * B]
     int64_t blk_bytes = 0;
+    float* wire_scales = nullptr;              // [max(B, 1)] staging for liec_unpack_sign_message
+    uint32_t wire_scales_len = 0;
 
     // profiling
     bool profiling = false;
@@ -140,6 +142,7 @@ BlockTable block_table(const liec_ctx* c) { return BlockTable{c->tile_blk, c->bl
 
 void free_scratch(liec_ctx* c) {
     free_blocks(c);
+    (void)hipFree(c->wire_scales);
     (void)hipFree(c->desc);
     (void)hipFree(c->vbuf);
     (void)hipFree(c->w_partial);
@@ -579,6 +582,80 @@ liec_status liec_get_block_scales(liec_ctx* c, float* worker_scales, float* serv
             std::memset(server_scales, 0, (size_t)c->B * sizeof(float));
     }
     if (e != hipSuccess) {
+        c->broken = true;
+        return LIEC_EDEVICE;
+    }
+    return LIEC_OK;
+}
+
+int64_t liec_message_bytes(liec_comp comp, int64_t d, int64_t k, int32_t nblocks) {
+    if (d < 1) return -1;
+    switch (comp) {
+    case LIEC_COMP_IDENTITY: return 4 * d;
+    case LIEC_COMP_SIGN: return (d + 7) / 8 + 4;
+    case LIEC_COMP_BLOCKSIGN: return nblocks < 1 ? -1 : (d + 7) / 8 + 4 * (int64_t)nblocks;
+    case LIEC_COMP_TOPK: return (k < 1 || k > d) ? -1 : 8 * k;
+    default: return -1;
+    }
+}
+
+liec_status liec_comm_cost(int32_t N, int64_t d, liec_comp worker_comp, int64_t worker_k, liec_comp server_comp,
+                           int64_t server_k, int32_t nblocks, int32_t period, int32_t count_model_exchange,
+                           double* bytes_per_iteration) {
+    if (!bytes_per_iteration || N < 1 || period < 0 || period == 1) return LIEC_EINVAL;
+    const int64_t up = liec_message_bytes(worker_comp, d, worker_k, nblocks);
+    const int64_t down = liec_message_bytes(server_comp, d, server_k, nblocks);
+    if (up < 0 || down < 0) return LIEC_EINVAL;
+    const double compressed = (double)N * ((double)up + (double)down);
+    if (period == 0) {
+        *bytes_per_iteration = compressed;
+        return LIEC_OK;
+    }
+    const double full = 4.0 * (double)d;
+    const double averaging = (double)N * (2.0 * full) + (count_model_exchange ? (double)N * (2.0 * full) : 0.0);
+    *bytes_per_iteration = ((double)(period - 1) * compressed + averaging) / (double)period;
+    return LIEC_OK;
+}
+
+liec_status liec_pack_sign_bits(liec_ctx* c, int32_t worker, uint8_t* out) {
+    if (!c || !out || worker < 0 || worker >= c->N) return LIEC_EINVAL;
+    if (c->broken) return LIEC_EDEVICE;
+    if ((c->worker_comp != kSign && c->worker_comp != kBlockSign) || c->steps_done == 0) return LIEC_EINVAL;
+    const uint32_t nbytes = (uint32_t)((c->d + 7) / 8);
+    k_pack_sign<<<(nbytes + kBlock - 1) / kBlock, kBlock, 0, c->stream>>>(c->bits + (size_t)worker * c->nwt * 64, nbytes, out);
+    if (hipGetLastError() != hipSuccess) {
+        c->broken = true;
+        return LIEC_EDEVICE;
+    }
+    return LIEC_OK;
+}
+
+liec_status liec_unpack_sign_message(liec_ctx* c, const uint8_t* bits, const float* scales, int32_t blockwise,
+                                     float* p_out) {
+    if (!c || !bits || !scales || !p_out) return LIEC_EINVAL;
+    if (c->broken) return LIEC_EDEVICE;
+    if (blockwise && c->B == 0) return LIEC_EINVAL;
+    const uint32_t n = blockwise ? c->B : 1u;
+    hipError_t e = hipSuccess;
+    if (c->wire_scales_len < n) {
+        e = hipStreamSynchronize(c->stream);
+        (void)hipFree(c->wire_scales);
+        c->wire_scales = nullptr;
+        c->wire_scales_len = 0;
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->wire_scales), (size_t)n * sizeof(float));
+        if (e == hipSuccess) c->wire_scales_len = n;
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(c->wire_scales, scales, (size_t)n * sizeof(float), hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);        // the host array may be reused on return
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return e == hipErrorOutOfMemory ? LIEC_ENOMEM : LIEC_EDEVICE;
+    }
+    BlockTable bt = block_table(c);
+    if (!blockwise) bt.B = 0;
+    const uint32_t d = (uint32_t)c->d;
+    k_unpack_sign<<<(d + kBlock - 1) / kBlock, kBlock, 0, c->stream>>>(bits, d, c->wire_scales, bt, p_out);
+    if (hipGetLastError() != hipSuccess) {
         c->broken = true;
         return LIEC_EDEVICE;
     }

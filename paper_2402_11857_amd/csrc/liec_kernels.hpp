@@ -1025,6 +1025,34 @@ __global__ __launch_bounds__(kBlock) void k_sync(const float* __restrict__ grads
     for (i = 0; i < N; ++i) st4<VEC, true>(x + (size_t)i * d, j, d, o);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Wire form of a (blockwise) scaled-sign message: one bit per element, bit j % 8 of byte j / 8 set
+// when the element is negative.  k_pack_sign turns one row of the lane-major bitmap into that
+// form (one thread per output byte); k_unpack_sign expands wire bits and scale(s) into the dense
+// message p_j = -s or +s (one thread per column).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_pack_sign(const uint16_t* __restrict__ row_bits, uint32_t nbytes,
+                                                       uint8_t* __restrict__ out) {
+    const uint32_t b = blockIdx.x * kBlock + threadIdx.x;
+    if (b >= nbytes) return;
+    const uint32_t col = b * 8, t = col / kWaveTile, o = col % kWaveTile, u = o / kChunk, lane = (o % kChunk) / 4;
+    const uint32_t m0 = row_bits[(size_t)t * 64 + lane], m1 = row_bits[(size_t)t * 64 + lane + 1];
+    out[b] = (uint8_t)(((m0 >> (4 * u)) & 0xfu) | (((m1 >> (4 * u)) & 0xfu) << 4));
+}
+
+__global__ __launch_bounds__(kBlock) void k_unpack_sign(const uint8_t* __restrict__ bytes, uint32_t d,
+                                                         const float* __restrict__ scales, BlockTable bt,
+                                                         float* __restrict__ p) {
+    const uint32_t j = blockIdx.x * kBlock + threadIdx.x;
+    if (j >= d) return;
+    float s = scales[0];
+    if (bt.B) {
+        const uint32_t tb = bt.tile_blk[j / kColTile];
+        s = scales[(tb >> 31) ? block_of(bt, tb & 0x7fffffffu, j) : tb];
+    }
+    p[j] = ((bytes[j / 8] >> (j % 8)) & 1u) ? -s : s;
+}
+
 // Plain device copy (128-bit), used to measure the achievable streaming bandwidth next to the
 // step's kernels and to calibrate byte counters.
 __global__ __launch_bounds__(kBlock) void k_copy16(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {

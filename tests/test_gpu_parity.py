@@ -348,6 +348,38 @@ def test_full_size_c3_resnet18_blocksign():
                 assert H.bit_equal(x[i].cpu().numpy(), xo[i]), f"step {t} row {i}"
 
 
+# ---- wire form of the sign messages ----------------------------------------------------------------
+@pytest.mark.parametrize("comp", ["sign", "blocksign"])
+@pytest.mark.parametrize("N,d", [(2, 8), (3, 1001), (4, 70_003), (2, 262_144)])
+def test_sign_message_wire_form_round_trip(N, d, comp):
+    _say(f"case wire N={N} d={d} {comp}")
+    import oracle
+    from paper_2402_11857_amd import LiecContext
+
+    off = [0, d] if d < 16 else sorted({0, 5, d // 3, d // 2 + 1, d})
+    w = workloads.scaled(WL["c1_tiny_sign"], N=N, d=d, worker_comp=comp, server_comp=comp)
+    g = workloads.GradientSource(w, seed=d, device=DEV).grads(0)
+    g[0, ::3] = 0.0
+    g[0, 1::5] = -0.0
+    gh = g.cpu().numpy()
+    x = torch.zeros((N, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    bits = torch.empty((d + 7) // 8, dtype=torch.uint8, device=DEV)
+    p = torch.empty(d, dtype=torch.float32, device=DEV)
+    with LiecContext(N, d, comp, comp, 0, 0, 0.1) as ctx:
+        if comp == "blocksign":
+            ctx.set_blocks(off)
+        ctx.step(g, x, e)
+        scales = ctx.block_scales()[0] if comp == "blocksign" else [[s] for s in ctx.worker_desc()["scale"]]
+        for i in range(N):
+            ctx.pack_sign_bits(i, bits)
+            ctx.unpack_sign_message(bits, scales[i], comp == "blocksign", p)
+            torch.cuda.synchronize()
+            assert np.array_equal(bits.cpu().numpy(), oracle.pack_sign(gh[i])), f"worker {i}: wire bits"
+            ref = oracle.compress_blocksign(gh[i], off)[0] if comp == "blocksign" else oracle.compress("sign", gh[i])[0]
+            assert H.bit_equal(p.cpu().numpy(), ref), f"worker {i}: decompressed message"
+
+
 # ---- averaging iteration of Algorithm 1 ------------------------------------------------------------
 @pytest.mark.parametrize("N,d", [(1, 1), (3, 1023), (4, 4096), (5, 50_003), (16, 70_000)])
 def test_sync_iteration_small_shapes(N, d):
