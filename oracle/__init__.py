@@ -14,6 +14,8 @@ from .liec_oracle import (  # noqa: F401
     compress_blocksign,
     error_update,
     pack_sign,
+    pack_topk,
+    unpack_topk,
     unpack_sign,
     server_average,
     step,

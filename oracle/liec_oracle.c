@@ -321,4 +321,40 @@ void liec_oracle_unpack_sign(const uint8_t *bytes, int64_t d, const float *scale
     }
 }
 
+static int cmp_u32_asc(const void *a, const void *b)
+{
+    uint32_t x = *(const uint32_t *)a, y = *(const uint32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* Wire form of a top-k message (Definition 2): the k kept entries as (index, value) pairs in
+ * increasing index order; 8k bytes.  Kept entries may be zero when zeros had to be admitted. */
+int liec_oracle_pack_topk(const float *v, int64_t d, int64_t k, uint32_t *idx, float *val)
+{
+    if (k < 1 || k > d || d > (int64_t)0x7fffffff)
+        return 1;
+    uint64_t *order = (uint64_t *)malloc((size_t)d * sizeof *order);
+    if (!order)
+        return 2;
+    for (int64_t j = 0; j < d; ++j)
+        order[j] = ((uint64_t)abs_key(v[j]) << 32) | (uint64_t)(0xffffffffu - (uint32_t)j);
+    qsort(order, (size_t)d, sizeof *order, cmp_u64_desc);
+    for (int64_t r = 0; r < k; ++r)
+        idx[r] = 0xffffffffu - (uint32_t)(order[r] & 0xffffffffu);
+    free(order);
+    qsort(idx, (size_t)k, sizeof *idx, cmp_u32_asc);
+    for (int64_t r = 0; r < k; ++r)
+        val[r] = v[idx[r]];
+    return 0;
+}
+
+/* Decompression: zeros everywhere except the listed entries. */
+void liec_oracle_unpack_topk(const uint32_t *idx, const float *val, int64_t k, int64_t d, float *p)
+{
+    for (int64_t j = 0; j < d; ++j)
+        p[j] = 0.0f;
+    for (int64_t r = 0; r < k; ++r)
+        p[idx[r]] = val[r];
+}
+
 int liec_oracle_desc_size(void) { return (int)sizeof(oracle_desc); }

@@ -85,6 +85,11 @@ def _load():
         lib.liec_oracle_pack_sign.argtypes = [fp, ctypes.c_int64, u8p]
         lib.liec_oracle_unpack_sign.restype = None
         lib.liec_oracle_unpack_sign.argtypes = [u8p, ctypes.c_int64, fp, ip, ctypes.c_int32, fp]
+        u32p = ctypes.POINTER(ctypes.c_uint32)
+        lib.liec_oracle_pack_topk.restype = ctypes.c_int
+        lib.liec_oracle_pack_topk.argtypes = [fp, ctypes.c_int64, ctypes.c_int64, u32p, fp]
+        lib.liec_oracle_unpack_topk.restype = None
+        lib.liec_oracle_unpack_topk.argtypes = [u32p, fp, ctypes.c_int64, ctypes.c_int64, fp]
         lib.liec_oracle_step_sync.restype = ctypes.c_int
         lib.liec_oracle_step_sync.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_float, fp, fp, fp, fp]
         lib.liec_oracle_desc_size.restype = ctypes.c_int
@@ -271,4 +276,25 @@ def unpack_sign(bits: np.ndarray, d: int, scales, blocks=None) -> np.ndarray:
         off = _offsets(blocks)
         offp, B = off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), off.size - 1
     lib.liec_oracle_unpack_sign(bits.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), d, _ptr(sc), offp, B, _ptr(p))
+    return p
+
+
+def pack_topk(v: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Wire form of a top-k message: (indices ascending, values), k entries each."""
+    lib = _load()
+    v = _f32(v)
+    idx = np.empty(k, dtype=np.uint32)
+    val = np.empty(k, dtype=np.float32)
+    rc = lib.liec_oracle_pack_topk(_ptr(v), v.shape[0], k, idx.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), _ptr(val))
+    if rc != 0:
+        raise ValueError(f"liec_oracle_pack_topk failed with code {rc}")
+    return idx, val
+
+
+def unpack_topk(idx: np.ndarray, val: np.ndarray, d: int) -> np.ndarray:
+    lib = _load()
+    idx = np.ascontiguousarray(idx, dtype=np.uint32)
+    val = _f32(np.ascontiguousarray(val, dtype=np.float32))
+    p = np.empty(d, dtype=np.float32)
+    lib.liec_oracle_unpack_topk(idx.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), _ptr(val), idx.size, d, _ptr(p))
     return p

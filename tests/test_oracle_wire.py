@@ -21,3 +21,18 @@ def test_unpack_inverts_pack_into_the_compressed_message(oracle):
     off = [0, 5, 1000, 1001, 3001]
     pb, scales = oracle.compress_blocksign(v, off)
     assert np.array_equal(oracle.unpack_sign(oracle.pack_sign(v), v.size, scales, off), pb)
+
+
+def test_topk_message_lists_the_kept_entries_in_index_order(oracle):
+    rng = np.random.default_rng(2)
+    for d, k in ((1, 1), (40, 7), (64, 64), (5000, 123)):
+        v = rng.choice(np.array([0.0, -0.0, 0.5, -0.5, 1.0, 2.0, -2.0], dtype=np.float32), size=d)
+        m = rng.random(d) < 0.5
+        v[m] = rng.standard_normal(m.sum()).astype(np.float32)
+        idx, val = oracle.pack_topk(v, k)
+        assert idx.size == k and np.all(np.diff(idx.astype(np.int64)) > 0)         # 8k bytes, ascending, distinct
+        assert np.array_equal(val.view(np.uint32), v[idx].view(np.uint32))
+        brute = sorted(sorted(range(d), key=lambda j: (-abs(float(v[j])), j))[:k])  # Definition 2, ties to lower index
+        assert idx.tolist() == brute
+        p, _ = oracle.compress("topk", v, k)
+        assert np.array_equal(oracle.unpack_topk(idx, val, d).view(np.uint32), p.view(np.uint32))
