@@ -176,6 +176,25 @@ liec_status liec_pack_sign_bits(liec_ctx *ctx, int32_t worker, uint8_t *out);
 liec_status liec_unpack_sign_message(liec_ctx *ctx, const uint8_t *bits, const float *scales,
                                      int32_t blockwise, float *p_out);
 
+/*
+ * Wire form of worker `worker`'s top-k message of the last step (Definition 2):
+ * its worker_k kept entries as (index, value) pairs in increasing index order,
+ * written to the DEVICE arrays idx_out / val_out (worker_k entries each, 8k
+ * bytes in all).  `grads` must be the [N, d] DEVICE tensor the last liec_step
+ * was given (the library does not keep it).  Enqueued on the context's stream;
+ * the first call allocates a small scratch array.
+ */
+liec_status liec_pack_topk_message(liec_ctx *ctx, const float *grads, int32_t worker, uint32_t *idx_out,
+                                   float *val_out);
+
+/*
+ * Decompression of such a message: p_out (DEVICE, [d]) is zero except
+ * p_out[idx[r]] = val[r] for r < k.  idx / val: DEVICE arrays of k entries with
+ * distinct indices below d.
+ */
+liec_status liec_unpack_topk_message(liec_ctx *ctx, const uint32_t *idx, const float *val, int64_t k,
+                                     float *p_out);
+
 /* Learning-rate schedules (the paper decays eta during training): takes effect
  * from the next liec_step. */
 liec_status liec_set_lr(liec_ctx *ctx, float lr);

@@ -80,6 +80,10 @@ def lib():
         L.liec_pack_sign_bits.argtypes = [vp, i32, vp]
         L.liec_unpack_sign_message.restype = ctypes.c_int
         L.liec_unpack_sign_message.argtypes = [vp, vp, ctypes.POINTER(f32), i32, vp]
+        L.liec_pack_topk_message.restype = ctypes.c_int
+        L.liec_pack_topk_message.argtypes = [vp, vp, i32, vp, vp]
+        L.liec_unpack_topk_message.restype = ctypes.c_int
+        L.liec_unpack_topk_message.argtypes = [vp, vp, vp, i64, vp]
         L.liec_set_lr.restype = ctypes.c_int
         L.liec_set_lr.argtypes = [vp, f32]
         L.liec_get_info.restype = ctypes.c_int
@@ -242,6 +246,17 @@ class LiecContext:
         arr = (ctypes.c_float * len(sc))(*sc)
         _check(lib().liec_unpack_sign_message(self._h, bits.data_ptr(), arr, 1 if blockwise else 0, out.data_ptr()),
                "liec_unpack_sign_message")
+
+    def pack_topk_message(self, grads: torch.Tensor, worker: int, idx_out: torch.Tensor, val_out: torch.Tensor) -> None:
+        assert idx_out.is_cuda and idx_out.dtype == torch.int32 and idx_out.is_contiguous()
+        assert val_out.is_cuda and val_out.dtype == torch.float32 and val_out.numel() == idx_out.numel()
+        _check(lib().liec_pack_topk_message(self._h, _dev_ptr(grads, (self.N, self.d), "grads"), worker,
+                                            idx_out.data_ptr(), val_out.data_ptr()), "liec_pack_topk_message")
+
+    def unpack_topk_message(self, idx: torch.Tensor, val: torch.Tensor, out: torch.Tensor) -> None:
+        assert idx.is_cuda and idx.dtype == torch.int32 and val.dtype == torch.float32 and idx.numel() == val.numel()
+        _check(lib().liec_unpack_topk_message(self._h, idx.data_ptr(), val.data_ptr(), idx.numel(),
+                                              _dev_ptr(out, (self.d,), "out")), "liec_unpack_topk_message")
 
     def set_lr(self, lr: float) -> None:
         liec_set_lr(self._h, lr)

@@ -99,6 +99,7 @@ struct liec_ctx {
     float* blk_scales = nullptr;               // [(N + 1) * B]
     double* blk_l1 = nullptr;                  // [(N + 1) * B]
     int64_t blk_bytes = 0;
+    uint32_t* wire_tiles = nullptr;            // [nwt + 1] per-tile counts / offsets of liec_pack_topk_message
     float* wire_scales = nullptr;              // [max(B, 1)] staging for liec_unpack_sign_message
     uint32_t wire_scales_len = 0;
 
@@ -143,6 +144,7 @@ BlockTable block_table(const liec_ctx* c) { return BlockTable{c->tile_blk, c->bl
 void free_scratch(liec_ctx* c) {
     free_blocks(c);
     (void)hipFree(c->wire_scales);
+    (void)hipFree(c->wire_tiles);
     (void)hipFree(c->desc);
     (void)hipFree(c->vbuf);
     (void)hipFree(c->w_partial);
@@ -640,6 +642,7 @@ liec_status liec_unpack_sign_message(liec_ctx* c, const uint8_t* bits, const flo
     if (c->wire_scales_len < n) {
         e = hipStreamSynchronize(c->stream);
         (void)hipFree(c->wire_scales);
+    (void)hipFree(c->wire_tiles);
         c->wire_scales = nullptr;
         c->wire_scales_len = 0;
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->wire_scales), (size_t)n * sizeof(float));
@@ -655,6 +658,49 @@ liec_status liec_unpack_sign_message(liec_ctx* c, const uint8_t* bits, const flo
     if (!blockwise) bt.B = 0;
     const uint32_t d = (uint32_t)c->d;
     k_unpack_sign<<<(d + kBlock - 1) / kBlock, kBlock, 0, c->stream>>>(bits, d, c->wire_scales, bt, p_out);
+    if (hipGetLastError() != hipSuccess) {
+        c->broken = true;
+        return LIEC_EDEVICE;
+    }
+    return LIEC_OK;
+}
+
+liec_status liec_pack_topk_message(liec_ctx* c, const float* grads, int32_t worker, uint32_t* idx_out, float* val_out) {
+    if (!c || !grads || !idx_out || !val_out || worker < 0 || worker >= c->N) return LIEC_EINVAL;
+    if (c->broken) return LIEC_EDEVICE;
+    if (c->worker_comp != kTopk || c->steps_done == 0 || ((uintptr_t)grads & 3u)) return LIEC_EINVAL;
+    if (!c->wire_tiles) {
+        if (hipStreamSynchronize(c->stream) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void**>(&c->wire_tiles), ((size_t)c->nwt + 1) * sizeof(uint32_t)) != hipSuccess) {
+            (void)hipGetLastError();
+            c->wire_tiles = nullptr;
+            return LIEC_ENOMEM;
+        }
+    }
+    const uint32_t d = (uint32_t)c->d, k = (uint32_t)c->worker_k;
+    const float* row = grads + (size_t)worker * (size_t)c->d;
+    const bool vec = (c->d % 4 == 0) && (((uintptr_t)grads & 15u) == 0);
+    const RowDesc* rd = c->desc + worker;
+    const uint32_t blocks = c->agg_blocks;
+    if (vec) k_topk_count<true><<<blocks, kBlock, 0, c->stream>>>(row, d, c->nwt, rd, c->wire_tiles);
+    else k_topk_count<false><<<blocks, kBlock, 0, c->stream>>>(row, d, c->nwt, rd, c->wire_tiles);
+    k_scan_u32<<<1, 1024, 0, c->stream>>>(c->wire_tiles, c->nwt, c->wire_tiles + c->nwt);
+    if (vec) k_topk_emit<true><<<blocks, kBlock, 0, c->stream>>>(row, d, c->nwt, rd, c->wire_tiles, k, idx_out, val_out);
+    else k_topk_emit<false><<<blocks, kBlock, 0, c->stream>>>(row, d, c->nwt, rd, c->wire_tiles, k, idx_out, val_out);
+    if (hipGetLastError() != hipSuccess) {
+        c->broken = true;
+        return LIEC_EDEVICE;
+    }
+    return LIEC_OK;
+}
+
+liec_status liec_unpack_topk_message(liec_ctx* c, const uint32_t* idx, const float* val, int64_t k, float* p_out) {
+    if (!c || !idx || !val || !p_out || k < 0 || k > c->d) return LIEC_EINVAL;
+    if (c->broken) return LIEC_EDEVICE;
+    const uint32_t d = (uint32_t)c->d;
+    k_fill_f32<<<std::min<uint32_t>((d + kBlock - 1) / kBlock, 8192u), kBlock, 0, c->stream>>>(p_out, d, 0.f);
+    if (k > 0)
+        k_scatter_pairs<<<((uint32_t)k + kBlock - 1) / kBlock, kBlock, 0, c->stream>>>(idx, val, (uint32_t)k, d, p_out);
     if (hipGetLastError() != hipSuccess) {
         c->broken = true;
         return LIEC_EDEVICE;

@@ -380,6 +380,34 @@ def test_sign_message_wire_form_round_trip(N, d, comp):
             assert H.bit_equal(p.cpu().numpy(), ref), f"worker {i}: decompressed message"
 
 
+@pytest.mark.parametrize("N,d,k", [(2, 9, 3), (3, 1001, 50), (4, 70_003, 700), (2, 262_144, 262_144), (2, 5000, 1)])
+def test_topk_message_wire_form_round_trip(N, d, k):
+    _say(f"case wire topk N={N} d={d} k={k}")
+    import oracle
+    from paper_2402_11857_amd import LiecContext
+
+    w = workloads.scaled(WL["c2_topk_mid"], N=N, d=d, worker_comp="topk", server_comp="sign", worker_k=k, server_k=0)
+    g = workloads.GradientSource(w, seed=d + k, device=DEV).grads(0)
+    g = workloads.inject_ties(g, seed=k, frac_zero=0.2, frac_dup=0.3)
+    gh = g.cpu().numpy()
+    x = torch.zeros((N, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    idx = torch.empty(k, dtype=torch.int32, device=DEV)
+    val = torch.empty(k, dtype=torch.float32, device=DEV)
+    p = torch.empty(d, dtype=torch.float32, device=DEV)
+    with LiecContext(N, d, "topk", "sign", k, 0, 0.1) as ctx:
+        ctx.step(g, x, e)
+        for i in range(N):
+            idx.fill_(-1)
+            ctx.pack_topk_message(g, i, idx, val)
+            ctx.unpack_topk_message(idx, val, p)
+            torch.cuda.synchronize()
+            ri, rv = oracle.pack_topk(gh[i], k)
+            assert np.array_equal(idx.cpu().numpy().view(np.uint32), ri), f"worker {i}: indices"
+            assert H.bit_equal(val.cpu().numpy(), rv), f"worker {i}: values"
+            assert H.bit_equal(p.cpu().numpy(), oracle.compress("topk", gh[i], k)[0]), f"worker {i}: decompressed"
+
+
 # ---- averaging iteration of Algorithm 1 ------------------------------------------------------------
 @pytest.mark.parametrize("N,d", [(1, 1), (3, 1023), (4, 4096), (5, 50_003), (16, 70_000)])
 def test_sync_iteration_small_shapes(N, d):
