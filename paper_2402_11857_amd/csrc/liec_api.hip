@@ -81,7 +81,8 @@ struct liec_ctx {
     float* vbuf = nullptr;                     // [d]  compensated average v
     double* w_partial = nullptr;               // [N * row_blocks]
     double* s_partial = nullptr;               // [agg_blocks]
-    uint16_t* bits = nullptr;                  // [N * nwt * 64] sign bits or candidate bitmap
+    uint16_t* bits = nullptr;                  // [N * nwt * 64] sign bits (sign operators)
+    uint64_t* gbits = nullptr;                 // [N * nwt * 4] group bitmap of the candidates (top-k workers)
     uint2* list = nullptr;                     // [(N + 1) * cap] candidates (key, index)
     uint32_t* sure_partial = nullptr;          // [(N + 1) * part_stride]
     uint32_t* ghist = nullptr;                 // [(N + 1) * kHistBins]
@@ -150,6 +151,7 @@ void free_scratch(liec_ctx* c) {
     (void)hipFree(c->w_partial);
     (void)hipFree(c->s_partial);
     (void)hipFree(c->bits);
+    (void)hipFree(c->gbits);
     (void)hipFree(c->list);
     (void)hipFree(c->sure_partial);
     (void)hipFree(c->ghist);
@@ -188,7 +190,7 @@ struct Launcher {
 // asks for it, so the warm path costs one pass over the data and the others return at once.
 template <bool VEC>
 void launch_topk_select(Launcher& L, const float* src, size_t row_stride, uint32_t rows, uint32_t row0, uint32_t k,
-                        uint16_t* bits, uint32_t blocks, uint32_t cold_blocks, int slot0) {
+                        uint64_t* bits, uint32_t blocks, uint32_t cold_blocks, int slot0) {
     liec_ctx* c = L.c;
     const uint32_t d = (uint32_t)c->d;
     hipStream_t st = c->stream;
@@ -256,11 +258,11 @@ void launch_aggregate(Launcher& L, const float* grads, const float* e, bool srv_
     const uint32_t d = (uint32_t)c->d;
     L.begin(S_AGGREGATE);
     if (srv_l1)
-        k_aggregate<WC, true, VEC><<<c->agg_blocks, kBlock, 0, c->stream>>>(grads, c->bits, c->N, d, c->nwt, inv_n,
+        k_aggregate<WC, true, VEC><<<c->agg_blocks, kBlock, 0, c->stream>>>(grads, c->bits, c->gbits, c->N, d, c->nwt, inv_n,
                                                                              c->desc, e, c->vbuf, c->s_partial,
                                                                              block_table(c));
     else
-        k_aggregate<WC, false, VEC><<<c->agg_blocks, kBlock, 0, c->stream>>>(grads, c->bits, c->N, d, c->nwt, inv_n,
+        k_aggregate<WC, false, VEC><<<c->agg_blocks, kBlock, 0, c->stream>>>(grads, c->bits, c->gbits, c->N, d, c->nwt, inv_n,
                                                                               c->desc, e, c->vbuf, c->s_partial,
                                                                              block_table(c));
     L.end();
@@ -306,7 +308,7 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
     } else if (c->worker_comp == kBlockSign) {
         launch_block_l1<VEC>(L, grads, stride, (uint32_t)c->N, 0u, c->bits, S_W_L1);
     } else if (c->worker_comp == kTopk) {
-        launch_topk_select<VEC>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, c->bits,
+        launch_topk_select<VEC>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, c->gbits,
                                 c->filter_row_blocks, c->cold_row_blocks, S_W_SEL);
     }
 
@@ -421,7 +423,9 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     if (e == hipSuccess) e = dev_alloc(c, &c->vbuf, (size_t)c->nwt * kWaveTile);
     if (e == hipSuccess) e = dev_alloc(c, &c->w_partial, (size_t)N * c->row_blocks);
     if (e == hipSuccess) e = dev_alloc(c, &c->s_partial, (size_t)c->agg_blocks);
-    if (e == hipSuccess && worker_comp != LIEC_COMP_IDENTITY) e = dev_alloc(c, &c->bits, (size_t)N * c->nwt * 64);
+    if (e == hipSuccess && (worker_comp == LIEC_COMP_SIGN || worker_comp == LIEC_COMP_BLOCKSIGN))
+        e = dev_alloc(c, &c->bits, (size_t)N * c->nwt * 64);
+    if (e == hipSuccess && worker_comp == LIEC_COMP_TOPK) e = dev_alloc(c, &c->gbits, (size_t)N * c->nwt * 4);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->list, rows * c->cap);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->sure_partial, rows * c->part_stride);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->ghist, rows * kHistBins);

@@ -351,8 +351,10 @@ __global__ __launch_bounds__(kBlock) void k_l1_items_final(const double* __restr
 // among its ties are found without sorting:
 //   1. k_filter streams the row once against a band [lo, hi) of keys expected to hold tau:
 //      keys >= hi are only counted, keys inside the band are appended to a candidate list
-//      (key, index), and a bitmap of "key >= lo" (same layout as the sign bits) is written for
-//      the aggregation kernel.
+//      (key, index), and a group bitmap is written for the aggregation kernel: 4 words of 64 bits
+//      per wave tile, bit l of word u set when any of the 4 columns 1024t + 256u + 4l .. + 3 has
+//      key >= lo (a quarter of the bytes a per-column bitmap would take; writes are what a
+//      read stream pays most for).
 //      The band is predicted from the previous step's tau (kWarm); when there is none, or the
 //      prediction fails (k_check), the band is the first-radix-digit bin holding rank k, found by
 //      k_hist0 + k_pick_band over the whole row (kCold -> kColdBand), and the row is filtered again.
@@ -365,7 +367,7 @@ __global__ __launch_bounds__(kBlock) void k_l1_items_final(const double* __restr
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src, size_t row_stride, uint32_t d,
                                                     uint32_t nwt, uint32_t row0, RowDesc* __restrict__ desc,
-                                                    uint32_t expect_mode, uint16_t* __restrict__ bits,
+                                                    uint32_t expect_mode, uint64_t* __restrict__ gbits,
                                                     uint2* __restrict__ list, uint32_t cap,
                                                     uint32_t* __restrict__ sure_partial) {
     __shared__ uint2 stage[4][kStage];
@@ -383,13 +385,14 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
         float4 a[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
-        uint32_t word = 0;
+        uint64_t word = 0;                                     // lane u (< 4) ends up holding group word u
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
             const float av[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
             uint32_t keys[4];
             uint64_t bc[4];
+            uint64_t any = 0;
             uint32_t m = 0;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -397,10 +400,9 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
                 const bool valid = j + q < d;
                 keys[q] = key;
                 bad |= valid && key >= 0x7f800000u;
-                const bool in_lo = valid && key >= lo;
-                const uint64_t bl = __ballot(in_lo);
+                const uint64_t bl = __ballot(valid && key >= lo);
                 const uint64_t bh = __ballot(valid && key >= hi);
-                word |= (in_lo ? 1u : 0u) << (4 * u + q);
+                any |= bl;
                 nsure += __popcll(bh);
                 bc[q] = bl & ~bh;
                 m += __popcll(bc[q]);
@@ -424,8 +426,9 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
                 }
                 cnt += m;
             }
+            word = lane == (uint32_t)u ? any : word;
         }
-        if (bits) bits[((size_t)blockIdx.y * nwt + t) * 64 + lane] = (uint16_t)word;
+        if (gbits && lane < 4) gbits[((size_t)blockIdx.y * nwt + t) * 4 + lane] = word;
     }
     if (cnt) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -784,12 +787,13 @@ __device__ __forceinline__ float message_of(float g, uint32_t j, float scale, ui
 // |v| (fp64) for the server's scaled-sign operator.  grid = blocks; waves stride over wave tiles.
 //   WC == kSign / kBlockSign  read the packed sign bits instead of the gradients (blockwise: the scale
 //                   comes from the column's block);
-//   WC == kTopk     reads each row's candidate bitmap and fetches only the flagged gradients,
-//                   testing them against (tau, cut-off); per-lane sums live in LDS;
+//   WC == kTopk     reads each row's group bitmap and fetches only the flagged groups of 4
+//                   gradients, testing them against (tau, cut-off); per-lane sums live in LDS;
 //   WC == kIdentity reads the gradients.
 // ---------------------------------------------------------------------------------------------
 template <int WC, bool SRV_L1, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ grads, const uint16_t* __restrict__ bits,
+                                                       const uint64_t* __restrict__ gbits,
                                                        int N, uint32_t d, uint32_t nwt, float inv_n,
                                                        const RowDesc* __restrict__ desc, const float* __restrict__ e_in,
                                                        float* __restrict__ v_out, double* __restrict__ srv_partial,
@@ -852,20 +856,30 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
             float* my = accs + threadIdx.x;                    // slot b of this lane: my[b * kBlock]
 #pragma unroll
             for (int b = 0; b < 16; ++b) my[b * kBlock] = 0.f;
-            const uint16_t* __restrict__ bw = bits + (size_t)t * 64 + lane;
-            const size_t brow = (size_t)nwt * 64;
+            const uint64_t* __restrict__ gw = gbits + (size_t)t * 4;   // the tile's 4 group words of row 0
+            const size_t grow = (size_t)nwt * 4;
             for (int i = 0; i < N; ++i) {
                 const float* __restrict__ gi = grads + (size_t)i * d;
                 const uint32_t tau = desc[i].tau, cut = desc[i].cutoff;
-                uint32_t mask = desc[i].dense ? 0xffffu : (uint32_t)bw[(size_t)i * brow];
+                uint32_t mask = 0xfu;                          // bit u: this lane's group of chunk u is flagged
+                if (!desc[i].dense) {
+                    const uint64_t* __restrict__ w = gw + (size_t)i * grow;
+                    mask = (uint32_t)((w[0] >> lane) & 1) | (uint32_t)((w[1] >> lane) & 1) << 1 |
+                           (uint32_t)((w[2] >> lane) & 1) << 2 | (uint32_t)((w[3] >> lane) & 1) << 3;
+                }
                 while (mask) {
-                    const int b = __builtin_ctz(mask);
+                    const int u = __builtin_ctz(mask);
                     mask &= mask - 1;
-                    const uint32_t j = j0 + (b >> 2) * kChunk + (b & 3);
-                    if (j < d) {
-                        const float g = gi[j];
-                        const uint32_t key = key_of(g);
-                        if (key > tau || (key == tau && j <= cut)) my[b * kBlock] = __fadd_rn(my[b * kBlock], g);
+                    const uint32_t j = j0 + u * kChunk;
+                    const float4 g = ld4<VEC>(gi, j, d);
+                    const float gv[4] = {g.x, g.y, g.z, g.w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t key = key_of(gv[q]);
+                        if (j + q < d && (key > tau || (key == tau && j + q <= cut))) {
+                            float* slot = my + (4 * u + q) * kBlock;
+                            *slot = __fadd_rn(*slot, gv[q]);
+                        }
                     }
                 }
             }
