@@ -364,6 +364,32 @@ __global__ __launch_bounds__(kBlock) void k_l1_items_final(const double* __restr
 // All decisions are taken on the device per row; the host always enqueues the same kernels.
 // `row0` is added to blockIdx.y to address per-row state (the server's vector uses row N).
 // ---------------------------------------------------------------------------------------------
+// One chunk (256 columns, 4 per lane) of the filter: updates the per-lane count of keys >= hi and the
+// running maximum key, returns the ballot of "any of my 4 columns has key >= lo" and, per component,
+// the ballots of the candidates lo <= key < hi.  FULL: every column of the chunk is below d.
+template <bool FULL>
+__device__ __forceinline__ uint64_t filter_chunk(const float4 a, uint32_t j, uint32_t d, uint32_t lo, uint32_t hi,
+                                                 uint32_t (&keys)[4], uint64_t (&bc)[4], uint64_t& any_cand,
+                                                 uint32_t& n_hi, uint32_t& kmax) {
+    const float av[4] = {a.x, a.y, a.z, a.w};
+    uint64_t any_lo = 0;
+    any_cand = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t key = key_of(av[q]);
+        const bool valid = FULL || j + q < d;
+        const bool ge_lo = valid && key >= lo, ge_hi = valid && key >= hi;
+        keys[q] = key;
+        kmax = max(kmax, valid ? key : 0u);
+        n_hi += ge_hi ? 1u : 0u;
+        const uint64_t bl = __ballot(ge_lo), bh = __ballot(ge_hi);
+        any_lo |= bl;
+        bc[q] = bl & ~bh;
+        any_cand |= bc[q];
+    }
+    return any_lo;
+}
+
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src, size_t row_stride, uint32_t d,
                                                     uint32_t nwt, uint32_t row0, RowDesc* __restrict__ desc,
@@ -379,35 +405,24 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
     uint2* __restrict__ out = list + (size_t)row * cap;
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     uint2* st = stage[wave];
-    uint32_t cnt = 0, nsure = 0;
-    bool bad = false;
+    uint32_t cnt = 0;                                           // staged candidates (wave-uniform)
+    uint32_t n_hi = 0, kmax = 0;                                // per lane: keys >= hi seen, largest key seen
     for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
         float4 a[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
-        uint64_t word = 0;                                     // lane u (< 4) ends up holding group word u
+        const bool full = (t + 1) * (uint32_t)kWaveTile <= d;  // wave-uniform
+        uint64_t word = 0;                                      // lane u (< 4) ends up holding group word u
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
-            const float av[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
             uint32_t keys[4];
-            uint64_t bc[4];
-            uint64_t any = 0;
-            uint32_t m = 0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t key = key_of(av[q]);
-                const bool valid = j + q < d;
-                keys[q] = key;
-                bad |= valid && key >= 0x7f800000u;
-                const uint64_t bl = __ballot(valid && key >= lo);
-                const uint64_t bh = __ballot(valid && key >= hi);
-                any |= bl;
-                nsure += __popcll(bh);
-                bc[q] = bl & ~bh;
-                m += __popcll(bc[q]);
-            }
-            if (m) {                                            // wave-uniform
+            uint64_t bc[4], any_cand;
+            const uint64_t any_lo = full ? filter_chunk<true>(a[u], j, d, lo, hi, keys, bc, any_cand, n_hi, kmax)
+                                         : filter_chunk<false>(a[u], j, d, lo, hi, keys, bc, any_cand, n_hi, kmax);
+            word = lane == (uint32_t)u ? any_lo : word;
+            if (any_cand) {                                     // wave-uniform
+                const uint32_t m = __popcll(bc[0]) + __popcll(bc[1]) + __popcll(bc[2]) + __popcll(bc[3]);
                 if (cnt + m > kStage) {                         // flush the staged candidates
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     uint32_t base = 0;
@@ -426,7 +441,6 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
                 }
                 cnt += m;
             }
-            word = lane == (uint32_t)u ? any : word;
         }
         if (gbits && lane < 4) gbits[((size_t)blockIdx.y * nwt + t) * 4 + lane] = word;
     }
@@ -438,8 +452,11 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
         for (uint32_t s = lane; s < cnt; s += 64)
             if (base + s < cap) out[base + s] = st[s];
     }
-    if (__ballot(bad) && lane == 0) atomicOr(&desc[row].nonfinite_acc, 1u);
-    if (lane == 0) wsure[wave] = nsure;
+    // keys at or above 0x7f800000 are Inf / NaN
+    if (__ballot(kmax >= 0x7f800000u) && lane == 0) atomicOr(&desc[row].nonfinite_acc, 1u);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) n_hi += __shfl_down(n_hi, o, 64);
+    if (lane == 0) wsure[wave] = n_hi;
     __syncthreads();
     if (threadIdx.x == 0)
         sure_partial[(size_t)row * gridDim.x + blockIdx.x] = wsure[0] + wsure[1] + wsure[2] + wsure[3];
