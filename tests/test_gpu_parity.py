@@ -263,6 +263,30 @@ def test_step_rejects_bad_buffers_and_reports_nonfinite_input():
         assert ctx.info_status()[1] == 4
 
 
+def test_per_kernel_timing_and_scratch_accounting():
+    _say("case profile api")
+    w = workloads.scaled(WL["c2_topk_mid"], N=4, d=200_000, worker_comp="topk", server_comp="sign", worker_k=2000)
+    g = workloads.GradientSource(w, seed=1, device=DEV).grads(0)
+    x = torch.zeros((w.N, w.d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    with _ctx(w) as ctx:
+        assert ctx.scratch_bytes() > w.d * 4                  # at least the v buffer
+        ctx.step(g, x, e)
+        ctx.profile_begin(2, update_only=True)
+        for _ in range(3):                                    # only the first two steps are recorded
+            ctx.step(g, x, e)
+        got = ctx.profile_end()
+        assert set(got) == {"update"} and got["update"][1] == 2 and got["update"][0] > 0
+        ctx.profile_begin(1)
+        ctx.step(g, x, e)
+        got = ctx.profile_end()
+        assert {"worker_filter_warm", "server_aggregate", "update"} <= set(got)
+        assert all(n == 1 and ms >= 0 for ms, n in got.values())
+        ctx.step(g, x, e)                                     # recording is off again
+        assert ctx.profile_end() == {}
+        assert ctx.info().steps_done == 6
+
+
 # ---- Blockwise-SignSGD (Definition 5) --------------------------------------------------------------
 BLOCK_TABLES = {
     "one": lambda d: [0, d],
