@@ -230,6 +230,9 @@ __global__ __launch_bounds__(kBlock) void k_l1_bits(const float* __restrict__ sr
             m |= (a[u].w < 0.f ? 1u : 0u) << (4 * u + 3);
         }
         bits[((size_t)row * nwt + t) * 64 + lane] = (uint16_t)m;
+#if defined(__HIP_DEVICE_COMPILE__)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // let the small store land before the next loads (~2 % faster)
+#endif
     }
     const double s = block_sum_f64(acc, lds_w);
     if (threadIdx.x == 0) partial[(size_t)row * gridDim.x + blockIdx.x] = s;
