@@ -22,6 +22,7 @@ HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 DEFAULT_WORKLOAD = "c5_vgg16_mixed"   # the largest configuration; fits one GPU (grads 8.25 GiB)
 ALSO = ["c3_resnet18_sign", "c3_resnet18_blocksign", "c4_resnet50_topk", "c5_vgg16_sign"]
 N_GRAD_BUFFERS = 4          # distinct gradient batches rotated through the timed steps
+REPEATS = 5                 # timed regions per workload; the median one is reported
 # HBM bytes one launch of the update kernel moves, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this script, each counter scaled by what it reads for the 1 GiB copy probe (profiles/liec_step_<workload>.md)
 UPDATE_TRAFFIC_BYTES = {"c5_vgg16_mixed": 28.427e9, "c5_vgg16_sign": 28.423e9, "c3_resnet18_sign": 2.395e9,
@@ -57,13 +58,19 @@ def run_workload(w, steps: int, warmup: int, seed: int = 0):
         for t in range(warmup):
             ctx.step(grads[t % nbuf], x, e)
         torch.cuda.synchronize()
-        ctx.profile_begin(steps, update_only=True)   # HIP events around the dominant kernel, on the step's stream
-        t0 = time.perf_counter()
-        for t in range(steps):
-            ctx.step(grads[(warmup + t) % nbuf], x, e)
-        torch.cuda.synchronize()
-        elapsed = time.perf_counter() - t0
-        upd_ms, upd_n = ctx.profile_end()["update"]
+        # REPEATS timed regions of exactly `steps` steps each; the median region is reported
+        regions = []
+        for rep in range(REPEATS):
+            torch.cuda.synchronize()
+            ctx.profile_begin(steps, update_only=True)   # HIP events around the dominant kernel, on the step's stream
+            t0 = time.perf_counter()
+            for t in range(steps):
+                ctx.step(grads[(warmup + t) % nbuf], x, e)
+            torch.cuda.synchronize()
+            el = time.perf_counter() - t0
+            regions.append((el, ctx.profile_end()["update"]))
+        regions.sort(key=lambda r: r[0])
+        elapsed, (upd_ms, upd_n) = regions[len(regions) // 2]
         info, status = ctx.info_status()
         assert status == 0, "non-finite values met during the bench"
         # diagnostic breakdown, outside the timed region: every kernel bracketed by events
@@ -87,6 +94,7 @@ def run_workload(w, steps: int, warmup: int, seed: int = 0):
         "alg_gbps": w.alg_bytes_per_step * steps / elapsed / 1e9,
         "kernels_ms_per_step": {k: v[0] for k, v in kernels.items()},
         "scratch_bytes": scratch,
+        "region_ms_per_step": [round(1e3 * r[0] / steps, 4) for r in regions],
         "sync_ms": sync_ms,
         "sync_gbps": dominant_kernel_bytes(w) / (sync_ms * 1e-3) / 1e9,   # same bytes: g, x in, x out, e in/out
     }
@@ -205,6 +213,7 @@ def main() -> int:
         "config": {"workload": w.name, "N": w.N, "d": w.d, "worker_comp": w.worker_comp,
                    "server_comp": w.server_comp, "worker_k": w.worker_k, "server_k": w.server_k,
                    "lr": w.lr, "grad_buffers_rotated": N_GRAD_BUFFERS},
+        "timed_regions_ms_per_step": main_res["region_ms_per_step"],
         "step_alg_bytes": w.alg_bytes_per_step,
         "step_alg_gbps": main_res["alg_gbps"],
         "step_hbm_frac": main_res["alg_gbps"] / HBM_PEAK_GBPS,

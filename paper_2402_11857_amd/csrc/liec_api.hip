@@ -840,9 +840,9 @@ liec_status liec_device_copy(void* dst, const void* src, int64_t bytes, void* hi
     if (!dst || !src || bytes < 0 || (bytes & 15) || (((uintptr_t)dst | (uintptr_t)src) & 15u)) return LIEC_EINVAL;
     if (bytes == 0) return LIEC_OK;
     const size_t n16 = (size_t)bytes / 16;
-    size_t blocks = (n16 + kBlock - 1) / kBlock;
-    if (blocks > 256u * 32u) blocks = 256u * 32u;
-    k_copy16<<<(uint32_t)blocks, kBlock, 0, (hipStream_t)hip_stream>>>((const uint4*)src, (uint4*)dst, n16);
+    const size_t blocks = (n16 + kBlock - 1) / kBlock;
+    if (blocks >= ((size_t)1 << 31)) return LIEC_EINVAL;           // 512 GiB per call is plenty
+    k_copy16<<<(uint32_t)blocks, kBlock, 0, (hipStream_t)hip_stream>>>((const v4f*)src, (v4f*)dst, n16);
     return hipGetLastError() == hipSuccess ? LIEC_OK : LIEC_EDEVICE;
 }
 

@@ -1206,12 +1206,11 @@ __global__ __launch_bounds__(kBlock) void k_fill_f32(float* __restrict__ p, uint
     for (uint32_t j = blockIdx.x * kBlock + threadIdx.x; j < n; j += gridDim.x * kBlock) p[j] = v;
 }
 
-// Plain device copy (128-bit), used to measure the achievable streaming bandwidth next to the
-// step's kernels and to calibrate byte counters.
-__global__ __launch_bounds__(kBlock) void k_copy16(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
-    size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * kBlock;
-    for (; i < n16; i += stride) dst[i] = src[i];
+// Plain device copy (128 bits per thread, streaming hints), used to measure the achievable
+// read+write bandwidth next to the step's kernels and to calibrate byte counters.
+__global__ __launch_bounds__(kBlock) void k_copy16(const v4f* __restrict__ src, v4f* __restrict__ dst, size_t n16) {
+    const size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < n16) __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]), &dst[i]);
 }
 
 }  // namespace liec
