@@ -143,7 +143,7 @@ struct Pick {
 __device__ __forceinline__ Pick block_pick(const uint32_t* __restrict__ h, int nbins, uint32_t rank,
                                            uint32_t* part, uint32_t* res) {
     const int per = nbins >> 8;   // 2, 4 or 16 bins per thread
-    const uint32_t tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint32_t local[16];
     uint32_t sum = 0;
 #pragma unroll
@@ -151,24 +151,23 @@ __device__ __forceinline__ Pick block_pick(const uint32_t* __restrict__ h, int n
         local[q] = (tid < 256 && q < per) ? h[tid * per + q] : 0u;
         sum += local[q];
     }
-    if (tid < 256) part[tid] = sum;
+    // count in the bins above this thread's range: suffix sum over the 256 threads (lanes, then waves)
+    uint32_t incl = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_down(incl, o, 64);
+        if (lane + o < 64) incl += up;
+    }
+    if (tid < 256 && lane == 0) part[wave] = incl;             // total of wave `wave`
     if (tid == 0) {
         res[0] = 0;
         res[1] = 1;
         res[2] = 0;
     }
     __syncthreads();
-    if (tid == 0) {
-        uint32_t run = 0;
-        for (int t = 255; t >= 0; --t) {
-            const uint32_t s = part[t];
-            part[t] = run;            // count in the bins above thread t's range
-            run += s;
-        }
-    }
-    __syncthreads();
     if (tid < 256) {
-        const uint32_t above = part[tid];
+        uint32_t above = incl - sum;
+        for (uint32_t w = wave + 1; w < 4; ++w) above += part[w];
         if (above < rank && rank <= above + sum) {   // true for exactly one thread
             uint32_t run = above, bin = tid * per, cnt = local[0];
             bool done = false;
