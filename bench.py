@@ -25,8 +25,8 @@ N_GRAD_BUFFERS = 4          # distinct gradient batches rotated through the time
 REPEATS = 5                 # timed regions per workload; the median one is reported
 # HBM bytes one launch of the update kernel moves, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this script, each counter scaled by what it reads for the 1 GiB copy probe (profiles/liec_step_<workload>.md)
-UPDATE_TRAFFIC_BYTES = {"c5_vgg16_mixed": 28.427e9, "c5_vgg16_sign": 28.423e9, "c3_resnet18_sign": 2.395e9,
-                        "c4_resnet50_topk": 10.252e9}
+UPDATE_TRAFFIC_BYTES = {"c5_vgg16_mixed": 28.404e9, "c5_vgg16_sign": 28.400e9, "c3_resnet18_sign": 2.394e9,
+                        "c4_resnet50_topk": 10.236e9}
 
 
 def log(msg: str) -> None:
