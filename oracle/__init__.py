@@ -8,6 +8,7 @@ from .liec_oracle import (  # noqa: F401
     SIGN,
     TOPK,
     BLOCKSIGN,
+    RANDK,
     Desc,
     build,
     compress,
@@ -15,6 +16,8 @@ from .liec_oracle import (  # noqa: F401
     error_update,
     pack_sign,
     pack_topk,
+    pack_randk,
+    randk_priorities,
     unpack_topk,
     unpack_sign,
     server_average,

@@ -25,6 +25,12 @@
  *     lower index wins, and exactly k entries are kept even if some are zero.
  *     Magnitudes are compared through the integer key (bits & 0x7fffffff),
  *     which orders finite fp32 magnitudes exactly as |.| does.
+ *   - Definition 3: the k-subset S is drawn by giving every index a priority
+ *     from a counter-based generator keyed by (seed, draw, row) and keeping the
+ *     k indices of highest priority (ties, at most pairs, to the lower index).
+ *     `draw` counts the compressed iterations, `row` is the worker index, or N
+ *     for the server.  The generator is stated below; the HIP library carries
+ *     its own statement of it.
  *   - Algorithm 1, server average: the N messages are added in worker order
  *     in fp32 starting from +0, then one fused multiply-add with 1/N adds the
  *     global error.
@@ -39,7 +45,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORACLE_IDENTITY = 0, ORACLE_SIGN = 1, ORACLE_TOPK = 2, ORACLE_BLOCKSIGN = 3 };
+enum { ORACLE_IDENTITY = 0, ORACLE_SIGN = 1, ORACLE_TOPK = 2, ORACLE_BLOCKSIGN = 3, ORACLE_RANDK = 4 };
 
 /* What a compressed message consists of besides the per-element part. */
 typedef struct {
@@ -110,6 +116,83 @@ static int compress_topk(const float *v, int64_t d, int64_t k, float *p, oracle_
     return 0;
 }
 
+/* Definition 3 (random-k): the generator behind "S is sampled uniformly from the k-element
+ * subsets".  One 64-bit stream word per (seed, draw, row) through three rounds of a 64-bit
+ * multiply-xorshift finalizer (the SplitMix64 output function with its additive constant), then
+ * per index j a keyed 32-bit multiply-xorshift permutation of j (two odd multipliers, the
+ * stream's low word mixed in before the first and its high word between the two).  Every step
+ * of the 32-bit part is a bijection of 32-bit words, so distinct indices get distinct 32-bit
+ * words; the priority is that word without its lowest bit (31 bits, like a magnitude key). */
+static uint64_t mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+uint64_t liec_oracle_randk_stream(uint64_t seed, uint64_t draw, uint32_t row)
+{
+    const uint64_t gamma = 0x9E3779B97F4A7C15ull;
+    uint64_t z = mix64(seed + gamma);
+    z = mix64(z + draw + gamma);
+    z = mix64(z + (uint64_t)row + gamma);
+    return z;
+}
+
+uint32_t liec_oracle_randk_priority(uint64_t stream, uint32_t j)
+{
+    uint32_t h = j ^ (uint32_t)(stream & 0xffffffffu);
+    h ^= h >> 16;
+    h *= 0x85EBCA6Bu;
+    h ^= h >> 13;
+    h += (uint32_t)(stream >> 32);
+    h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h >> 1;
+}
+
+/* Priorities of the indices 0 .. d-1 in one draw (for tests of the generator). */
+void liec_oracle_randk_priorities(uint64_t seed, uint64_t draw, uint32_t row, int64_t d, uint32_t *out)
+{
+    const uint64_t stream = liec_oracle_randk_stream(seed, draw, row);
+    for (int64_t j = 0; j < d; ++j)
+        out[j] = liec_oracle_randk_priority(stream, (uint32_t)j);
+}
+
+/* Definition 3: keep the k indices of highest priority (priority descending, index ascending),
+ * zero elsewhere.  The descriptor carries the priority of the k-th kept index and that index. */
+static int compress_randk(const float *v, int64_t d, int64_t k, uint64_t seed, uint64_t draw,
+                          uint32_t row, float *p, oracle_desc *desc)
+{
+    if (k < 1 || k > d || d > (int64_t)0x7fffffff)
+        return 1;
+    uint64_t *order = (uint64_t *)malloc((size_t)d * sizeof *order);
+    if (!order)
+        return 2;
+    const uint64_t stream = liec_oracle_randk_stream(seed, draw, row);
+    for (int64_t j = 0; j < d; ++j)
+        order[j] = ((uint64_t)liec_oracle_randk_priority(stream, (uint32_t)j) << 32) |
+                   (uint64_t)(0xffffffffu - (uint32_t)j);
+    qsort(order, (size_t)d, sizeof *order, cmp_u64_desc);
+    if (p) {
+        for (int64_t j = 0; j < d; ++j)
+            p[j] = 0.0f;
+        for (int64_t r = 0; r < k; ++r) {
+            int64_t j = (int64_t)(0xffffffffu - (uint32_t)(order[r] & 0xffffffffu));
+            p[j] = v[j];
+        }
+    }
+    uint32_t tau = (uint32_t)(order[k - 1] >> 32);
+    int64_t above = 0;
+    while (above < k && (uint32_t)(order[above] >> 32) > tau)
+        ++above;
+    desc->tau_key = tau;
+    desc->cutoff = (int64_t)(0xffffffffu - (uint32_t)(order[k - 1] & 0xffffffffu));
+    desc->count_above = above;
+    free(order);
+    return 0;
+}
+
 /* Definition 5 (Blockwise-SignSGD): Definition 4 applied independently to each of the B consecutive
  * blocks [off[b], off[b+1]) of v, each with its own length d_b = off[b+1] - off[b] (off[0] = 0,
  * off[B] = d, strictly increasing).  scales [B] receives the per-block scales. */
@@ -129,9 +212,17 @@ static int compress_blocksign(const float *v, int64_t d, const int64_t *off, int
     return 0;
 }
 
-/* p = C(v) for the chosen operator.  Returns 0 on success. */
+/* p = C(v) for the chosen operator.  Returns 0 on success.  (seed, draw, row) name the random
+ * draw of Definition 3 and are ignored by the other operators. */
+int liec_oracle_compress_rng(int comp, const float *v, int64_t d, int64_t k, const int64_t *off,
+                             int32_t B, uint64_t seed, uint64_t draw, uint32_t row, float *p,
+                             oracle_desc *desc, float *block_scales);
+
 int liec_oracle_compress_ex(int comp, const float *v, int64_t d, int64_t k, const int64_t *off,
-                            int32_t B, float *p, oracle_desc *desc, float *block_scales);
+                            int32_t B, float *p, oracle_desc *desc, float *block_scales)
+{
+    return liec_oracle_compress_rng(comp, v, d, k, off, B, 0, 0, 0, p, desc, block_scales);
+}
 
 int liec_oracle_compress(int comp, const float *v, int64_t d, int64_t k, float *p,
                          oracle_desc *desc)
@@ -139,8 +230,9 @@ int liec_oracle_compress(int comp, const float *v, int64_t d, int64_t k, float *
     return liec_oracle_compress_ex(comp, v, d, k, NULL, 0, p, desc, NULL);
 }
 
-int liec_oracle_compress_ex(int comp, const float *v, int64_t d, int64_t k, const int64_t *off,
-                            int32_t B, float *p, oracle_desc *desc, float *block_scales)
+int liec_oracle_compress_rng(int comp, const float *v, int64_t d, int64_t k, const int64_t *off,
+                             int32_t B, uint64_t seed, uint64_t draw, uint32_t row, float *p,
+                             oracle_desc *desc, float *block_scales)
 {
     oracle_desc local;
     if (!desc)
@@ -161,6 +253,8 @@ int liec_oracle_compress_ex(int comp, const float *v, int64_t d, int64_t k, cons
         return compress_topk(v, d, k, p, desc);
     case ORACLE_BLOCKSIGN:
         return compress_blocksign(v, d, off, B, p, block_scales);
+    case ORACLE_RANDK:
+        return compress_randk(v, d, k, seed, draw, row, p, desc);
     default:
         return 1;
     }
@@ -204,10 +298,20 @@ void liec_oracle_worker_update(const float *g_i, const float *p_i, const float *
  *   wdesc [N], sdesc [1], v_out [d] (compensated average), p_out [d] (broadcast),
  *   P_out [N,d] (uplink messages, decompressed).
  * Returns 0 on success, 1 on bad arguments, 2 when out of memory. */
+int liec_oracle_step_rng(int32_t N, int64_t d, int worker_comp, int64_t worker_k, int server_comp,
+                         int64_t server_k, float lr, const float *g, float *x, float *e,
+                         const int64_t *off, int32_t B, uint64_t seed, uint64_t draw,
+                         oracle_desc *wdesc, oracle_desc *sdesc, float *wscales, float *sscales,
+                         float *v_out, float *p_out, float *P_out);
+
 int liec_oracle_step_ex(int32_t N, int64_t d, int worker_comp, int64_t worker_k, int server_comp,
                         int64_t server_k, float lr, const float *g, float *x, float *e,
                         const int64_t *off, int32_t B, oracle_desc *wdesc, oracle_desc *sdesc,
-                        float *wscales, float *sscales, float *v_out, float *p_out, float *P_out);
+                        float *wscales, float *sscales, float *v_out, float *p_out, float *P_out)
+{
+    return liec_oracle_step_rng(N, d, worker_comp, worker_k, server_comp, server_k, lr, g, x, e, off, B,
+                                0, 0, wdesc, sdesc, wscales, sscales, v_out, p_out, P_out);
+}
 
 int liec_oracle_step(int32_t N, int64_t d, int worker_comp, int64_t worker_k, int server_comp,
                      int64_t server_k, float lr, const float *g, float *x, float *e,
@@ -220,11 +324,13 @@ int liec_oracle_step(int32_t N, int64_t d, int worker_comp, int64_t worker_k, in
 
 /* The same iteration with the block table of Definition 5 available to either side
  * (off [B+1], used where the operator is the blockwise scaled sign); wscales [N*B] and sscales [B]
- * optionally receive the per-block scales. */
-int liec_oracle_step_ex(int32_t N, int64_t d, int worker_comp, int64_t worker_k, int server_comp,
-                        int64_t server_k, float lr, const float *g, float *x, float *e,
-                        const int64_t *off, int32_t B, oracle_desc *wdesc, oracle_desc *sdesc,
-                        float *wscales, float *sscales, float *v_out, float *p_out, float *P_out)
+ * optionally receive the per-block scales.  (seed, draw) name this iteration's random draws of
+ * Definition 3: worker i draws with row i, the server with row N. */
+int liec_oracle_step_rng(int32_t N, int64_t d, int worker_comp, int64_t worker_k, int server_comp,
+                         int64_t server_k, float lr, const float *g, float *x, float *e,
+                         const int64_t *off, int32_t B, uint64_t seed, uint64_t draw,
+                         oracle_desc *wdesc, oracle_desc *sdesc, float *wscales, float *sscales,
+                         float *v_out, float *p_out, float *P_out)
 {
     if (N < 1 || d < 1 || !g || !x || !e)
         return 1;
@@ -236,13 +342,15 @@ int liec_oracle_step_ex(int32_t N, int64_t d, int worker_comp, int64_t worker_k,
 
     /* worker i: p^i = C(g_i) */
     for (int32_t i = 0; rc == 0 && i < N; ++i)
-        rc = liec_oracle_compress_ex(worker_comp, g + (size_t)i * (size_t)d, d, worker_k, off, B,
-                                     P + (size_t)i * (size_t)d, wdesc ? &wdesc[i] : NULL,
-                                     wscales ? wscales + (size_t)i * (size_t)B : NULL);
+        rc = liec_oracle_compress_rng(worker_comp, g + (size_t)i * (size_t)d, d, worker_k, off, B,
+                                      seed, draw, (uint32_t)i, P + (size_t)i * (size_t)d,
+                                      wdesc ? &wdesc[i] : NULL,
+                                      wscales ? wscales + (size_t)i * (size_t)B : NULL);
     if (rc == 0) {
         /* server: v = e + mean_i p^i ; p = C(v) ; e <- v - p */
         liec_oracle_server_average(P, N, d, e, v);
-        rc = liec_oracle_compress_ex(server_comp, v, d, server_k, off, B, p, sdesc, sscales);
+        rc = liec_oracle_compress_rng(server_comp, v, d, server_k, off, B, seed, draw, (uint32_t)N, p,
+                                      sdesc, sscales);
     }
     if (rc == 0) {
         liec_oracle_error_update(v, p, d, e);
@@ -338,6 +446,30 @@ int liec_oracle_pack_topk(const float *v, int64_t d, int64_t k, uint32_t *idx, f
         return 2;
     for (int64_t j = 0; j < d; ++j)
         order[j] = ((uint64_t)abs_key(v[j]) << 32) | (uint64_t)(0xffffffffu - (uint32_t)j);
+    qsort(order, (size_t)d, sizeof *order, cmp_u64_desc);
+    for (int64_t r = 0; r < k; ++r)
+        idx[r] = 0xffffffffu - (uint32_t)(order[r] & 0xffffffffu);
+    free(order);
+    qsort(idx, (size_t)k, sizeof *idx, cmp_u32_asc);
+    for (int64_t r = 0; r < k; ++r)
+        val[r] = v[idx[r]];
+    return 0;
+}
+
+/* Wire form of a random-k message (Definition 3): the k kept entries as (index, value) pairs in
+ * increasing index order, as for top-k. */
+int liec_oracle_pack_randk(const float *v, int64_t d, int64_t k, uint64_t seed, uint64_t draw,
+                           uint32_t row, uint32_t *idx, float *val)
+{
+    if (k < 1 || k > d || d > (int64_t)0x7fffffff)
+        return 1;
+    uint64_t *order = (uint64_t *)malloc((size_t)d * sizeof *order);
+    if (!order)
+        return 2;
+    const uint64_t stream = liec_oracle_randk_stream(seed, draw, row);
+    for (int64_t j = 0; j < d; ++j)
+        order[j] = ((uint64_t)liec_oracle_randk_priority(stream, (uint32_t)j) << 32) |
+                   (uint64_t)(0xffffffffu - (uint32_t)j);
     qsort(order, (size_t)d, sizeof *order, cmp_u64_desc);
     for (int64_t r = 0; r < k; ++r)
         idx[r] = 0xffffffffu - (uint32_t)(order[r] & 0xffffffffu);

@@ -14,8 +14,8 @@ from typing import List, Optional, Tuple
 
 import numpy as np
 
-IDENTITY, SIGN, TOPK, BLOCKSIGN = 0, 1, 2, 3
-_NAMES = {"identity": IDENTITY, "sign": SIGN, "topk": TOPK, "blocksign": BLOCKSIGN}
+IDENTITY, SIGN, TOPK, BLOCKSIGN, RANDK = 0, 1, 2, 3, 4
+_NAMES = {"identity": IDENTITY, "sign": SIGN, "topk": TOPK, "blocksign": BLOCKSIGN, "randk": RANDK}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "liec_oracle.c")
@@ -92,6 +92,22 @@ def _load():
         lib.liec_oracle_unpack_topk.argtypes = [u32p, fp, ctypes.c_int64, ctypes.c_int64, fp]
         lib.liec_oracle_step_sync.restype = ctypes.c_int
         lib.liec_oracle_step_sync.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_float, fp, fp, fp, fp]
+        u64, u32 = ctypes.c_uint64, ctypes.c_uint32
+        lib.liec_oracle_randk_stream.restype = u64
+        lib.liec_oracle_randk_stream.argtypes = [u64, u64, u32]
+        lib.liec_oracle_randk_priority.restype = u32
+        lib.liec_oracle_randk_priority.argtypes = [u64, u32]
+        lib.liec_oracle_randk_priorities.restype = None
+        lib.liec_oracle_randk_priorities.argtypes = [u64, u64, u32, ctypes.c_int64, u32p]
+        lib.liec_oracle_compress_rng.restype = ctypes.c_int
+        lib.liec_oracle_compress_rng.argtypes = [ctypes.c_int, fp, ctypes.c_int64, ctypes.c_int64, ip, ctypes.c_int32,
+                                                 u64, u64, u32, fp, dp, fp]
+        lib.liec_oracle_step_rng.restype = ctypes.c_int
+        lib.liec_oracle_step_rng.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int, ctypes.c_int64,
+                                             ctypes.c_int, ctypes.c_int64, ctypes.c_float, fp, fp, fp, ip,
+                                             ctypes.c_int32, u64, u64, dp, dp, fp, fp, fp, fp, fp]
+        lib.liec_oracle_pack_randk.restype = ctypes.c_int
+        lib.liec_oracle_pack_randk.argtypes = [fp, ctypes.c_int64, ctypes.c_int64, u64, u64, u32, u32p, fp]
         lib.liec_oracle_desc_size.restype = ctypes.c_int
         assert lib.liec_oracle_desc_size() == ctypes.sizeof(_CDesc)
         _lib = lib
@@ -120,17 +136,29 @@ def _desc(c: _CDesc) -> Desc:
     return Desc(float(c.scale), float(c.l1), int(c.tau_key), int(c.cutoff), int(c.count_above))
 
 
-def compress(comp, v: np.ndarray, k: int = 0, want_p: bool = True) -> Tuple[Optional[np.ndarray], Desc]:
-    """p = C(v) (Definition 2 or 4, or identity) and its descriptor."""
+def compress(comp, v: np.ndarray, k: int = 0, want_p: bool = True,
+             rng: Tuple[int, int, int] = (0, 0, 0)) -> Tuple[Optional[np.ndarray], Desc]:
+    """p = C(v) (Definition 2, 3 or 4, or identity) and its descriptor.  rng = (seed, draw, row)
+    names the random draw of Definition 3."""
     lib = _load()
     v = _f32(v)
     assert v.ndim == 1
     p = np.empty_like(v) if want_p else None
     c = _CDesc()
-    rc = lib.liec_oracle_compress(_comp(comp), _ptr(v), v.shape[0], int(k), _ptr(p), ctypes.byref(c))
+    rc = lib.liec_oracle_compress_rng(_comp(comp), _ptr(v), v.shape[0], int(k), None, 0, int(rng[0]), int(rng[1]),
+                                      int(rng[2]), _ptr(p), ctypes.byref(c), None)
     if rc != 0:
-        raise ValueError(f"liec_oracle_compress failed with code {rc}")
+        raise ValueError(f"liec_oracle_compress_rng failed with code {rc}")
     return p, _desc(c)
+
+
+def randk_priorities(d: int, rng: Tuple[int, int, int]) -> np.ndarray:
+    """Priority (31 bits) that the generator of Definition 3's draw gives to each index 0..d-1."""
+    lib = _load()
+    out = np.empty(d, dtype=np.uint32)
+    lib.liec_oracle_randk_priorities(int(rng[0]), int(rng[1]), int(rng[2]), d,
+                                     out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)))
+    return out
 
 
 def server_average(P: np.ndarray, e: np.ndarray) -> np.ndarray:
@@ -172,8 +200,9 @@ class StepTrace:
 
 
 def step(g: np.ndarray, x: np.ndarray, e: np.ndarray, worker_comp, server_comp, lr: float,
-         worker_k: int = 0, server_k: int = 0, trace: bool = False) -> StepTrace:
-    """One compressed iteration of Algorithm 1; x [N,d] and e [d] are updated in place."""
+         worker_k: int = 0, server_k: int = 0, trace: bool = False, rng: Tuple[int, int] = (0, 0)) -> StepTrace:
+    """One compressed iteration of Algorithm 1; x [N,d] and e [d] are updated in place.
+    rng = (seed, draw) names this iteration's draws of Definition 3."""
     lib = _load()
     g, x, e = _f32(g), _f32(x, True), _f32(e, True)
     N, d = g.shape
@@ -183,11 +212,11 @@ def step(g: np.ndarray, x: np.ndarray, e: np.ndarray, worker_comp, server_comp, 
     v = np.empty(d, dtype=np.float32) if trace else None
     p = np.empty(d, dtype=np.float32) if trace else None
     P = np.empty((N, d), dtype=np.float32) if trace else None
-    rc = lib.liec_oracle_step(N, d, _comp(worker_comp), int(worker_k), _comp(server_comp), int(server_k),
-                              ctypes.c_float(lr), _ptr(g), _ptr(x), _ptr(e), wd, ctypes.byref(sd),
-                              _ptr(v), _ptr(p), _ptr(P))
+    rc = lib.liec_oracle_step_rng(N, d, _comp(worker_comp), int(worker_k), _comp(server_comp), int(server_k),
+                                  ctypes.c_float(lr), _ptr(g), _ptr(x), _ptr(e), None, 0, int(rng[0]), int(rng[1]),
+                                  wd, ctypes.byref(sd), None, None, _ptr(v), _ptr(p), _ptr(P))
     if rc != 0:
-        raise ValueError(f"liec_oracle_step failed with code {rc}")
+        raise ValueError(f"liec_oracle_step_rng failed with code {rc}")
     return StepTrace([_desc(c) for c in wd], _desc(sd), v, p, P)
 
 
@@ -288,6 +317,19 @@ def pack_topk(v: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
     rc = lib.liec_oracle_pack_topk(_ptr(v), v.shape[0], k, idx.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), _ptr(val))
     if rc != 0:
         raise ValueError(f"liec_oracle_pack_topk failed with code {rc}")
+    return idx, val
+
+
+def pack_randk(v: np.ndarray, k: int, rng: Tuple[int, int, int]) -> Tuple[np.ndarray, np.ndarray]:
+    """Wire form of a random-k message: (indices ascending, values), k entries each."""
+    lib = _load()
+    v = _f32(v)
+    idx = np.empty(k, dtype=np.uint32)
+    val = np.empty(k, dtype=np.float32)
+    rc = lib.liec_oracle_pack_randk(_ptr(v), v.shape[0], k, int(rng[0]), int(rng[1]), int(rng[2]),
+                                    idx.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), _ptr(val))
+    if rc != 0:
+        raise ValueError(f"liec_oracle_pack_randk failed with code {rc}")
     return idx, val
 
 

@@ -38,9 +38,10 @@ int main(void)
         if (B == 1) off[1] = d;
         oracle_desc wd[3], sd;
         float ws[9], ss[3];
-        for (int wc = 0; wc < 4; ++wc)
-            for (int sc = 0; sc < 4; ++sc)
-                if (liec_oracle_step_ex(N, d, wc, k, sc, k, 0.1f, g, x, e, off, B, wd, &sd, ws, ss, NULL, NULL, NULL)) return 3;
+        for (int wc = 0; wc < 5; ++wc)
+            for (int sc = 0; sc < 5; ++sc)
+                if (liec_oracle_step_rng(N, d, wc, k, sc, k, 0.1f, g, x, e, off, B, 5, (uint64_t)z, wd, &sd, ws, ss,
+                                         NULL, NULL, NULL)) return 3;
         if (liec_oracle_step_sync(N, d, 0.1f, g, x, e, NULL)) return 4;
         for (int64_t j = 0; j < d; ++j) if (e[j] != 0.0f) return 5;
         if (liec_oracle_compress(ORACLE_TOPK, g, d, k, p, &sd)) return 6;
@@ -56,6 +57,10 @@ int main(void)
         liec_oracle_unpack_sign(bits, d, ss, off, B, p);
         for (int64_t j = 0; j < d; ++j) if ((p[j] < 0.0f) != (g[j] < 0.0f) && p[j] != 0.0f) return 9;
         if (liec_oracle_compress(ORACLE_TOPK, g, d, 0, p, &sd) == 0) return 10;      /* bad k must be refused */
+        if (liec_oracle_pack_randk(g, d, k, 1, 2, 3, idx, val)) return 11;
+        for (int64_t r = 1; r < k; ++r) if (idx[r] <= idx[r - 1] || idx[r] >= (uint32_t)d) return 12;
+        liec_oracle_randk_priorities(1, 2, 3, d, idx);
+        if (liec_oracle_compress_rng(ORACLE_RANDK, g, d, d + 1, NULL, 0, 1, 2, 3, p, &sd, NULL) == 0) return 13;
         free(g); free(x); free(e); free(p); free(bits); free(idx); free(val);
     }
     puts("oracle selftest ok");

@@ -646,7 +646,6 @@ liec_status liec_unpack_sign_message(liec_ctx* c, const uint8_t* bits, const flo
     if (c->wire_scales_len < n) {
         e = hipStreamSynchronize(c->stream);
         (void)hipFree(c->wire_scales);
-    (void)hipFree(c->wire_tiles);
         c->wire_scales = nullptr;
         c->wire_scales_len = 0;
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->wire_scales), (size_t)n * sizeof(float));

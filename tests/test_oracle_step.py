@@ -14,7 +14,8 @@ import pytest
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "liec_step_worked_examples.json")
 
 COMBOS = [("sign", "sign"), ("topk", "topk"), ("topk", "sign"), ("sign", "topk"),
-          ("identity", "sign"), ("topk", "identity"), ("identity", "identity")]
+          ("identity", "sign"), ("topk", "identity"), ("identity", "identity"),
+          ("randk", "randk"), ("randk", "sign"), ("topk", "randk")]
 
 
 def _grads(rng, N, d):
@@ -103,7 +104,7 @@ def test_lemma3_mean_model_minus_virtual_sequence_is_eta_times_error(oracle, wc,
     virt = x0.astype(np.float64)
     for t in range(T):
         g = _grads(rng, N, d)
-        oracle.step(g, x, e, wc, sc, lr, worker_k=40, server_k=60)
+        oracle.step(g, x, e, wc, sc, lr, worker_k=40, server_k=60, rng=(17, t))
         virt = virt - np.float64(np.float32(lr)) * g.astype(np.float64).mean(axis=0)
         lhs = x.astype(np.float64).mean(axis=0) - virt
         rhs = np.float64(np.float32(lr)) * e.astype(np.float64)
@@ -144,6 +145,49 @@ def test_server_identity_keeps_error_zero_and_worker_identity_keeps_models_equal
         oracle.step(_grads(rng, N, d), x, e, "identity", "sign", lr)
         assert all(np.array_equal(x[0], x[i]) for i in range(1, N))
     assert e.any()
+
+
+def test_lemma6_worker_drift_identity_random_k(oracle):
+    # the same identity with Definition 3's operator; the kept set of (seed, draw, worker) is re-derived
+    # from the priorities alone
+    rng = np.random.default_rng(22)
+    N, d, lr, T, k, seed = 4, 900, 0.2, 10, 45, 5
+    x = np.zeros((N, d), dtype=np.float32)
+    e = np.zeros(d, dtype=np.float32)
+    acc = np.zeros((N, d), dtype=np.float64)
+    for t in range(T):
+        g = _grads(rng, N, d)
+        oracle.step(g, x, e, "randk", "randk", lr, worker_k=k, server_k=2 * k, rng=(seed, t))
+        delta = np.empty((N, d))
+        for i in range(N):
+            pr = oracle.randk_priorities(d, (seed, t, i))
+            keep = np.lexsort((np.arange(d), -pr.astype(np.int64)))[:k]
+            delta[i] = g[i].astype(np.float64)
+            delta[i, keep] = 0.0
+        acc += delta - delta.mean(axis=0, keepdims=True)
+    x64 = x.astype(np.float64)
+    lhs = x64.mean(axis=0, keepdims=True) - x64
+    rhs = np.float64(np.float32(lr)) * acc
+    assert np.abs(lhs - rhs).max() <= T * 8 * 2.0 ** -23 * max(1.0, np.abs(x).max())
+
+
+def test_random_k_step_composes_with_worker_rows_and_server_row_N(oracle):
+    rng = np.random.default_rng(4)
+    N, d, lr, k, seed, draw = 3, 500, 0.3, 25, 99, 12
+    g = _grads(rng, N, d)
+    x = rng.standard_normal((N, d)).astype(np.float32)
+    e = (0.01 * rng.standard_normal(d)).astype(np.float32)
+    x2, e2 = x.copy(), e.copy()
+    tr = oracle.step(g, x, e, "randk", "randk", lr, worker_k=k, server_k=3 * k, trace=True, rng=(seed, draw))
+    P = np.stack([oracle.compress("randk", g[i], k, rng=(seed, draw, i))[0] for i in range(N)])
+    v = oracle.server_average(P, e2)
+    p, _ = oracle.compress("randk", v, 3 * k, rng=(seed, draw, N))
+    e2 = oracle.error_update(v, p)
+    for i in range(N):
+        oracle.worker_update(g[i], P[i], p, lr, x2[i])
+    assert np.array_equal(tr.P, P) and np.array_equal(tr.v, v) and np.array_equal(tr.p, p)
+    assert np.array_equal(e, e2) and np.array_equal(x, x2)
+    assert len({tuple(np.flatnonzero(P[i])) for i in range(N)}) == N   # the workers draw different sets
 
 
 def test_step_pieces_compose_to_the_whole_step(oracle):
