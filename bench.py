@@ -20,7 +20,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 DEFAULT_WORKLOAD = "c5_vgg16_mixed"   # the largest configuration; fits one GPU (grads 8.25 GiB)
-ALSO = ["c3_resnet18_sign", "c3_resnet18_blocksign", "c4_resnet50_topk", "c5_vgg16_sign"]
+ALSO = ["c3_resnet18_sign", "c3_resnet18_blocksign", "c4_resnet50_topk", "c4_resnet50_randk", "c5_vgg16_sign"]
 N_GRAD_BUFFERS = 4          # distinct gradient batches rotated through the timed steps
 REPEATS = 5                 # timed regions per workload; the median one is reported
 # HBM bytes one launch of the update kernel moves, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of

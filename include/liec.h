@@ -11,11 +11,14 @@
  *   e   <- v - p                              global error update
  *   x^i <- x^i - lr * (p + (g_i - p^i))       local immediate error compensation
  * C_w / C_s are the scaled-sign operator (Definition 4), its blockwise form
- * (Definition 5), top-k (Definition 2) or the identity.  Conventions the definitions leave open:
+ * (Definition 5), top-k (Definition 2), random-k (Definition 3) or the identity.
+ * Conventions the definitions leave open:
  *   - scaled sign: scale = fp32(sum_j |v_j| / d) with the sum carried in fp64;
  *     sign is binary, v >= 0 (both zeros included) -> +scale, v < 0 -> -scale;
  *   - top-k: magnitudes compare through the integer key (bits & 0x7fffffff);
  *     among equal keys the lower index wins; exactly k entries are kept;
+ *   - random-k: the k-subset of a draw is the k indices of highest priority under
+ *     a counter-based generator keyed by (seed, draw, row) -- see liec_set_random;
  *   - the N messages are added in worker order in fp32, then one fused
  *     multiply-add by 1/N adds e; the update is one fused multiply-add by -lr.
  *
@@ -48,7 +51,8 @@ typedef enum {
     LIEC_COMP_IDENTITY = 0, /* C(v) = v; with it on both sides the step is P-SGD */
     LIEC_COMP_SIGN = 1,     /* Definition 4 */
     LIEC_COMP_TOPK = 2,     /* Definition 2 */
-    LIEC_COMP_BLOCKSIGN = 3 /* Definition 5: Definition 4 on each block of liec_set_blocks */
+    LIEC_COMP_BLOCKSIGN = 3, /* Definition 5: Definition 4 on each block of liec_set_blocks */
+    LIEC_COMP_RANDK = 4     /* Definition 3: k coordinates drawn uniformly, see liec_set_random */
 } liec_comp;
 
 /* Scalars describing the LAST completed step (filled by liec_get_info). */
@@ -61,9 +65,10 @@ typedef struct {
     int64_t steps_done;
     float server_scale;       /* scaled sign on the server: ||v||_1 / d            */
     double server_l1;         /* scaled sign on the server: ||v||_1 (fp64 sum)     */
-    uint32_t server_tau_key;  /* top-k on the server: magnitude key of k-th entry  */
-    int64_t server_cutoff;    /* top-k on the server: largest kept index among
-                                 entries whose key equals server_tau_key           */
+    uint32_t server_tau_key;  /* top-k on the server: magnitude key of k-th entry
+                                 (random-k: priority of the k-th kept index)       */
+    int64_t server_cutoff;    /* top-k / random-k on the server: largest kept index
+                                 among entries whose key equals server_tau_key     */
     int32_t nonfinite;        /* 1 if a NaN/Inf reached an L1 sum or a top-k key   */
 } liec_info;
 
@@ -73,7 +78,7 @@ typedef struct {
  *   out         receives the context (host pointer to a host pointer)
  *   N >= 1      number of simulated workers (rows)
  *   1 <= d < 2^31 - 2^20   model dimension (columns); also N * (d / 1024 + 4097) < 2^31
- *   k           kept entries for LIEC_COMP_TOPK, 1 <= k <= d; ignored otherwise
+ *   k           kept entries for LIEC_COMP_TOPK / LIEC_COMP_RANDK, 1 <= k <= d; ignored otherwise
  *   lr          learning rate eta, finite
  * Allocates O(N * d / 8 + d) bytes of device scratch.  Uses the current HIP device.
  */
@@ -138,8 +143,10 @@ liec_status liec_get_block_scales(liec_ctx *ctx, float *worker_scales, float *se
 /*
  * Bytes of one message C(v) on the wire, as the paper counts communication
  * (one bit per element for the sign operators, "32x"): identity 4d; scaled sign
- * ceil(d/8) + 4 (bits + scale); blockwise ceil(d/8) + 4*nblocks; top-k 8k
- * (32-bit index + fp32 value per kept entry).  -1 for bad arguments.  Host only.
+ * ceil(d/8) + 4 (bits + scale); blockwise ceil(d/8) + 4*nblocks; top-k and
+ * random-k 8k (32-bit index + fp32 value per kept entry; a receiver that shares
+ * the seed could rebuild random-k's indices itself, which is not counted here).
+ * -1 for bad arguments.  Host only.
  */
 int64_t liec_message_bytes(liec_comp comp, int64_t d, int64_t k, int32_t nblocks);
 
@@ -177,7 +184,8 @@ liec_status liec_unpack_sign_message(liec_ctx *ctx, const uint8_t *bits, const f
                                      int32_t blockwise, float *p_out);
 
 /*
- * Wire form of worker `worker`'s top-k message of the last step (Definition 2):
+ * Wire form of worker `worker`'s top-k (Definition 2) or random-k (Definition 3)
+ * message of the last step:
  * its worker_k kept entries as (index, value) pairs in increasing index order,
  * written to the DEVICE arrays idx_out / val_out (worker_k entries each, 8k
  * bytes in all).  `grads` must be the [N, d] DEVICE tensor the last liec_step
@@ -199,6 +207,35 @@ liec_status liec_unpack_topk_message(liec_ctx *ctx, const uint32_t *idx, const f
  * from the next liec_step. */
 liec_status liec_set_lr(liec_ctx *ctx, float lr);
 
+/*
+ * Random-k (Definition 3: keep the coordinates of a set S drawn uniformly from
+ * the k-element subsets of [d]).  The draw of row r (worker index, or N for the
+ * server) in the compressed iteration number `draw` under `seed` is made by a
+ * counter-based generator, so that it can be reproduced anywhere:
+ *   mix(z): z = (z ^ z >> 30) * 0xBF58476D1CE4E5B9; z = (z ^ z >> 27) * 0x94D049BB133111EB; z ^ z >> 31
+ *   G = 0x9E3779B97F4A7C15;  s = mix(mix(mix(seed + G) + draw + G) + r + G)        (64-bit, wrapping)
+ *   h = j ^ low32(s); h ^= h >> 16; h *= 0x85EBCA6B; h ^= h >> 13; h += high32(s);
+ *   h *= 0xC2B2AE35; h ^= h >> 16;  priority(j) = h >> 1                            (32-bit, wrapping)
+ * S = the k indices of highest priority, equal priorities (at most pairs) to the
+ * lower index.  liec_set_random sets the seed and the number of the next draw
+ * (both 0 in a new context); every liec_step uses one draw number and then
+ * advances it by one (liec_step_sync does not).  liec_get_random reads them back,
+ * e.g. for a checkpoint.  The gradients are not read to make a draw, so
+ * non-finite inputs are not reported for this operator.
+ */
+liec_status liec_set_random(liec_ctx *ctx, uint64_t seed, uint64_t draw);
+liec_status liec_get_random(const liec_ctx *ctx, uint64_t *seed, uint64_t *draw);
+
+/*
+ * Testing aid for the threshold search behind top-k (Definition 2) and random-k
+ * (Definition 3): makes every such row start the next liec_step's search in the
+ * given mode -- 0: filter the band predicted by the previous step, 1: no
+ * prediction (first radix digit over the whole row, then filter), 4: the general
+ * one-block-per-row search.  The modes differ in cost only; the kept set is the
+ * same in each.  Synchronises the stream.  LIEC_EINVAL for any other mode.
+ */
+liec_status liec_force_search_mode(liec_ctx *ctx, int32_t mode);
+
 /* Synchronises the stream and copies the scalars of the last step to the host
  * struct `info`.  Returns LIEC_ENONFINITE (with `info` filled) if that step met
  * a NaN or Inf. */
@@ -209,8 +246,8 @@ liec_status liec_get_info(liec_ctx *ctx, liec_info *info);
  * last step into HOST arrays of length N; any pointer may be NULL.
  *   scales  scaled sign: ||g_i||_1 / d
  *   l1      scaled sign: ||g_i||_1 as summed in fp64
- *   tau     top-k: magnitude key of the k-th kept entry of g_i
- *   cutoff  top-k: largest kept index among entries of g_i whose key equals tau
+ *   tau     top-k: magnitude key of the k-th kept entry of g_i (random-k: its priority)
+ *   cutoff  top-k / random-k: largest kept index among entries of g_i whose key equals tau
  * Arrays that do not apply to the worker operator are zero-filled.
  */
 liec_status liec_get_worker_desc(liec_ctx *ctx, float *scales, double *l1, uint32_t *tau,

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     COMP_SIGN,
     COMP_TOPK,
     COMP_BLOCKSIGN,
+    COMP_RANDK,
     LiecContext,
     LiecError,
     LiecInfo,
@@ -21,6 +22,8 @@ from .binding import (  # noqa: F401
     liec_get_info,
     liec_get_worker_desc,
     liec_set_lr,
+    liec_set_random,
+    liec_get_random,
     liec_message_bytes,
     liec_comm_cost,
     liec_set_blocks,

@@ -11,8 +11,9 @@ from typing import Dict, List, Optional, Tuple
 
 import torch
 
-COMP_IDENTITY, COMP_SIGN, COMP_TOPK, COMP_BLOCKSIGN = 0, 1, 2, 3
-_COMP_NAMES = {"identity": COMP_IDENTITY, "sign": COMP_SIGN, "topk": COMP_TOPK, "blocksign": COMP_BLOCKSIGN}
+COMP_IDENTITY, COMP_SIGN, COMP_TOPK, COMP_BLOCKSIGN, COMP_RANDK = 0, 1, 2, 3, 4
+_COMP_NAMES = {"identity": COMP_IDENTITY, "sign": COMP_SIGN, "topk": COMP_TOPK, "blocksign": COMP_BLOCKSIGN,
+               "randk": COMP_RANDK}
 OK, EINVAL, ENOMEM, EDEVICE, ENONFINITE = 0, 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -86,6 +87,12 @@ def lib():
         L.liec_unpack_topk_message.argtypes = [vp, vp, vp, i64, vp]
         L.liec_set_lr.restype = ctypes.c_int
         L.liec_set_lr.argtypes = [vp, f32]
+        L.liec_set_random.restype = ctypes.c_int
+        L.liec_set_random.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint64]
+        L.liec_get_random.restype = ctypes.c_int
+        L.liec_get_random.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
+        L.liec_force_search_mode.restype = ctypes.c_int
+        L.liec_force_search_mode.argtypes = [vp, i32]
         L.liec_get_info.restype = ctypes.c_int
         L.liec_get_info.argtypes = [vp, ctypes.POINTER(LiecInfo)]
         L.liec_get_worker_desc.restype = ctypes.c_int
@@ -177,6 +184,16 @@ def liec_set_lr(ctx: int, lr: float) -> None:
     _check(lib().liec_set_lr(ctx, lr), "liec_set_lr")
 
 
+def liec_set_random(ctx: int, seed: int, draw: int) -> None:
+    _check(lib().liec_set_random(ctx, seed, draw), "liec_set_random")
+
+
+def liec_get_random(ctx: int) -> Tuple[int, int]:
+    seed, draw = ctypes.c_uint64(), ctypes.c_uint64()
+    _check(lib().liec_get_random(ctx, ctypes.byref(seed), ctypes.byref(draw)), "liec_get_random")
+    return int(seed.value), int(draw.value)
+
+
 def liec_get_info(ctx: int) -> Tuple[LiecInfo, int]:
     info = LiecInfo()
     st = lib().liec_get_info(ctx, ctypes.byref(info))
@@ -260,6 +277,15 @@ class LiecContext:
 
     def set_lr(self, lr: float) -> None:
         liec_set_lr(self._h, lr)
+
+    def set_random(self, seed: int, draw: int = 0) -> None:
+        liec_set_random(self._h, seed, draw)
+
+    def get_random(self) -> Tuple[int, int]:
+        return liec_get_random(self._h)
+
+    def force_search_mode(self, mode: int) -> None:
+        _check(lib().liec_force_search_mode(self._h, mode), "liec_force_search_mode")
 
     def info(self) -> LiecInfo:
         return liec_get_info(self._h)[0]

@@ -20,30 +20,32 @@ namespace {
 // Kernel slots for per-kernel timing: worker side, aggregation, server side, update.
 enum Slot : int {
     S_W_L1 = 0, S_W_L1_FINAL,
-    S_W_SEL,                       // 12 slots of the worker-side top-k search
-    S_AGGREGATE = S_W_SEL + 12,
+    S_W_SEL,                       // 13 slots of the worker-side top-k / random-k search
+    S_AGGREGATE = S_W_SEL + 13,
     S_S_L1, S_S_L1_FINAL,
-    S_S_SEL,                       // 12 slots of the server-side top-k search
-    S_UPDATE = S_S_SEL + 12,
+    S_S_SEL,                       // 13 slots of the server-side top-k / random-k search
+    S_UPDATE = S_S_SEL + 13,
     S_SYNC,
     S_COUNT
 };
 
-const char* const kWorkerSel[12] = {"worker_filter_warm", "worker_check_warm", "worker_hist0", "worker_pick_band",
+const char* const kWorkerSel[13] = {"worker_filter_warm", "worker_check_warm", "worker_hist0", "worker_pick_band",
                                     "worker_filter_cold", "worker_check_cold", "worker_list_hist0", "worker_list_hist1",
-                                    "worker_list_hist2", "worker_list_ties", "worker_list_finish", "worker_slow_select"};
-const char* const kServerSel[12] = {"server_filter_warm", "server_check_warm", "server_hist0", "server_pick_band",
+                                    "worker_list_hist2", "worker_list_ties", "worker_list_finish", "worker_slow_select",
+                                    "worker_randk_mark"};
+const char* const kServerSel[13] = {"server_filter_warm", "server_check_warm", "server_hist0", "server_pick_band",
                                     "server_filter_cold", "server_check_cold", "server_list_hist0", "server_list_hist1",
-                                    "server_list_hist2", "server_list_ties", "server_list_finish", "server_slow_select"};
+                                    "server_list_hist2", "server_list_ties", "server_list_finish", "server_slow_select",
+                                    "server_randk_mark"};
 
 const char* slot_name(int s) {
     if (s == S_W_L1) return "worker_l1_bits";
     if (s == S_W_L1_FINAL) return "worker_l1_final";
-    if (s >= S_W_SEL && s < S_W_SEL + 12) return kWorkerSel[s - S_W_SEL];
+    if (s >= S_W_SEL && s < S_W_SEL + 13) return kWorkerSel[s - S_W_SEL];
     if (s == S_AGGREGATE) return "server_aggregate";
     if (s == S_S_L1) return "server_l1";
     if (s == S_S_L1_FINAL) return "server_l1_final";
-    if (s >= S_S_SEL && s < S_S_SEL + 12) return kServerSel[s - S_S_SEL];
+    if (s >= S_S_SEL && s < S_S_SEL + 13) return kServerSel[s - S_S_SEL];
     if (s == S_SYNC) return "sync";
     return "update";
 }
@@ -81,7 +83,9 @@ struct liec_ctx {
     float* vbuf = nullptr;                     // [d]  compensated average v
     double* w_partial = nullptr;               // [N * row_blocks]
     double* s_partial = nullptr;               // [agg_blocks]
-    uint16_t* bits = nullptr;                  // [N * nwt * 64] sign bits (sign operators)
+    uint16_t* bits = nullptr;                  // [(N or N + 1) * nwt * 64] sign bits (sign operators) / kept bits (random-k; row N: server)
+    uint64_t rk_seed = 0, rk_draw = 0;         // random-k: seed and index of the next draw
+    uint32_t rk_wlo = 0, rk_whi = 0, rk_slo = 0, rk_shi = 0;   // random-k: threshold bands of the worker / server draws
     uint64_t* gbits = nullptr;                 // [N * nwt * 4] group bitmap of the candidates (top-k workers)
     uint2* list = nullptr;                     // [(N + 1) * cap] candidates (key, index)
     uint32_t* sure_partial = nullptr;          // [(N + 1) * part_stride]
@@ -160,7 +164,23 @@ void free_scratch(liec_ctx* c) {
 }
 
 bool valid_comp(int c) {
-    return c == LIEC_COMP_IDENTITY || c == LIEC_COMP_SIGN || c == LIEC_COMP_TOPK || c == LIEC_COMP_BLOCKSIGN;
+    return c == LIEC_COMP_IDENTITY || c == LIEC_COMP_SIGN || c == LIEC_COMP_TOPK || c == LIEC_COMP_BLOCKSIGN ||
+           c == LIEC_COMP_RANDK;
+}
+
+bool selects_k(int c) { return c == LIEC_COMP_TOPK || c == LIEC_COMP_RANDK; }
+
+// Random-k: band of keys [lo, hi) that holds the k-th largest of d uniform 31-bit priorities, 8 standard
+// deviations of that order statistic on either side (the search stays exact if the key falls outside).
+void randk_band(int64_t d, int64_t k, uint32_t* lo, uint32_t* hi) {
+    const double range = 2147483648.0, dd = (double)d, kk = (double)k;
+    const double centre = range * (1.0 - kk / dd);
+    const double sigma = range * std::sqrt(kk * (dd - kk) / dd) / dd;
+    const double margin = 8.0 * sigma + 4.0 * range / dd + 16.0;
+    const double l = std::floor(centre - margin), h = std::ceil(centre + margin);
+    *lo = l < 0.0 ? 0u : (uint32_t)l;
+    *hi = h > range ? 0x80000000u : (uint32_t)h;
+    if (*hi <= *lo) *hi = *lo + 1;
 }
 
 struct Launcher {
@@ -188,29 +208,31 @@ struct Launcher {
 // Top-k threshold search (Definition 2) of `rows` rows of `src`; per-row state lives at row0 + r.
 // The host enqueues the same twelve kernels every step; each one acts only on the rows whose mode
 // asks for it, so the warm path costs one pass over the data and the others return at once.
-template <bool VEC>
-void launch_topk_select(Launcher& L, const float* src, size_t row_stride, uint32_t rows, uint32_t row0, uint32_t k,
-                        uint64_t* bits, uint32_t blocks, uint32_t cold_blocks, int slot0) {
+// RK: the same search over the priorities of a random-k draw (Definition 3), which read nothing from
+// `src`, followed by the kernel that completes the kept bitmap.
+template <bool VEC, bool RK>
+void launch_select(Launcher& L, const float* src, size_t row_stride, uint32_t rows, uint32_t row0, uint32_t k,
+                   uint64_t* gbits, uint32_t blocks, uint32_t cold_blocks, int slot0, RkDraw rk) {
     liec_ctx* c = L.c;
     const uint32_t d = (uint32_t)c->d;
     hipStream_t st = c->stream;
     const dim3 grid(blocks, rows), cold_grid(cold_blocks, rows), list_grid(c->list_blocks, rows);
     L.begin(slot0 + 0);
-    k_filter<VEC><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kWarm, bits, c->list, c->cap,
-                                            c->sure_partial);
+    k_filter<VEC, RK><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kWarm, gbits, c->bits, c->list,
+                                                c->cap, c->sure_partial, rk);
     L.end();
     L.begin(slot0 + 1);
     k_check<<<rows, kBlock, 0, st>>>(row0, c->desc, kWarm, c->sure_partial, blocks, c->cap, k);
     L.end();
     L.begin(slot0 + 2);
-    k_hist0<VEC><<<cold_grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, c->ghist);
+    k_hist0<VEC, RK><<<cold_grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, c->ghist, rk);
     L.end();
     L.begin(slot0 + 3);
     k_pick_band<<<rows, kBlock, 0, st>>>(row0, c->desc, c->ghist, c->cap, k);
     L.end();
     L.begin(slot0 + 4);
-    k_filter<VEC><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kColdBand, bits, c->list, c->cap,
-                                            c->sure_partial);
+    k_filter<VEC, RK><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kColdBand, gbits, c->bits,
+                                                c->list, c->cap, c->sure_partial, rk);
     L.end();
     L.begin(slot0 + 5);
     k_check<<<rows, kBlock, 0, st>>>(row0, c->desc, kColdBand, c->sure_partial, blocks, c->cap, k);
@@ -228,11 +250,16 @@ void launch_topk_select(Launcher& L, const float* src, size_t row_stride, uint32
     k_list_ties<<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, c->lhist, c->tiebuf);
     L.end();
     L.begin(slot0 + 10);
-    k_list_finish<<<rows, kBlock, 0, st>>>(row0, c->desc, c->lhist, c->tiebuf);
+    k_list_finish<<<rows, kBlock, 0, st>>>(row0, c->desc, c->lhist, c->tiebuf, c->cap, rk.fix_lo, rk.fix_hi);
     L.end();
     L.begin(slot0 + 11);
-    k_slow_select<VEC><<<rows, 1024, 0, st>>>(src, row_stride, d, row0, c->desc, k);
+    k_slow_select<VEC, RK><<<rows, 1024, 0, st>>>(src, row_stride, d, row0, c->desc, k, rk);
     L.end();
+    if (RK) {
+        L.begin(slot0 + 12);
+        k_rk_mark<<<dim3(cold_blocks, rows), kBlock, 0, st>>>(d, c->nwt, row0, c->desc, c->list, c->cap, c->bits, rk);
+        L.end();
+    }
 }
 
 // Blockwise scaled sign (Definition 5): per-block L1 norms of `rows` rows of `src` -> scales; for the
@@ -276,7 +303,8 @@ void launch_update(Launcher& L, const float* grads, float* x, float* e) {
     const uint64_t blocks = (uint64_t)npanels * panel * (uint64_t)c->N;
     L.begin(S_UPDATE);
     k_update<WC, SC, VEC><<<(uint32_t)blocks, kBlock, 0, c->stream>>>(grads, x, c->vbuf, e, c->N, panel, c->ncol_tiles,
-                                                                       (uint32_t)c->d, -c->lr, c->desc, block_table(c));
+                                                                       (uint32_t)c->d, -c->lr, c->desc, block_table(c),
+                                                                       c->bits);
     L.end();
 }
 
@@ -286,6 +314,7 @@ void launch_update_sc(Launcher& L, int sc, const float* grads, float* x, float* 
     case kIdentity: launch_update<WC, kIdentity, VEC>(L, grads, x, e); break;
     case kSign: launch_update<WC, kSign, VEC>(L, grads, x, e); break;
     case kBlockSign: launch_update<WC, kBlockSign, VEC>(L, grads, x, e); break;
+    case kRandk: launch_update<WC, kRandk, VEC>(L, grads, x, e); break;
     default: launch_update<WC, kTopk, VEC>(L, grads, x, e); break;
     }
 }
@@ -308,8 +337,12 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
     } else if (c->worker_comp == kBlockSign) {
         launch_block_l1<VEC>(L, grads, stride, (uint32_t)c->N, 0u, c->bits, S_W_L1);
     } else if (c->worker_comp == kTopk) {
-        launch_topk_select<VEC>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, c->gbits,
-                                c->filter_row_blocks, c->cold_row_blocks, S_W_SEL);
+        launch_select<VEC, false>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, c->gbits,
+                                  c->filter_row_blocks, c->cold_row_blocks, S_W_SEL, RkDraw{0, 0, 0, 0});
+    } else if (c->worker_comp == kRandk) {
+        launch_select<VEC, true>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, nullptr,
+                                 c->filter_row_blocks, c->cold_row_blocks, S_W_SEL,
+                                 RkDraw{c->rk_seed, c->rk_draw, c->rk_wlo, c->rk_whi});
     }
 
     // ---- server: v = e + mean_i p^i, then the descriptor of C_s(v) ---------------------------------
@@ -318,6 +351,7 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
     case kIdentity: launch_aggregate<kIdentity, VEC>(L, grads, e, srv_l1); break;
     case kSign: launch_aggregate<kSign, VEC>(L, grads, e, srv_l1); break;
     case kBlockSign: launch_aggregate<kBlockSign, VEC>(L, grads, e, srv_l1); break;
+    case kRandk: launch_aggregate<kRandk, VEC>(L, grads, e, srv_l1); break;
     default: launch_aggregate<kTopk, VEC>(L, grads, e, srv_l1); break;
     }
     if (c->server_comp == kSign) {
@@ -328,8 +362,12 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
         launch_block_l1<VEC>(L, c->vbuf, 0, 1u, (uint32_t)c->N, nullptr, S_S_L1);
     } else if (c->server_comp == kTopk) {
         // v is always 16-byte aligned scratch, but d % 4 decides whether 128-bit loads stay in bounds
-        launch_topk_select<VEC>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, nullptr,
-                                c->filter_srv_blocks, c->cold_srv_blocks, S_S_SEL);
+        launch_select<VEC, false>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, nullptr,
+                                  c->filter_srv_blocks, c->cold_srv_blocks, S_S_SEL, RkDraw{0, 0, 0, 0});
+    } else if (c->server_comp == kRandk) {
+        launch_select<VEC, true>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, nullptr,
+                                 c->filter_srv_blocks, c->cold_srv_blocks, S_S_SEL,
+                                 RkDraw{c->rk_seed, c->rk_draw, c->rk_slo, c->rk_shi});
     }
 
     // ---- p = C_s(v), e <- v - p, x^i <- x^i - lr (p + (g_i - p^i)) ---------------------------------
@@ -337,6 +375,7 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
     case kIdentity: launch_update_sc<kIdentity, VEC>(L, c->server_comp, grads, x, e); break;
     case kSign: launch_update_sc<kSign, VEC>(L, c->server_comp, grads, x, e); break;
     case kBlockSign: launch_update_sc<kBlockSign, VEC>(L, c->server_comp, grads, x, e); break;
+    case kRandk: launch_update_sc<kRandk, VEC>(L, c->server_comp, grads, x, e); break;
     default: launch_update_sc<kTopk, VEC>(L, c->server_comp, grads, x, e); break;
     }
 }
@@ -378,8 +417,8 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     if (!valid_comp((int)worker_comp) || !valid_comp((int)server_comp) || !finite_f(lr)) return LIEC_EINVAL;
     // the update kernel launches one block per (1024-column tile, row): keep that under 2^31
     if (((d + kColTile - 1) / kColTile + kUpdatePanel) * (int64_t)N >= ((int64_t)1 << 31)) return LIEC_EINVAL;
-    if (worker_comp == LIEC_COMP_TOPK && (worker_k < 1 || worker_k > d)) return LIEC_EINVAL;
-    if (server_comp == LIEC_COMP_TOPK && (server_k < 1 || server_k > d)) return LIEC_EINVAL;
+    if (selects_k((int)worker_comp) && (worker_k < 1 || worker_k > d)) return LIEC_EINVAL;
+    if (selects_k((int)server_comp) && (server_k < 1 || server_k > d)) return LIEC_EINVAL;
 
     liec_ctx* c = new (std::nothrow) liec_ctx();
     if (!c) return LIEC_ENOMEM;
@@ -387,8 +426,10 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     c->d = d;
     c->worker_comp = (int)worker_comp;
     c->server_comp = (int)server_comp;
-    c->worker_k = worker_comp == LIEC_COMP_TOPK ? worker_k : 0;
-    c->server_k = server_comp == LIEC_COMP_TOPK ? server_k : 0;
+    c->worker_k = selects_k((int)worker_comp) ? worker_k : 0;
+    c->server_k = selects_k((int)server_comp) ? server_k : 0;
+    if (worker_comp == LIEC_COMP_RANDK) randk_band(d, worker_k, &c->rk_wlo, &c->rk_whi);
+    if (server_comp == LIEC_COMP_RANDK) randk_band(d, server_k, &c->rk_slo, &c->rk_shi);
     c->lr = lr;
     c->stream = (hipStream_t)hip_stream;
     if (hipGetDevice(&c->device) != hipSuccess) {
@@ -396,7 +437,7 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
         return LIEC_EDEVICE;
     }
 
-    const bool any_topk = worker_comp == LIEC_COMP_TOPK || server_comp == LIEC_COMP_TOPK;
+    const bool any_topk = selects_k((int)worker_comp) || selects_k((int)server_comp);   // any threshold search
     const uint32_t un = (uint32_t)N;
     c->nwt = (uint32_t)((d + kWaveTile - 1) / kWaveTile);
     c->ncol_tiles = (uint32_t)((d + kColTile - 1) / kColTile);
@@ -423,7 +464,10 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     if (e == hipSuccess) e = dev_alloc(c, &c->vbuf, (size_t)c->nwt * kWaveTile);
     if (e == hipSuccess) e = dev_alloc(c, &c->w_partial, (size_t)N * c->row_blocks);
     if (e == hipSuccess) e = dev_alloc(c, &c->s_partial, (size_t)c->agg_blocks);
-    if (e == hipSuccess && (worker_comp == LIEC_COMP_SIGN || worker_comp == LIEC_COMP_BLOCKSIGN))
+    if (e == hipSuccess && server_comp == LIEC_COMP_RANDK)
+        e = dev_alloc(c, &c->bits, rows * c->nwt * 64);
+    else if (e == hipSuccess && (worker_comp == LIEC_COMP_SIGN || worker_comp == LIEC_COMP_BLOCKSIGN ||
+                                 worker_comp == LIEC_COMP_RANDK))
         e = dev_alloc(c, &c->bits, (size_t)N * c->nwt * 64);
     if (e == hipSuccess && worker_comp == LIEC_COMP_TOPK) e = dev_alloc(c, &c->gbits, (size_t)N * c->nwt * 4);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->list, rows * c->cap);
@@ -435,6 +479,13 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
         std::vector<RowDesc> init(rows);
         std::memset(init.data(), 0, rows * sizeof(RowDesc));
         for (auto& r : init) r.mode = kCold;       // no prediction before the first step
+        for (size_t r = 0; r < rows; ++r) {        // random-k rows know their band from the start
+            const bool rk = r < (size_t)N ? worker_comp == LIEC_COMP_RANDK : server_comp == LIEC_COMP_RANDK;
+            if (!rk) continue;
+            init[r].mode = kWarm;
+            init[r].lo = r < (size_t)N ? c->rk_wlo : c->rk_slo;
+            init[r].hi = r < (size_t)N ? c->rk_whi : c->rk_shi;
+        }
         e = hipMemcpy(c->desc, init.data(), rows * sizeof(RowDesc), hipMemcpyHostToDevice);
     }
     if (e == hipSuccess && any_topk) e = hipMemsetAsync(c->ghist, 0, rows * kHistBins * sizeof(uint32_t), c->stream);
@@ -478,6 +529,42 @@ liec_status liec_step(liec_ctx* c, const float* grads, float* x, float* server_e
         return LIEC_EDEVICE;
     }
     ++c->steps_done;
+    ++c->rk_draw;
+    return LIEC_OK;
+}
+
+liec_status liec_set_random(liec_ctx* c, uint64_t seed, uint64_t draw) {
+    if (!c) return LIEC_EINVAL;
+    c->rk_seed = seed;
+    c->rk_draw = draw;
+    return LIEC_OK;
+}
+
+liec_status liec_force_search_mode(liec_ctx* c, int32_t mode) {
+    if (!c || (mode != (int32_t)kWarm && mode != (int32_t)kCold && mode != (int32_t)kSlow)) return LIEC_EINVAL;
+    if (c->broken) return LIEC_EDEVICE;
+    std::vector<RowDesc> h((size_t)c->N + 1);
+    if (hipStreamSynchronize(c->stream) != hipSuccess ||
+        hipMemcpy(h.data(), c->desc, h.size() * sizeof(RowDesc), hipMemcpyDeviceToHost) != hipSuccess) {
+        c->broken = true;
+        return LIEC_EDEVICE;
+    }
+    for (size_t r = 0; r < h.size(); ++r) {
+        if (!selects_k(r < (size_t)c->N ? c->worker_comp : c->server_comp)) continue;
+        h[r].mode = (uint32_t)mode;
+        h[r].n_cand = 0;
+    }
+    if (hipMemcpy(c->desc, h.data(), h.size() * sizeof(RowDesc), hipMemcpyHostToDevice) != hipSuccess) {
+        c->broken = true;
+        return LIEC_EDEVICE;
+    }
+    return LIEC_OK;
+}
+
+liec_status liec_get_random(const liec_ctx* c, uint64_t* seed, uint64_t* draw) {
+    if (!c || !seed || !draw) return LIEC_EINVAL;
+    *seed = c->rk_seed;
+    *draw = c->rk_draw;
     return LIEC_OK;
 }
 
@@ -601,6 +688,7 @@ int64_t liec_message_bytes(liec_comp comp, int64_t d, int64_t k, int32_t nblocks
     case LIEC_COMP_SIGN: return (d + 7) / 8 + 4;
     case LIEC_COMP_BLOCKSIGN: return nblocks < 1 ? -1 : (d + 7) / 8 + 4 * (int64_t)nblocks;
     case LIEC_COMP_TOPK: return (k < 1 || k > d) ? -1 : 8 * k;
+    case LIEC_COMP_RANDK: return (k < 1 || k > d) ? -1 : 8 * k;
     default: return -1;
     }
 }
@@ -671,7 +759,7 @@ liec_status liec_unpack_sign_message(liec_ctx* c, const uint8_t* bits, const flo
 liec_status liec_pack_topk_message(liec_ctx* c, const float* grads, int32_t worker, uint32_t* idx_out, float* val_out) {
     if (!c || !grads || !idx_out || !val_out || worker < 0 || worker >= c->N) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
-    if (c->worker_comp != kTopk || c->steps_done == 0 || ((uintptr_t)grads & 3u)) return LIEC_EINVAL;
+    if (!selects_k(c->worker_comp) || c->steps_done == 0 || ((uintptr_t)grads & 3u)) return LIEC_EINVAL;
     if (!c->wire_tiles) {
         if (hipStreamSynchronize(c->stream) != hipSuccess ||
             hipMalloc(reinterpret_cast<void**>(&c->wire_tiles), ((size_t)c->nwt + 1) * sizeof(uint32_t)) != hipSuccess) {
@@ -684,12 +772,14 @@ liec_status liec_pack_topk_message(liec_ctx* c, const float* grads, int32_t work
     const float* row = grads + (size_t)worker * (size_t)c->d;
     const bool vec = (c->d % 4 == 0) && (((uintptr_t)grads & 15u) == 0);
     const RowDesc* rd = c->desc + worker;
+    // random-k: the kept set of the last draw is the worker's row of the kept bitmap
+    const uint16_t* kept = c->worker_comp == kRandk ? c->bits + (size_t)worker * c->nwt * 64 : nullptr;
     const uint32_t blocks = c->agg_blocks;
-    if (vec) k_topk_count<true><<<blocks, kBlock, 0, c->stream>>>(row, d, c->nwt, rd, c->wire_tiles);
-    else k_topk_count<false><<<blocks, kBlock, 0, c->stream>>>(row, d, c->nwt, rd, c->wire_tiles);
+    if (vec) k_topk_count<true><<<blocks, kBlock, 0, c->stream>>>(row, d, c->nwt, rd, kept, c->wire_tiles);
+    else k_topk_count<false><<<blocks, kBlock, 0, c->stream>>>(row, d, c->nwt, rd, kept, c->wire_tiles);
     k_scan_u32<<<1, 1024, 0, c->stream>>>(c->wire_tiles, c->nwt, c->wire_tiles + c->nwt);
-    if (vec) k_topk_emit<true><<<blocks, kBlock, 0, c->stream>>>(row, d, c->nwt, rd, c->wire_tiles, k, idx_out, val_out);
-    else k_topk_emit<false><<<blocks, kBlock, 0, c->stream>>>(row, d, c->nwt, rd, c->wire_tiles, k, idx_out, val_out);
+    if (vec) k_topk_emit<true><<<blocks, kBlock, 0, c->stream>>>(row, d, c->nwt, rd, kept, c->wire_tiles, k, idx_out, val_out);
+    else k_topk_emit<false><<<blocks, kBlock, 0, c->stream>>>(row, d, c->nwt, rd, kept, c->wire_tiles, k, idx_out, val_out);
     if (hipGetLastError() != hipSuccess) {
         c->broken = true;
         return LIEC_EDEVICE;
@@ -739,7 +829,7 @@ liec_status liec_get_info(liec_ctx* c, liec_info* info) {
     if (c->server_comp == kSign) {
         info->server_scale = s.scale;
         info->server_l1 = s.l1;
-    } else if (c->server_comp == kTopk) {
+    } else if (selects_k(c->server_comp)) {
         info->server_tau_key = s.tau;
         info->server_cutoff = (int64_t)s.cutoff;
     }
@@ -773,7 +863,7 @@ liec_status liec_get_worker_desc(liec_ctx* c, float* scales, double* l1, uint32_
     }
     for (int32_t i = 0; i < c->N; ++i) {
         const RowDesc& r = h[(size_t)i];
-        const bool sg = c->worker_comp == kSign, tk = c->worker_comp == kTopk;
+        const bool sg = c->worker_comp == kSign, tk = selects_k(c->worker_comp);
         if (scales) scales[i] = sg ? r.scale : 0.f;
         if (l1) l1[i] = sg ? r.l1 : 0.0;
         if (tau) tau[i] = tk ? r.tau : 0u;

@@ -23,7 +23,7 @@ constexpr int kTieCap = 4096;           // ties at the threshold the fast path r
 constexpr uint32_t kBandMargin = 1u << 18;   // least half width, in key units, of the predicted band (about 2 % in value)
 constexpr uint32_t kUpdatePanel = 4096; // column tiles per panel of the update kernel
 
-enum Comp : int { kIdentity = 0, kSign = 1, kTopk = 2, kBlockSign = 3 };
+enum Comp : int { kIdentity = 0, kSign = 1, kTopk = 2, kBlockSign = 3, kRandk = 4 };
 
 // Progress of a row's top-k threshold search within one step.
 enum SelMode : uint32_t {
@@ -48,6 +48,7 @@ struct RowDesc {
     uint32_t mode;         // SelMode
     uint32_t n_cand;       // candidates appended so far (may exceed the capacity: overflow)
     uint32_t n_ties;       // ties collected
+    uint32_t n_list;       // candidates that were listed when the search finished (random-k marks the kept ones)
     uint32_t dense;        // the row's candidate bitmap is not valid: test every column
     uint32_t sel_prefix[3];  // list select: key prefix before digit p
     uint32_t sel_rank[3];    // list select: rank inside the prefix before digit p
@@ -61,6 +62,41 @@ __host__ __device__ constexpr int digit_shift(int pass) { return pass == 0 ? 19 
 __host__ __device__ constexpr int digit_bits(int pass) { return pass == 0 ? 12 : (pass == 1 ? 10 : 9); }
 
 __device__ __forceinline__ uint32_t key_of(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+
+// ---------------------------------------------------------------------------------------------
+// Random-k (Definition 3): the k-subset is drawn by giving index j the priority
+// rk_priority(stream, j) and keeping the k highest (ties, at most pairs, to the lower index), so the
+// draw is a top-k search over keys that do not depend on the data.  `stream` is one 64-bit word per
+// (seed, draw, row): three rounds of a multiply-xorshift finalizer over seed, draw counter and row
+// (worker index, or N for the server).  The per-index part is a keyed permutation of 32-bit words
+// (every step is a bijection) with its lowest bit dropped: a 31-bit key like a magnitude key.
+// ---------------------------------------------------------------------------------------------
+struct RkDraw {
+    uint64_t seed, draw;
+    uint32_t fix_lo, fix_hi;   // band that holds rank k of uniform priorities (set by the host); fix_hi == 0: not random-k
+};
+
+__host__ __device__ __forceinline__ uint64_t rk_mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+__host__ __device__ __forceinline__ uint64_t rk_stream(uint64_t seed, uint64_t draw, uint32_t row) {
+    const uint64_t gamma = 0x9E3779B97F4A7C15ull;
+    uint64_t z = rk_mix64(seed + gamma);
+    z = rk_mix64(z + draw + gamma);
+    return rk_mix64(z + (uint64_t)row + gamma);
+}
+__host__ __device__ __forceinline__ uint32_t rk_priority(uint32_t k0, uint32_t k1, uint32_t j) {
+    uint32_t h = j ^ k0;
+    h ^= h >> 16;
+    h *= 0x85EBCA6Bu;
+    h ^= h >> 13;
+    h += k1;
+    h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h >> 1;
+}
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -370,20 +406,20 @@ __global__ __launch_bounds__(kBlock) void k_l1_items_final(const double* __restr
 // running maximum key, returns the ballot of "any of my 4 columns has key >= lo" and, per component,
 // the ballots of the candidates lo <= key < hi.  FULL: every column of the chunk is below d.
 template <bool FULL>
-__device__ __forceinline__ uint64_t filter_chunk(const float4 a, uint32_t j, uint32_t d, uint32_t lo, uint32_t hi,
-                                                 uint32_t (&keys)[4], uint64_t (&bc)[4], uint64_t& any_cand,
-                                                 uint32_t& n_hi, uint32_t& kmax) {
-    const float av[4] = {a.x, a.y, a.z, a.w};
+__device__ __forceinline__ uint64_t filter_chunk(const uint32_t (&keys)[4], uint32_t j, uint32_t d, uint32_t lo, uint32_t hi,
+                                                 uint64_t (&bc)[4], uint64_t& any_cand,
+                                                 uint32_t& n_hi, uint32_t& kmax, uint32_t& hi4) {
     uint64_t any_lo = 0;
     any_cand = 0;
+    hi4 = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const uint32_t key = key_of(av[q]);
+        const uint32_t key = keys[q];
         const bool valid = FULL || j + q < d;
         const bool ge_lo = valid && key >= lo, ge_hi = valid && key >= hi;
-        keys[q] = key;
         kmax = max(kmax, valid ? key : 0u);
         n_hi += ge_hi ? 1u : 0u;
+        hi4 |= (ge_hi ? 1u : 0u) << q;
         const uint64_t bl = __ballot(ge_lo), bh = __ballot(ge_hi);
         any_lo |= bl;
         bc[q] = bl & ~bh;
@@ -392,12 +428,15 @@ __device__ __forceinline__ uint64_t filter_chunk(const float4 a, uint32_t j, uin
     return any_lo;
 }
 
-template <bool VEC>
+// RK: the keys are the priorities of a random-k draw (nothing is read from src), and instead of the
+// group bitmap the kernel writes, per column, whether its key is at or above the band (lane-major
+// half-words like the sign bits, at row `row` of kbits); k_rk_mark later adds the kept candidates.
+template <bool VEC, bool RK>
 __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src, size_t row_stride, uint32_t d,
                                                     uint32_t nwt, uint32_t row0, RowDesc* __restrict__ desc,
                                                     uint32_t expect_mode, uint64_t* __restrict__ gbits,
-                                                    uint2* __restrict__ list, uint32_t cap,
-                                                    uint32_t* __restrict__ sure_partial) {
+                                                    uint16_t* __restrict__ kbits, uint2* __restrict__ list, uint32_t cap,
+                                                    uint32_t* __restrict__ sure_partial, RkDraw rk) {
     __shared__ uint2 stage[4][kStage];
     __shared__ uint32_t wsure[4];
     const uint32_t row = row0 + blockIdx.y;
@@ -406,23 +445,43 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
     const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
     uint2* __restrict__ out = list + (size_t)row * cap;
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    uint32_t k0 = 0, k1 = 0;
+    if (RK) {
+        const uint64_t stream = rk_stream(rk.seed, rk.draw, row);
+        k0 = (uint32_t)stream;
+        k1 = (uint32_t)(stream >> 32);
+    }
     uint2* st = stage[wave];
     uint32_t cnt = 0;                                           // staged candidates (wave-uniform)
     uint32_t n_hi = 0, kmax = 0;                                // per lane: keys >= hi seen, largest key seen
     for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
         float4 a[4];
+        if (!RK) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
+            for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
+        }
         const bool full = (t + 1) * (uint32_t)kWaveTile <= d;  // wave-uniform
         uint64_t word = 0;                                      // lane u (< 4) ends up holding group word u
+        uint32_t sure16 = 0;                                    // RK: bit 4u + q: my column q of chunk u has key >= hi
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
             uint32_t keys[4];
+            if (RK) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) keys[q] = rk_priority(k0, k1, j + q);
+            } else {
+                keys[0] = key_of(a[u].x);
+                keys[1] = key_of(a[u].y);
+                keys[2] = key_of(a[u].z);
+                keys[3] = key_of(a[u].w);
+            }
             uint64_t bc[4], any_cand;
-            const uint64_t any_lo = full ? filter_chunk<true>(a[u], j, d, lo, hi, keys, bc, any_cand, n_hi, kmax)
-                                         : filter_chunk<false>(a[u], j, d, lo, hi, keys, bc, any_cand, n_hi, kmax);
+            uint32_t hi4;
+            const uint64_t any_lo = full ? filter_chunk<true>(keys, j, d, lo, hi, bc, any_cand, n_hi, kmax, hi4)
+                                         : filter_chunk<false>(keys, j, d, lo, hi, bc, any_cand, n_hi, kmax, hi4);
             word = lane == (uint32_t)u ? any_lo : word;
+            sure16 |= hi4 << (4 * u);
             if (any_cand) {                                     // wave-uniform
                 const uint32_t m = __popcll(bc[0]) + __popcll(bc[1]) + __popcll(bc[2]) + __popcll(bc[3]);
                 if (cnt + m > kStage) {                         // flush the staged candidates
@@ -444,7 +503,11 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
                 cnt += m;
             }
         }
-        if (gbits && lane < 4) gbits[((size_t)blockIdx.y * nwt + t) * 4 + lane] = word;
+        if (RK) {
+            kbits[((size_t)row * nwt + t) * 64 + lane] = (uint16_t)sure16;
+        } else {
+            if (gbits && lane < 4) gbits[((size_t)blockIdx.y * nwt + t) * 4 + lane] = word;
+        }
     }
     if (cnt) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -454,8 +517,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
         for (uint32_t s = lane; s < cnt; s += 64)
             if (base + s < cap) out[base + s] = st[s];
     }
-    // keys at or above 0x7f800000 are Inf / NaN
-    if (__ballot(kmax >= 0x7f800000u) && lane == 0) atomicOr(&desc[row].nonfinite_acc, 1u);
+    // keys at or above 0x7f800000 are Inf / NaN (magnitude keys only: priorities use the whole range)
+    if (!RK && __ballot(kmax >= 0x7f800000u) && lane == 0) atomicOr(&desc[row].nonfinite_acc, 1u);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) n_hi += __shfl_down(n_hi, o, 64);
     if (lane == 0) wsure[wave] = n_hi;
@@ -491,10 +554,10 @@ __global__ __launch_bounds__(kBlock) void k_check(uint32_t row0, RowDesc* __rest
 }
 
 // First radix digit (12 bits) of every key of the rows in kCold mode.  grid = (blocks, rows).
-template <bool VEC>
+template <bool VEC, bool RK>
 __global__ __launch_bounds__(kBlock) void k_hist0(const float* __restrict__ src, size_t row_stride, uint32_t d,
                                                    uint32_t nwt, uint32_t row0, const RowDesc* __restrict__ desc,
-                                                   uint32_t* __restrict__ hist) {
+                                                   uint32_t* __restrict__ hist, RkDraw rk) {
     __shared__ uint32_t h[kHistBins];
     const uint32_t row = row0 + blockIdx.y;
     if (desc[row].mode != kCold) return;
@@ -502,17 +565,34 @@ __global__ __launch_bounds__(kBlock) void k_hist0(const float* __restrict__ src,
     for (int b = threadIdx.x; b < kHistBins; b += kBlock) h[b] = 0;
     __syncthreads();
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    uint32_t k0 = 0, k1 = 0;
+    if (RK) {
+        const uint64_t stream = rk_stream(rk.seed, rk.draw, row);
+        k0 = (uint32_t)stream;
+        k1 = (uint32_t)(stream >> 32);
+    }
     for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
         float4 a[4];
+        if (!RK) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
+            for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
+        }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
-            if (j < d) atomicAdd(&h[key_of(a[u].x) >> 19], 1u);
-            if (j + 1 < d) atomicAdd(&h[key_of(a[u].y) >> 19], 1u);
-            if (j + 2 < d) atomicAdd(&h[key_of(a[u].z) >> 19], 1u);
-            if (j + 3 < d) atomicAdd(&h[key_of(a[u].w) >> 19], 1u);
+            uint32_t keys[4];
+            if (RK) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) keys[q] = rk_priority(k0, k1, j + q);
+            } else {
+                keys[0] = key_of(a[u].x);
+                keys[1] = key_of(a[u].y);
+                keys[2] = key_of(a[u].z);
+                keys[3] = key_of(a[u].w);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (j + q < d) atomicAdd(&h[keys[q] >> 19], 1u);
         }
     }
     __syncthreads();
@@ -615,7 +695,15 @@ __global__ __launch_bounds__(kBlock) void k_list_ties(uint32_t row0, RowDesc* __
 
 // Band for the next step: centred on tau extrapolated by its last change, at least kBandMargin wide
 // on either side, wider when tau is moving or when the last prediction failed.
-__device__ __forceinline__ void predict_band(RowDesc& r) {
+__device__ __forceinline__ void predict_band(RowDesc& r, uint32_t fix_lo, uint32_t fix_hi) {
+    if (fix_hi) {                                   // random-k: the band does not depend on the data
+        r.lo = fix_lo;
+        r.hi = fix_hi;
+        r.prev_tau = r.tau;
+        r.have_prev = 1;
+        r.was_cold = 0;
+        return;
+    }
     const int64_t tau = (int64_t)r.tau;
     const int64_t delta = r.have_prev ? tau - (int64_t)r.prev_tau : 0;
     int64_t margin = 2 * (delta < 0 ? -delta : delta);
@@ -637,7 +725,8 @@ __device__ __forceinline__ void predict_band(RowDesc& r) {
 // predicts the next step's band.  Rows with more ties than the buffer holds go to the slow search.
 __global__ __launch_bounds__(kBlock) void k_list_finish(uint32_t row0, RowDesc* __restrict__ desc,
                                                          uint32_t* __restrict__ lhist,
-                                                         const uint32_t* __restrict__ tiebuf) {
+                                                         const uint32_t* __restrict__ tiebuf, uint32_t cap,
+                                                         uint32_t fix_lo, uint32_t fix_hi) {
     __shared__ uint32_t t_idx[kTieCap];
     __shared__ uint32_t s_cut;
     const uint32_t row = row0 + blockIdx.x;
@@ -661,6 +750,7 @@ __global__ __launch_bounds__(kBlock) void k_list_finish(uint32_t row0, RowDesc* 
     }
     if (threadIdx.x == 0) {
         RowDesc r = desc[row];
+        r.n_list = r.n_cand < cap ? r.n_cand : cap;
         r.n_cand = 0;
         r.n_ties = 0;
         if (fits) {
@@ -668,7 +758,7 @@ __global__ __launch_bounds__(kBlock) void k_list_finish(uint32_t row0, RowDesc* 
             r.dense = 0;
             r.nonfinite = r.nonfinite_acc;
             r.nonfinite_acc = 0;
-            predict_band(r);
+            predict_band(r, fix_lo, fix_hi);
             r.mode = kWarm;
         } else {
             r.mode = kSlow;
@@ -680,9 +770,10 @@ __global__ __launch_bounds__(kBlock) void k_list_finish(uint32_t row0, RowDesc* 
 // General search for rows in kSlow mode, one block of 1024 threads per row: three radix digits
 // over the whole row, then the ties in index order.  Slow by design; only degenerate rows (a
 // threshold shared by thousands of entries) come here.  grid = rows.
-template <bool VEC>
+template <bool VEC, bool RK>
 __global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ src, size_t row_stride, uint32_t d,
-                                                       uint32_t row0, RowDesc* __restrict__ desc, uint32_t k) {
+                                                       uint32_t row0, RowDesc* __restrict__ desc, uint32_t k,
+                                                       RkDraw rk) {
     __shared__ uint32_t h[kHistBins];
     __shared__ uint32_t part[256], res[3];
     __shared__ uint32_t wtot[16];
@@ -691,6 +782,25 @@ __global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ 
     if (desc[row].mode != kSlow) return;
     const float* __restrict__ g = src + (size_t)blockIdx.x * row_stride;
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t k0 = 0, k1 = 0;
+    if (RK) {
+        const uint64_t stream = rk_stream(rk.seed, rk.draw, row);
+        k0 = (uint32_t)stream;
+        k1 = (uint32_t)(stream >> 32);
+    }
+    // the 4 keys of columns j .. j + 3 (columns at or beyond d give unspecified keys; callers test j + q < d)
+    auto keys_at = [&](uint32_t j, uint32_t (&key)[4]) {
+        if (RK) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) key[q] = rk_priority(k0, k1, j + q);
+        } else {
+            const float4 a = ld4<VEC>(g, j, d);
+            key[0] = key_of(a.x);
+            key[1] = key_of(a.y);
+            key[2] = key_of(a.z);
+            key[3] = key_of(a.w);
+        }
+    };
     uint32_t prefix = 0, rank = k, ties = 0;
     if (tid == 0) s_bad = 0;
     for (int pass = 0; pass < 3; ++pass) {
@@ -699,16 +809,14 @@ __global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ 
         for (int b = tid; b < nbins; b += 1024) h[b] = 0;
         __syncthreads();
         for (uint32_t j = tid * 4; j < d; j += 4096) {
-            const float4 a = ld4<VEC>(g, j, d);
-            const float av[4] = {a.x, a.y, a.z, a.w};
+            uint32_t key[4];
+            keys_at(j, key);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t key = key_of(av[q]);
-                if (j + q < d && ((key ^ prefix) >> hi_shift) == 0) atomicAdd(&h[(key >> shift) & (nbins - 1)], 1u);
-            }
+            for (int q = 0; q < 4; ++q)
+                if (j + q < d && ((key[q] ^ prefix) >> hi_shift) == 0) atomicAdd(&h[(key[q] >> shift) & (nbins - 1)], 1u);
         }
         __syncthreads();
-        if (pass == 0) {                       // keys >= 0x7f800000 (Inf/NaN) sit in the bins from 0xff0 up
+        if (pass == 0 && !RK) {                       // keys >= 0x7f800000 (Inf/NaN) sit in the bins from 0xff0 up
             bool bad = false;
             for (int b = 0xff0 + (int)tid; b < kHistBins; b += 1024) bad |= h[b] != 0;
             if (bad) s_bad = 1;
@@ -724,9 +832,10 @@ __global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ 
     uint32_t seen = 0;
     for (uint32_t base = 0; base < d; base += 4096) {          // uniform trip count and exit
         const uint32_t j = base + tid * 4;
-        const float4 a = ld4<VEC>(g, j, d);
-        const bool m0 = j < d && key_of(a.x) == prefix, m1 = j + 1 < d && key_of(a.y) == prefix;
-        const bool m2 = j + 2 < d && key_of(a.z) == prefix, m3 = j + 3 < d && key_of(a.w) == prefix;
+        uint32_t key[4];
+        keys_at(j, key);
+        const bool m0 = j < d && key[0] == prefix, m1 = j + 1 < d && key[1] == prefix;
+        const bool m2 = j + 2 < d && key[2] == prefix, m3 = j + 3 < d && key[3] == prefix;
         const uint32_t mine = m0 + m1 + m2 + m3;
         uint32_t incl = mine;                                   // inclusive scan inside the wave
 #pragma unroll
@@ -765,10 +874,58 @@ __global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ 
         r.nonfinite_acc = 0;
         r.n_cand = 0;
         r.n_ties = 0;
+        r.n_list = 0;
         r.have_prev = 0;
         r.was_cold = 0;
         r.mode = kCold;
+        if (RK) {                              // the band of a random-k draw is known without a prediction
+            r.lo = rk.fix_lo;
+            r.hi = rk.fix_hi;
+            r.mode = kWarm;
+        }
         desc[row] = r;
+    }
+}
+
+// Random-k: completes the kept bitmap of each row once (tau, cut-off) are known.  k_filter has set the
+// bits of the columns whose key is above the band; here the listed candidates that are kept get
+// theirs (atomic OR on the 32-bit word holding the lane's half-word).  Rows that went through the
+// slow search have no valid list: every block recomputes the priorities of its tiles and writes
+// whole half-words.  grid = (blocks, rows).
+__global__ __launch_bounds__(kBlock) void k_rk_mark(uint32_t d, uint32_t nwt, uint32_t row0, const RowDesc* __restrict__ desc,
+                                                     const uint2* __restrict__ list, uint32_t cap,
+                                                     uint16_t* __restrict__ kbits, RkDraw rk) {
+    const uint32_t row = row0 + blockIdx.y;
+    const uint32_t tau = desc[row].tau, cut = desc[row].cutoff;
+    if (!desc[row].dense) {
+        const uint32_t n = desc[row].n_list;
+        const uint2* __restrict__ in = list + (size_t)row * cap;
+        uint32_t* __restrict__ words = reinterpret_cast<uint32_t*>(kbits + (size_t)row * nwt * 64);
+        for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < n; e += gridDim.x * kBlock) {
+            const uint2 kv = in[e];
+            if (kv.x > tau || (kv.x == tau && kv.y <= cut)) {
+                const uint32_t t = kv.y / kWaveTile, o = kv.y % kWaveTile;
+                const uint32_t u = o / kChunk, l = (o % kChunk) / 4, q = o % 4;
+                const uint32_t half = t * 64 + l;                     // half-word of the row holding the column
+                atomicOr(&words[half >> 1], 1u << ((half & 1) * 16 + 4 * u + q));
+            }
+        }
+        return;
+    }
+    const uint64_t stream = rk_stream(rk.seed, rk.draw, row);
+    const uint32_t k0 = (uint32_t)stream, k1 = (uint32_t)(stream >> 32);
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
+        uint32_t m = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t j = t * kWaveTile + u * kChunk + lane * 4 + q;
+                const uint32_t key = rk_priority(k0, k1, j);
+                m |= ((j < d && (key > tau || (key == tau && j <= cut))) ? 1u : 0u) << (4 * u + q);
+            }
+        kbits[((size_t)row * nwt + t) * 64 + lane] = (uint16_t)m;
     }
 }
 
@@ -791,8 +948,10 @@ __device__ __forceinline__ void add_signed(float4 (&acc)[4], uint32_t m, float s
 // Worker message element p^i_j rebuilt from g_ij and the row's descriptor.
 // ---------------------------------------------------------------------------------------------
 template <int WC>
-__device__ __forceinline__ float message_of(float g, uint32_t j, float scale, uint32_t tau, uint32_t cutoff) {
+__device__ __forceinline__ float message_of(float g, uint32_t j, float scale, uint32_t tau, uint32_t cutoff,
+                                            uint32_t keep) {
     if (WC == kSign || WC == kBlockSign) return g < 0.f ? -scale : scale;
+    if (WC == kRandk) return keep ? g : 0.f;
     if (WC == kTopk) {
         const uint32_t key = key_of(g);
         return (key > tau || (key == tau && j <= cutoff)) ? g : 0.f;
@@ -808,6 +967,8 @@ __device__ __forceinline__ float message_of(float g, uint32_t j, float scale, ui
 //                   comes from the column's block);
 //   WC == kTopk     reads each row's group bitmap and fetches only the flagged groups of 4
 //                   gradients, testing them against (tau, cut-off); per-lane sums live in LDS;
+//   WC == kRandk    reads each row's kept bitmap and fetches only the groups of 4 gradients that hold a
+//                   kept column;
 //   WC == kIdentity reads the gradients.
 // ---------------------------------------------------------------------------------------------
 template <int WC, bool SRV_L1, bool VEC>
@@ -818,7 +979,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
                                                        float* __restrict__ v_out, double* __restrict__ srv_partial,
                                                        BlockTable bt) {
     __shared__ double lds_w[4];
-    __shared__ float accs[WC == kTopk ? 16 * kBlock : 1];
+    __shared__ float accs[(WC == kTopk || WC == kRandk) ? 16 * kBlock : 1];
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     double l1 = 0.0;
     for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
@@ -906,6 +1067,35 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
             for (int u = 0; u < 4; ++u)
                 acc[u] = make_float4(my[(4 * u) * kBlock], my[(4 * u + 1) * kBlock], my[(4 * u + 2) * kBlock],
                                      my[(4 * u + 3) * kBlock]);
+        } else if (WC == kRandk) {
+            // the kept bitmap of each row (one half-word per lane and wave tile) names the columns to fetch
+            float* my = accs + threadIdx.x;
+#pragma unroll
+            for (int b = 0; b < 16; ++b) my[b * kBlock] = 0.f;
+            const uint16_t* __restrict__ bw = bits + (size_t)t * 64 + lane;
+            const size_t brow = (size_t)nwt * 64;
+            for (int i = 0; i < N; ++i) {
+                const float* __restrict__ gi = grads + (size_t)i * d;
+                uint32_t m = bw[(size_t)i * brow];
+                while (m) {
+                    const int u = __builtin_ctz(m) >> 2;
+                    const uint32_t nib = (m >> (4 * u)) & 0xfu;
+                    m &= ~(0xfu << (4 * u));
+                    const float4 g = ld4<VEC>(gi, j0 + u * kChunk, d);
+                    const float gv[4] = {g.x, g.y, g.z, g.w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if ((nib >> q) & 1) {
+                            float* slot = my + (4 * u + q) * kBlock;
+                            *slot = __fadd_rn(*slot, gv[q]);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                acc[u] = make_float4(my[(4 * u) * kBlock], my[(4 * u + 1) * kBlock], my[(4 * u + 2) * kBlock],
+                                     my[(4 * u + 3) * kBlock]);
         } else {
             for (int i = 0; i < N; ++i) {
                 const float* __restrict__ gi = grads + (size_t)i * d;
@@ -955,7 +1145,8 @@ template <int WC, int SC, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ grads, float* __restrict__ x,
                                                     const float* __restrict__ v_in, float* __restrict__ e_out, int N,
                                                     uint32_t panel, uint32_t ncol_tiles, uint32_t d, float neg_lr,
-                                                    const RowDesc* __restrict__ desc, BlockTable bt) {
+                                                    const RowDesc* __restrict__ desc, BlockTable bt,
+                                                    const uint16_t* __restrict__ kbits) {
     const uint32_t per_panel = panel * (uint32_t)N;
     const uint32_t pn = blockIdx.x / per_panel, r = blockIdx.x % per_panel;
     const uint32_t i = r / panel, tile = pn * panel + r % panel;
@@ -966,6 +1157,13 @@ __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ gra
     float* __restrict__ xi = x + (size_t)i * d;
     uint32_t tb = 0;
     if (WC == kBlockSign || SC == kBlockSign) tb = bt.tile_blk[tile];   // issued ahead of the streams
+    // random-k: the 4 kept bits of this thread's columns (the thread is lane `threadIdx.x & 63` of chunk
+    // `threadIdx.x >> 6` of wave tile `tile`); row N of the bitmap is the server's draw
+    uint32_t wkeep = 0, skeep = 0;
+    if (WC == kRandk)
+        wkeep = (kbits[((size_t)i * ncol_tiles + tile) * 64 + (threadIdx.x & 63)] >> (4 * (threadIdx.x >> 6))) & 0xfu;
+    if (SC == kRandk)
+        skeep = (kbits[((size_t)N * ncol_tiles + tile) * 64 + (threadIdx.x & 63)] >> (4 * (threadIdx.x >> 6))) & 0xfu;
     const float4 g = ld4<VEC, true>(gi, j, d);
 #if defined(__HIP_DEVICE_COMPILE__)
     // One stream at a time per wave: waiting for the gradients before asking for the model measured
@@ -993,10 +1191,10 @@ __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ gra
         }
     }
     float4 p;
-    p.x = message_of<SC>(v.x, j, ss[0], stau, scut);
-    p.y = message_of<SC>(v.y, j + 1, ss[1], stau, scut);
-    p.z = message_of<SC>(v.z, j + 2, ss[2], stau, scut);
-    p.w = message_of<SC>(v.w, j + 3, ss[3], stau, scut);
+    p.x = message_of<SC>(v.x, j, ss[0], stau, scut, skeep & 1u);
+    p.y = message_of<SC>(v.y, j + 1, ss[1], stau, scut, skeep & 2u);
+    p.z = message_of<SC>(v.z, j + 2, ss[2], stau, scut, skeep & 4u);
+    p.w = message_of<SC>(v.w, j + 3, ss[3], stau, scut, skeep & 8u);
     if (i == 0) {
         float4 en;
         en.x = __fsub_rn(v.x, p.x);
@@ -1007,10 +1205,10 @@ __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ gra
     }
     const uint32_t tau = desc[i].tau, cut = desc[i].cutoff;
     float4 o;
-    o.x = __fmaf_rn(neg_lr, __fadd_rn(p.x, __fsub_rn(g.x, message_of<WC>(g.x, j, sw[0], tau, cut))), xv.x);
-    o.y = __fmaf_rn(neg_lr, __fadd_rn(p.y, __fsub_rn(g.y, message_of<WC>(g.y, j + 1, sw[1], tau, cut))), xv.y);
-    o.z = __fmaf_rn(neg_lr, __fadd_rn(p.z, __fsub_rn(g.z, message_of<WC>(g.z, j + 2, sw[2], tau, cut))), xv.z);
-    o.w = __fmaf_rn(neg_lr, __fadd_rn(p.w, __fsub_rn(g.w, message_of<WC>(g.w, j + 3, sw[3], tau, cut))), xv.w);
+    o.x = __fmaf_rn(neg_lr, __fadd_rn(p.x, __fsub_rn(g.x, message_of<WC>(g.x, j, sw[0], tau, cut, wkeep & 1u))), xv.x);
+    o.y = __fmaf_rn(neg_lr, __fadd_rn(p.y, __fsub_rn(g.y, message_of<WC>(g.y, j + 1, sw[1], tau, cut, wkeep & 2u))), xv.y);
+    o.z = __fmaf_rn(neg_lr, __fadd_rn(p.z, __fsub_rn(g.z, message_of<WC>(g.z, j + 2, sw[2], tau, cut, wkeep & 4u))), xv.z);
+    o.w = __fmaf_rn(neg_lr, __fadd_rn(p.w, __fsub_rn(g.w, message_of<WC>(g.w, j + 3, sw[3], tau, cut, wkeep & 8u))), xv.w);
     st4<VEC, true>(xi, j, d, o);
 }
 
@@ -1100,9 +1298,18 @@ __global__ __launch_bounds__(kBlock) void k_unpack_sign(const uint8_t* __restric
 // ---------------------------------------------------------------------------------------------
 template <bool VEC>
 __device__ __forceinline__ void kept_ballots(const float* __restrict__ g, uint32_t t, uint32_t lane, uint32_t d,
-                                             uint32_t tau, uint32_t cut, float4 (&a)[4], uint64_t (&kb)[4][4]) {
+                                             uint32_t tau, uint32_t cut, const uint16_t* __restrict__ kept_row,
+                                             float4 (&a)[4], uint64_t (&kb)[4][4]) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) a[u] = ld4<VEC>(g, t * kWaveTile + u * kChunk + lane * 4, d);
+    if (kept_row) {                                 // random-k: the kept set is a bitmap (wave-uniform branch)
+        const uint32_t m = kept_row[(size_t)t * 64 + lane];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) kb[u][q] = __ballot((m >> (4 * u + q)) & 1u);
+        return;
+    }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
@@ -1118,13 +1325,15 @@ __device__ __forceinline__ void kept_ballots(const float* __restrict__ g, uint32
 // grid = blocks over the wave tiles of the row.
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_topk_count(const float* __restrict__ g, uint32_t d, uint32_t nwt,
-                                                        const RowDesc* __restrict__ rd, uint32_t* __restrict__ tile_cnt) {
+                                                        const RowDesc* __restrict__ rd,
+                                                        const uint16_t* __restrict__ kept_row,
+                                                        uint32_t* __restrict__ tile_cnt) {
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const uint32_t tau = rd->tau, cut = rd->cutoff;
     for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
         float4 a[4];
         uint64_t kb[4][4];
-        kept_ballots<VEC>(g, t, lane, d, tau, cut, a, kb);
+        kept_ballots<VEC>(g, t, lane, d, tau, cut, kept_row, a, kb);
         uint32_t n = 0;
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -1163,6 +1372,7 @@ __global__ __launch_bounds__(1024) void k_scan_u32(uint32_t* __restrict__ v, uin
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_topk_emit(const float* __restrict__ g, uint32_t d, uint32_t nwt,
                                                        const RowDesc* __restrict__ rd,
+                                                       const uint16_t* __restrict__ kept_row,
                                                        const uint32_t* __restrict__ tile_off, uint32_t k,
                                                        uint32_t* __restrict__ idx_out, float* __restrict__ val_out) {
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -1170,7 +1380,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_emit(const float* __restrict__ 
     for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
         float4 a[4];
         uint64_t kb[4][4];
-        kept_ballots<VEC>(g, t, lane, d, tau, cut, a, kb);
+        kept_ballots<VEC>(g, t, lane, d, tau, cut, kept_row, a, kb);
         uint32_t base = tile_off[t];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {

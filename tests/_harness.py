@@ -17,16 +17,17 @@ TOL_CHAIN = 1e-4
 
 
 def oracle_step_rows(g: np.ndarray, x: np.ndarray, e: np.ndarray, wc: str, sc: str, lr: float,
-                     wk: int = 0, sk: int = 0):
+                     wk: int = 0, sk: int = 0, rng: Tuple[int, int] = (0, 0)):
     """Algorithm 1's compressed iteration assembled from the oracle's phases, with the per-worker
-    phases running concurrently.  x and e are updated in place.  Returns (worker descs, server
-    desc, v, p, P)."""
+    phases running concurrently.  x and e are updated in place.  rng = (seed, draw) names the
+    iteration's random-k draws (worker i draws with row i, the server with row N).  Returns
+    (worker descs, server desc, v, p, P)."""
     N, d = g.shape
-    res = list(POOL.map(lambda i: oracle.compress(wc, g[i], wk), range(N)))
+    res = list(POOL.map(lambda i: oracle.compress(wc, g[i], wk, rng=(rng[0], rng[1], i)), range(N)))
     P = np.stack([r[0] for r in res]) if N > 1 else res[0][0][None, :]
     wdesc = [r[1] for r in res]
     v = oracle.server_average(P, e)
-    p, sdesc = oracle.compress(sc, v, sk)
+    p, sdesc = oracle.compress(sc, v, sk, rng=(rng[0], rng[1], N))
     e[:] = oracle.error_update(v, p)
     list(POOL.map(lambda i: oracle.worker_update(g[i], P[i], p, lr, x[i]), range(N)))
     return wdesc, sdesc, v, p, P

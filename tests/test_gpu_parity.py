@@ -41,20 +41,22 @@ def _check_descs(ctx, w, wdesc, sdesc, g_host, v_host, label):
         for i in range(w.N):
             assert got["scale"][i] == np.float32(wdesc[i].scale), f"{label}: worker {i} scale"
             assert abs(got["l1"][i] - wdesc[i].l1) <= 1e-12 * wdesc[i].l1
-    if w.worker_comp == "topk":
+    if w.worker_comp in ("topk", "randk"):
         for i in range(w.N):
             assert got["tau_key"][i] == wdesc[i].tau_key, f"{label}: worker {i} threshold key"
             assert got["cutoff"][i] == wdesc[i].cutoff, f"{label}: worker {i} tie cut-off"
     if w.server_comp == "sign":
         assert info.server_scale == np.float32(sdesc.scale), f"{label}: server scale"
-    if w.server_comp == "topk":
+    if w.server_comp in ("topk", "randk"):
         assert info.server_tau_key == sdesc.tau_key, f"{label}: server threshold key"
         assert info.server_cutoff == sdesc.cutoff, f"{label}: server tie cut-off"
     assert info.nonfinite == 0
 
 
-def _run_chain(w, steps, seed=0, teacher_forced=False, mutate=None, check_descs=True, tol_end=H.TOL_CHAIN):
-    """Runs `steps` chained steps on both sides and compares after every step."""
+def _run_chain(w, steps, seed=0, teacher_forced=False, mutate=None, check_descs=True, tol_end=H.TOL_CHAIN,
+               rk_seed=0, force_mode=None):
+    """Runs `steps` chained steps on both sides and compares after every step.  rk_seed seeds the
+    random-k draws (draw t in step t); force_mode[t], when given, is the search mode forced before step t."""
     src = workloads.GradientSource(w, seed=seed, device=DEV)
     x = torch.zeros((w.N, w.d), dtype=torch.float32, device=DEV)
     e = torch.zeros(w.d, dtype=torch.float32, device=DEV)
@@ -62,6 +64,7 @@ def _run_chain(w, steps, seed=0, teacher_forced=False, mutate=None, check_descs=
     eo = np.zeros(w.d, dtype=np.float32)
     exact = True
     with _ctx(w) as ctx:
+        ctx.set_random(rk_seed, 0)
         for t in range(steps):
             g = src.grads(t)
             if mutate is not None:
@@ -70,9 +73,11 @@ def _run_chain(w, steps, seed=0, teacher_forced=False, mutate=None, check_descs=
             if teacher_forced and t > 0:
                 x.copy_(torch.from_numpy(xo))
                 e.copy_(torch.from_numpy(eo))
+            if force_mode is not None and force_mode[t] is not None:
+                ctx.force_search_mode(force_mode[t])
             ctx.step(g, x, e)
             wdesc, sdesc, v, p, P = H.oracle_step_rows(gh, xo, eo, w.worker_comp, w.server_comp, w.lr,
-                                                       w.worker_k, w.server_k)
+                                                       w.worker_k, w.server_k, rng=(rk_seed, t))
             xg, eg = x.cpu().numpy(), e.cpu().numpy()
             label = f"{w.name} N={w.N} d={w.d} step {t}"
             if check_descs:
@@ -81,7 +86,7 @@ def _run_chain(w, steps, seed=0, teacher_forced=False, mutate=None, check_descs=
             assert H.rel_err(eg, eo) <= tol, f"{label}: server error"
             assert H.rel_err(xg, xo) <= tol, f"{label}: models"
             # integer-valued parts of the state: the sign pattern / support of the new error
-            if w.server_comp == "topk":
+            if w.server_comp in ("topk", "randk"):
                 assert np.array_equal(eg == 0, eo == 0), f"{label}: server index set"
             exact = exact and H.bit_equal(xg, xo) and H.bit_equal(eg, eo)
     return exact
@@ -285,6 +290,120 @@ def test_per_kernel_timing_and_scratch_accounting():
         ctx.step(g, x, e)                                     # recording is off again
         assert ctx.profile_end() == {}
         assert ctx.info().steps_done == 6
+
+
+# ---- random-k (Definition 3) -----------------------------------------------------------------------
+RK_PAIRS = [("randk", "randk"), ("randk", "sign"), ("topk", "randk"), ("sign", "randk"), ("randk", "identity"),
+            ("identity", "randk"), ("randk", "topk")]
+
+
+@pytest.mark.parametrize("wc,sc", RK_PAIRS)
+@pytest.mark.parametrize("N,d", SMALL_SHAPES)
+def test_random_k_small_shapes(N, d, wc, sc):
+    _say(f"case randk small N={N} d={d} {wc}/{sc}")
+    wk = max(1, d // 50) if wc in ("topk", "randk") else 0
+    sk = max(1, d // 20) if sc in ("topk", "randk") else 0
+    w = workloads.scaled(WL["c2_topk_mid"], N=N, d=d, worker_comp=wc, server_comp=sc, worker_k=wk, server_k=sk, lr=0.05)
+    assert _run_chain(w, steps=3, seed=N * 1000 + d, rk_seed=d * 7 + N), "expected bit identity with the oracle"
+
+
+@pytest.mark.parametrize("d,k", [(5000, 5000), (5000, 1), (5000, 4999), (1024, 512), (262_144, 131_072), (4097, 4096)])
+def test_random_k_extreme_k(d, k):
+    _say(f"case randk extreme d={d} k={k}")
+    w = workloads.scaled(WL["c2_topk_mid"], N=3, d=d, worker_comp="randk", server_comp="randk", worker_k=k, server_k=k)
+    assert _run_chain(w, steps=3, seed=3, rk_seed=1)
+
+
+@pytest.mark.parametrize("modes", [[1, 0, 1], [4, 0, 4], [0, 4, 1]])
+@pytest.mark.parametrize("wc,sc", [("randk", "randk"), ("topk", "topk")])
+def test_every_search_mode_gives_the_same_result(wc, sc, modes):
+    """Predicted band, first-digit histogram and the general search are forced in turn."""
+    _say(f"case forced search modes {wc}/{sc} {modes}")
+    w = workloads.scaled(WL["c2_topk_mid"], N=3, d=150_001, worker_comp=wc, server_comp=sc, worker_k=1500, server_k=7000)
+    assert _run_chain(w, steps=3, seed=8, rk_seed=21, force_mode=modes)
+
+
+def test_random_k_draws_follow_seed_and_counter_and_resume():
+    _say("case randk seed / counter / resume")
+    w = workloads.scaled(WL["c2_topk_mid"], N=4, d=100_000, worker_comp="randk", server_comp="randk",
+                         worker_k=1000, server_k=5000)
+    src = workloads.GradientSource(w, seed=4, device=DEV)
+    gs = [src.grads(t) for t in range(5)]
+
+    def run(seed, split=None, sync_at=None):
+        x = torch.zeros((w.N, w.d), dtype=torch.float32, device=DEV)
+        e = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+        ctx = _ctx(w)
+        ctx.set_random(seed, 0)
+        for t, g in enumerate(gs):
+            if t == split:              # a new context resumes from x, e and the generator's (seed, draw)
+                state = ctx.get_random()
+                ctx.close()
+                ctx = _ctx(w)
+                ctx.set_random(*state)
+            ctx.step(g, x, e)
+        torch.cuda.synchronize()
+        assert ctx.get_random() == (seed, len(gs))
+        ctx.close()
+        return x.cpu().numpy(), e.cpu().numpy()
+
+    a, b, c, other = run(5), run(5), run(5, split=2), run(6)
+    assert H.bit_equal(a[0], b[0]) and H.bit_equal(a[1], b[1])
+    assert H.bit_equal(a[0], c[0]) and H.bit_equal(a[1], c[1])
+    assert not H.bit_equal(a[1], other[1])
+
+
+@pytest.mark.parametrize("N,d,k", [(2, 9, 3), (3, 1001, 50), (4, 70_003, 700), (2, 5000, 5000)])
+def test_random_k_message_wire_form_round_trip(N, d, k):
+    _say(f"case wire randk N={N} d={d} k={k}")
+    import oracle
+    from paper_2402_11857_amd import LiecContext
+
+    w = workloads.scaled(WL["c2_topk_mid"], N=N, d=d, worker_comp="randk", server_comp="sign", worker_k=k, server_k=0)
+    g = workloads.GradientSource(w, seed=d + k, device=DEV).grads(0)
+    gh = g.cpu().numpy()
+    x = torch.zeros((N, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    idx = torch.empty(k, dtype=torch.int32, device=DEV)
+    val = torch.empty(k, dtype=torch.float32, device=DEV)
+    p = torch.empty(d, dtype=torch.float32, device=DEV)
+    with LiecContext(N, d, "randk", "sign", k, 0, 0.1) as ctx:
+        ctx.set_random(77, 3)
+        ctx.step(g, x, e)
+        for i in range(N):
+            idx.fill_(-1)
+            ctx.pack_topk_message(g, i, idx, val)
+            ctx.unpack_topk_message(idx, val, p)
+            torch.cuda.synchronize()
+            ri, rv = oracle.pack_randk(gh[i], k, (77, 3, i))
+            assert np.array_equal(idx.cpu().numpy().view(np.uint32), ri), f"worker {i}: indices"
+            assert H.bit_equal(val.cpu().numpy(), rv), f"worker {i}: values"
+            assert H.bit_equal(p.cpu().numpy(), oracle.compress("randk", gh[i], k, rng=(77, 3, i))[0])
+
+
+def test_wire_scratch_survives_a_sign_unpack_between_two_topk_packs():
+    _say("case wire scratch reuse")
+    import oracle
+    from paper_2402_11857_amd import LiecContext
+
+    N, d, k = 2, 20_000, 200
+    w = workloads.scaled(WL["c2_topk_mid"], N=N, d=d, worker_comp="topk", server_comp="sign", worker_k=k, server_k=0)
+    g = workloads.GradientSource(w, seed=1, device=DEV).grads(0)
+    x = torch.zeros((N, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    idx = torch.empty(k, dtype=torch.int32, device=DEV)
+    val = torch.empty(k, dtype=torch.float32, device=DEV)
+    p = torch.empty(d, dtype=torch.float32, device=DEV)
+    bits = torch.zeros((d + 7) // 8, dtype=torch.uint8, device=DEV)
+    with LiecContext(N, d, "topk", "sign", k, 0, 0.1) as ctx:
+        ctx.step(g, x, e)
+        ctx.pack_topk_message(g, 0, idx, val)
+        ctx.unpack_sign_message(bits, [0.5], False, p)        # allocates the scale staging
+        ctx.pack_topk_message(g, 1, idx, val)
+        torch.cuda.synchronize()
+        ri, rv = oracle.pack_topk(g[1].cpu().numpy(), k)
+        assert np.array_equal(idx.cpu().numpy().view(np.uint32), ri) and H.bit_equal(val.cpu().numpy(), rv)
+        assert np.all(p.cpu().numpy() == 0.5)
 
 
 # ---- Blockwise-SignSGD (Definition 5) --------------------------------------------------------------
@@ -506,13 +625,14 @@ def _full_size_steps(name, steps, seed=0):
     xo = np.zeros((w.N, w.d), dtype=np.float32)
     eo = np.zeros(w.d, dtype=np.float32)
     with _ctx(w) as ctx:
+        ctx.set_random(seed + 1000, 0)
         for t in range(steps):
             g = src.grads(t)
             ctx.step(g, x, e)
             gh = g.cpu().numpy()
             del g
             wdesc, sdesc, v, p, P = H.oracle_step_rows(gh, xo, eo, w.worker_comp, w.server_comp, w.lr,
-                                                       w.worker_k, w.server_k)
+                                                       w.worker_k, w.server_k, rng=(seed + 1000, t))
             _say(f"  oracle step {t} done")
             _check_descs(ctx, w, wdesc, sdesc, gh, v, f"{name} step {t}")
             del P, gh
@@ -539,3 +659,7 @@ def test_full_size_c5_vgg16_mixed():
 
 def test_full_size_c5_vgg16_sign():
     _full_size_steps("c5_vgg16_sign", steps=2)
+
+
+def test_full_size_c4_resnet50_randk():
+    _full_size_steps("c4_resnet50_randk", steps=2)

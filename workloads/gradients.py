@@ -36,8 +36,10 @@ class Workload:
 
     @property
     def alg_bytes_per_step(self) -> int:
-        """Bytes the step must move: grads twice, x in and out, e read twice and written."""
-        return 16 * self.N * self.d + 12 * self.d
+        """Bytes the step must move: grads twice (once when the workers' operator does not look at them:
+        random-k, identity), x in and out, e read twice and written."""
+        reads_of_g = 1 if self.worker_comp in ("randk", "identity") else 2
+        return (8 + 4 * reads_of_g) * self.N * self.d + 12 * self.d
 
 
 def _mk(name, N, d, wc, sc, wk, sk, lr, steps, sizes, lo, hi, out) -> Workload:
@@ -64,6 +66,8 @@ def workloads() -> Dict[str, Workload]:
     # paper does not say where the blocks are cut, so the 62 parameter tensors are grouped in order
     w.append(dataclasses.replace(w[2], name="c3_resnet18_blocksign", worker_comp="blocksign",
                                  server_comp="blocksign", blocks=layer_blocks(r18, 10)))
+    # the ResNet-50 shape with random-k (Definition 3) in place of top-k, same k
+    w.append(dataclasses.replace(w[3], name="c4_resnet50_randk", worker_comp="randk", server_comp="randk"))
     return {x.name: x for x in w}
 
 
