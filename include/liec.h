@@ -76,7 +76,7 @@ typedef struct {
  * liec_create: same operator C and same k on the worker and the server side
  * (the form Algorithm 1 is written in), launching on the default (null) stream.
  *   out         receives the context (host pointer to a host pointer)
- *   N >= 1      number of simulated workers (rows)
+ *   1 <= N <= 65535   number of simulated workers (rows)
  *   1 <= d < 2^31 - 2^20   model dimension (columns); also N * (d / 1024 + 4097) < 2^31
  *   k           kept entries for LIEC_COMP_TOPK / LIEC_COMP_RANDK, 1 <= k <= d; ignored otherwise
  *   lr          learning rate eta, finite
@@ -219,12 +219,14 @@ liec_status liec_set_lr(liec_ctx *ctx, float lr);
  * S = the k indices of highest priority, equal priorities (at most pairs) to the
  * lower index.  liec_set_random sets the seed and the number of the next draw
  * (both 0 in a new context); every liec_step uses one draw number and then
- * advances it by one (liec_step_sync does not).  liec_get_random reads them back,
- * e.g. for a checkpoint.  The gradients are not read to make a draw, so
+ * advances it by one (liec_step_sync does not).  Both live in device memory and
+ * the step advances the number on the device, so a liec_step captured into a HIP
+ * graph makes a new draw at every replay.  liec_get_random reads them back, e.g.
+ * for a checkpoint; both calls synchronise the context's stream.  The gradients are not read to make a draw, so
  * non-finite inputs are not reported for this operator.
  */
 liec_status liec_set_random(liec_ctx *ctx, uint64_t seed, uint64_t draw);
-liec_status liec_get_random(const liec_ctx *ctx, uint64_t *seed, uint64_t *draw);
+liec_status liec_get_random(liec_ctx *ctx, uint64_t *seed, uint64_t *draw);
 
 /*
  * Testing aid for the threshold search behind top-k (Definition 2) and random-k

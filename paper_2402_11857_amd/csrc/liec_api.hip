@@ -84,7 +84,7 @@ struct liec_ctx {
     double* w_partial = nullptr;               // [N * row_blocks]
     double* s_partial = nullptr;               // [agg_blocks]
     uint16_t* bits = nullptr;                  // [(N or N + 1) * nwt * 64] sign bits (sign operators) / kept bits (random-k; row N: server)
-    uint64_t rk_seed = 0, rk_draw = 0;         // random-k: seed and index of the next draw
+    RkState* rk_state = nullptr;               // random-k: seed and number of the next draw (device)
     uint32_t rk_wlo = 0, rk_whi = 0, rk_slo = 0, rk_shi = 0;   // random-k: threshold bands of the worker / server draws
     uint64_t* gbits = nullptr;                 // [N * nwt * 4] group bitmap of the candidates (top-k workers)
     uint2* list = nullptr;                     // [(N + 1) * cap] candidates (key, index)
@@ -155,6 +155,7 @@ void free_scratch(liec_ctx* c) {
     (void)hipFree(c->w_partial);
     (void)hipFree(c->s_partial);
     (void)hipFree(c->bits);
+    (void)hipFree(c->rk_state);
     (void)hipFree(c->gbits);
     (void)hipFree(c->list);
     (void)hipFree(c->sure_partial);
@@ -338,11 +339,11 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
         launch_block_l1<VEC>(L, grads, stride, (uint32_t)c->N, 0u, c->bits, S_W_L1);
     } else if (c->worker_comp == kTopk) {
         launch_select<VEC, false>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, c->gbits,
-                                  c->filter_row_blocks, c->cold_row_blocks, S_W_SEL, RkDraw{0, 0, 0, 0});
+                                  c->filter_row_blocks, c->cold_row_blocks, S_W_SEL, RkDraw{nullptr, 0, 0});
     } else if (c->worker_comp == kRandk) {
         launch_select<VEC, true>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, nullptr,
                                  c->filter_row_blocks, c->cold_row_blocks, S_W_SEL,
-                                 RkDraw{c->rk_seed, c->rk_draw, c->rk_wlo, c->rk_whi});
+                                 RkDraw{c->rk_state, c->rk_wlo, c->rk_whi});
     }
 
     // ---- server: v = e + mean_i p^i, then the descriptor of C_s(v) ---------------------------------
@@ -363,11 +364,11 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
     } else if (c->server_comp == kTopk) {
         // v is always 16-byte aligned scratch, but d % 4 decides whether 128-bit loads stay in bounds
         launch_select<VEC, false>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, nullptr,
-                                  c->filter_srv_blocks, c->cold_srv_blocks, S_S_SEL, RkDraw{0, 0, 0, 0});
+                                  c->filter_srv_blocks, c->cold_srv_blocks, S_S_SEL, RkDraw{nullptr, 0, 0});
     } else if (c->server_comp == kRandk) {
         launch_select<VEC, true>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, nullptr,
                                  c->filter_srv_blocks, c->cold_srv_blocks, S_S_SEL,
-                                 RkDraw{c->rk_seed, c->rk_draw, c->rk_slo, c->rk_shi});
+                                 RkDraw{c->rk_state, c->rk_slo, c->rk_shi});
     }
 
     // ---- p = C_s(v), e <- v - p, x^i <- x^i - lr (p + (g_i - p^i)) ---------------------------------
@@ -377,6 +378,11 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
     case kBlockSign: launch_update_sc<kBlockSign, VEC>(L, c->server_comp, grads, x, e); break;
     case kRandk: launch_update_sc<kRandk, VEC>(L, c->server_comp, grads, x, e); break;
     default: launch_update_sc<kTopk, VEC>(L, c->server_comp, grads, x, e); break;
+    }
+    // the next compressed iteration makes the next draw
+    if (c->worker_comp == kRandk || c->server_comp == kRandk) {
+        k_rk_advance<<<1, 1, 0, c->stream>>>(c->rk_state);
+        if (hipGetLastError() != hipSuccess) L.ok = false;
     }
 }
 
@@ -413,7 +419,8 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
                            liec_comp server_comp, int64_t server_k, float lr, void* hip_stream) {
     if (!out) return LIEC_EINVAL;
     *out = nullptr;
-    if (N < 1 || d < 1 || d >= ((int64_t)1 << 31) - ((int64_t)1 << 20)) return LIEC_EINVAL;
+    // rows are the y dimension of several launch grids (at most 65535 blocks)
+    if (N < 1 || N > 65535 || d < 1 || d >= ((int64_t)1 << 31) - ((int64_t)1 << 20)) return LIEC_EINVAL;
     if (!valid_comp((int)worker_comp) || !valid_comp((int)server_comp) || !finite_f(lr)) return LIEC_EINVAL;
     // the update kernel launches one block per (1024-column tile, row): keep that under 2^31
     if (((d + kColTile - 1) / kColTile + kUpdatePanel) * (int64_t)N >= ((int64_t)1 << 31)) return LIEC_EINVAL;
@@ -469,6 +476,8 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     else if (e == hipSuccess && (worker_comp == LIEC_COMP_SIGN || worker_comp == LIEC_COMP_BLOCKSIGN ||
                                  worker_comp == LIEC_COMP_RANDK))
         e = dev_alloc(c, &c->bits, (size_t)N * c->nwt * 64);
+    if (e == hipSuccess) e = dev_alloc(c, &c->rk_state, 1);
+    if (e == hipSuccess) e = hipMemsetAsync(c->rk_state, 0, sizeof(RkState), c->stream);
     if (e == hipSuccess && worker_comp == LIEC_COMP_TOPK) e = dev_alloc(c, &c->gbits, (size_t)N * c->nwt * 4);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->list, rows * c->cap);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->sure_partial, rows * c->part_stride);
@@ -529,14 +538,18 @@ liec_status liec_step(liec_ctx* c, const float* grads, float* x, float* server_e
         return LIEC_EDEVICE;
     }
     ++c->steps_done;
-    ++c->rk_draw;
     return LIEC_OK;
 }
 
 liec_status liec_set_random(liec_ctx* c, uint64_t seed, uint64_t draw) {
     if (!c) return LIEC_EINVAL;
-    c->rk_seed = seed;
-    c->rk_draw = draw;
+    if (c->broken) return LIEC_EDEVICE;
+    const RkState st{seed, draw};
+    if (hipStreamSynchronize(c->stream) != hipSuccess ||
+        hipMemcpy(c->rk_state, &st, sizeof st, hipMemcpyHostToDevice) != hipSuccess) {
+        c->broken = true;
+        return LIEC_EDEVICE;
+    }
     return LIEC_OK;
 }
 
@@ -561,10 +574,17 @@ liec_status liec_force_search_mode(liec_ctx* c, int32_t mode) {
     return LIEC_OK;
 }
 
-liec_status liec_get_random(const liec_ctx* c, uint64_t* seed, uint64_t* draw) {
+liec_status liec_get_random(liec_ctx* c, uint64_t* seed, uint64_t* draw) {
     if (!c || !seed || !draw) return LIEC_EINVAL;
-    *seed = c->rk_seed;
-    *draw = c->rk_draw;
+    if (c->broken) return LIEC_EDEVICE;
+    RkState st{0, 0};
+    if (hipStreamSynchronize(c->stream) != hipSuccess ||
+        hipMemcpy(&st, c->rk_state, sizeof st, hipMemcpyDeviceToHost) != hipSuccess) {
+        c->broken = true;
+        return LIEC_EDEVICE;
+    }
+    *seed = st.seed;
+    *draw = st.draw;
     return LIEC_OK;
 }
 

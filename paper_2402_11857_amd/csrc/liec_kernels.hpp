@@ -71,8 +71,11 @@ __device__ __forceinline__ uint32_t key_of(float v) { return __float_as_uint(v) 
 // (worker index, or N for the server).  The per-index part is a keyed permutation of 32-bit words
 // (every step is a bijection) with its lowest bit dropped: a 31-bit key like a magnitude key.
 // ---------------------------------------------------------------------------------------------
+struct RkState {               // in device memory, so that a captured step draws anew on every replay
+    uint64_t seed, draw;       // draw: number of the draw the next step makes
+};
 struct RkDraw {
-    uint64_t seed, draw;
+    const RkState* state;
     uint32_t fix_lo, fix_hi;   // band that holds rank k of uniform priorities (set by the host); fix_hi == 0: not random-k
 };
 
@@ -447,7 +450,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     uint32_t k0 = 0, k1 = 0;
     if (RK) {
-        const uint64_t stream = rk_stream(rk.seed, rk.draw, row);
+        const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
         k0 = (uint32_t)stream;
         k1 = (uint32_t)(stream >> 32);
     }
@@ -567,7 +570,7 @@ __global__ __launch_bounds__(kBlock) void k_hist0(const float* __restrict__ src,
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     uint32_t k0 = 0, k1 = 0;
     if (RK) {
-        const uint64_t stream = rk_stream(rk.seed, rk.draw, row);
+        const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
         k0 = (uint32_t)stream;
         k1 = (uint32_t)(stream >> 32);
     }
@@ -784,7 +787,7 @@ __global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ 
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint32_t k0 = 0, k1 = 0;
     if (RK) {
-        const uint64_t stream = rk_stream(rk.seed, rk.draw, row);
+        const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
         k0 = (uint32_t)stream;
         k1 = (uint32_t)(stream >> 32);
     }
@@ -912,7 +915,7 @@ __global__ __launch_bounds__(kBlock) void k_rk_mark(uint32_t d, uint32_t nwt, ui
         }
         return;
     }
-    const uint64_t stream = rk_stream(rk.seed, rk.draw, row);
+    const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
     const uint32_t k0 = (uint32_t)stream, k1 = (uint32_t)(stream >> 32);
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
@@ -928,6 +931,9 @@ __global__ __launch_bounds__(kBlock) void k_rk_mark(uint32_t d, uint32_t nwt, ui
         kbits[((size_t)row * nwt + t) * 64 + lane] = (uint16_t)m;
     }
 }
+
+// One thread, after the last kernel of a step that used the draw.
+__global__ void k_rk_advance(RkState* __restrict__ state) { state->draw += 1; }
 
 // acc[u].{x,y,z,w} += (bit 4u + q of m) ? -s : s  -- one scaled-sign message, 16 columns of a lane.
 __device__ __forceinline__ float signed_scale(uint32_t m, int b, float s) {

@@ -51,6 +51,9 @@ def test_status_strings(lib):
     (2, 16, 2, 0, 0.1),          # top-k with k = 0
     (2, 16, 2, 17, 0.1),         # top-k with k > d
     (2, 16, 1, 0, float("nan")), # lr not finite
+    (65536, 16, 1, 0, 0.1),      # more rows than a launch grid's y dimension holds
+    (2, 16, 4, 0, 0.1),          # random-k with k = 0
+    (2, 16, 4, 17, 0.1),         # random-k with k > d
 ])
 def test_create_rejects_bad_arguments_before_touching_the_device(lib, args):
     h = ctypes.c_void_p()
@@ -62,6 +65,8 @@ def test_create_rejects_bad_arguments_before_touching_the_device(lib, args):
 def test_null_handles_are_rejected_or_ignored(lib):
     assert lib.liec_step(None, None, None, None) == 1
     assert lib.liec_set_lr(None, 0.1) == 1
+    assert lib.liec_set_random(None, 1, 2) == 1
+    assert lib.liec_force_search_mode(None, 0) == 1
     assert lib.liec_scratch_bytes(None) == 0
     lib.liec_destroy(None)
     assert lib.liec_create(None, 1, 1, 0, 0, 0.1) == 1
