@@ -27,6 +27,10 @@ REPEATS = 5                 # timed regions per workload; the median one is repo
 # this script, each counter scaled by what it reads for the 1 GiB copy probe (profiles/liec_step_<workload>.md)
 UPDATE_TRAFFIC_BYTES = {"c5_vgg16_mixed": 28.404e9, "c5_vgg16_sign": 28.400e9, "c3_resnet18_sign": 2.394e9,
                         "c4_resnet50_topk": 10.236e9}
+# the same counters summed over every kernel of one steady-state step (same profiles): what the whole
+# step moves, to be read next to its algorithmic bytes
+STEP_TRAFFIC_BYTES = {"c5_vgg16_mixed": 40.17e9, "c5_vgg16_sign": 39.04e9, "c3_resnet18_sign": 3.291e9,
+                      "c4_resnet50_topk": 14.11e9}
 
 
 def log(msg: str) -> None:
@@ -146,9 +150,32 @@ def cpu_baseline(w, seed: int = 0):
         el = time.perf_counter() - t0
         if el > 10.0 or steps >= 50:
             break
-    return {"value": ws.N * ws.d * steps / el, "unit": "elems/s", "cores": 1, "kind": "oracle",
-            "sample": f"{steps} step(s) of the same recipe cut to N={ws.N}, d={ws.d} columns "
-                      f"(k scaled with d), {el:.1f} s of one host thread"}
+    out = {"value": ws.N * ws.d * steps / el, "unit": "elems/s", "cores": 1, "kind": "oracle",
+           "sample": f"{steps} step(s) of the same recipe cut to N={ws.N}, d={ws.d} columns "
+                     f"(k scaled with d), {el:.1f} s of one host thread"}
+    # the same oracle functions with the per-worker phases of the step on one host thread per worker
+    from concurrent.futures import ThreadPoolExecutor
+
+    threads = min(ws.N, os.cpu_count() or 1, 16)
+    x[:] = 0
+    e[:] = 0
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        steps, t0 = 0, time.perf_counter()
+        while True:
+            res = list(pool.map(lambda i: oracle.compress(ws.worker_comp, g[i], ws.worker_k), range(ws.N)))
+            P = np.stack([r[0] for r in res])
+            v = oracle.server_average(P, e)
+            p, _ = oracle.compress(ws.server_comp, v, ws.server_k)
+            e[:] = oracle.error_update(v, p)
+            list(pool.map(lambda i: oracle.worker_update(g[i], P[i], p, ws.lr, x[i]), range(ws.N)))
+            steps += 1
+            el = time.perf_counter() - t0
+            if el > 5.0 or steps >= 50:
+                break
+    out["workers_in_parallel"] = {"value": ws.N * ws.d * steps / el, "unit": "elems/s", "threads": threads,
+                                  "note": "same oracle functions, the per-worker phases of a step on one thread "
+                                          "per worker; the server phases stay on one thread"}
+    return out
 
 
 def main() -> int:
@@ -217,6 +244,7 @@ def main() -> int:
         "step_alg_bytes": w.alg_bytes_per_step,
         "step_alg_gbps": main_res["alg_gbps"],
         "step_hbm_frac": main_res["alg_gbps"] / HBM_PEAK_GBPS,
+        "step_traffic_bytes": STEP_TRAFFIC_BYTES.get(w.name),
         "copy_kernel_gbps": copy_gbps,
         "roofline": {"bound": "hbm", "kernel": "update", "achieved": main_res["update_gbps"],
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": main_res["update_gbps"] / HBM_PEAK_GBPS,
