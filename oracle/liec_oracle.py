@@ -264,8 +264,9 @@ class BlockStepTrace:
 
 
 def step_blocks(g: np.ndarray, x: np.ndarray, e: np.ndarray, worker_comp, server_comp, lr: float, blocks,
-                worker_k: int = 0, server_k: int = 0) -> BlockStepTrace:
-    """One compressed iteration of Algorithm 1 with Definition 5's block table available to both sides."""
+                worker_k: int = 0, server_k: int = 0, rng: Tuple[int, int] = (0, 0)) -> BlockStepTrace:
+    """One compressed iteration of Algorithm 1 with Definition 5's block table available to both sides
+    (and rng = (seed, draw) for Definition 3's draws)."""
     lib = _load()
     g, x, e = _f32(g), _f32(x, True), _f32(e, True)
     N, d = g.shape
@@ -275,12 +276,12 @@ def step_blocks(g: np.ndarray, x: np.ndarray, e: np.ndarray, worker_comp, server
     sd = _CDesc()
     ws = np.zeros((N, B), dtype=np.float32)
     ss = np.zeros(B, dtype=np.float32)
-    rc = lib.liec_oracle_step_ex(N, d, _comp(worker_comp), int(worker_k), _comp(server_comp), int(server_k),
-                                 ctypes.c_float(lr), _ptr(g), _ptr(x), _ptr(e),
-                                 off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), B, wd, ctypes.byref(sd),
-                                 _ptr(ws), _ptr(ss), None, None, None)
+    rc = lib.liec_oracle_step_rng(N, d, _comp(worker_comp), int(worker_k), _comp(server_comp), int(server_k),
+                                  ctypes.c_float(lr), _ptr(g), _ptr(x), _ptr(e),
+                                  off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), B, int(rng[0]), int(rng[1]),
+                                  wd, ctypes.byref(sd), _ptr(ws), _ptr(ss), None, None, None)
     if rc != 0:
-        raise ValueError(f"liec_oracle_step_ex failed with code {rc}")
+        raise ValueError(f"liec_oracle_step_rng failed with code {rc}")
     return BlockStepTrace([_desc(c) for c in wd], _desc(sd), ws, ss)
 
 

@@ -406,6 +406,48 @@ def test_wire_scratch_survives_a_sign_unpack_between_two_topk_packs():
         assert np.all(p.cpu().numpy() == 0.5)
 
 
+ALL_OPS = ["identity", "sign", "topk", "randk", "blocksign"]
+
+
+@pytest.mark.parametrize("case", range(48))
+def test_random_shapes_and_operator_pairs(case):
+    """Seeded sweep over worker counts (odd, above the 8-row batches of the aggregation, not powers of
+    two), dimensions (log-uniform, ragged against every tile size), k and all 25 operator pairs."""
+    import oracle
+    from paper_2402_11857_amd import LiecContext
+
+    rng = np.random.default_rng(1000 + case)
+    wc, sc = ALL_OPS[case % 5], ALL_OPS[(case // 5 + case) % 5]
+    N = int(rng.choice([1, 2, 3, 5, 7, 9, 12, 17, 24, 33, 70]))
+    d = int(np.exp(rng.uniform(np.log(1), np.log(400_000 // max(1, N // 8)))))
+    wk = int(rng.integers(1, d + 1)) if rng.random() < 0.3 else max(1, d // int(rng.choice([10, 100, 1000])))
+    sk = int(rng.integers(1, d + 1)) if rng.random() < 0.3 else max(1, d // int(rng.choice([10, 100, 1000])))
+    wk = wk if wc in ("topk", "randk") else 0
+    sk = sk if sc in ("topk", "randk") else 0
+    lr = float(rng.choice([0.5, 0.1, 0.01]))
+    nb = int(rng.integers(1, min(d, 40) + 1))
+    off = sorted({0, d, *map(int, rng.integers(0, d + 1, size=nb - 1))})
+    _say(f"case sweep {case}: N={N} d={d} {wc}/{sc} k={wk}/{sk} lr={lr} blocks={len(off) - 1}")
+    w = workloads.scaled(WL["c2_topk_mid"], N=N, d=d, worker_comp=wc, server_comp=sc, worker_k=wk, server_k=sk, lr=lr)
+    src = workloads.GradientSource(w, seed=case, device=DEV)
+    x = torch.zeros((N, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    xo, eo = np.zeros((N, d), dtype=np.float32), np.zeros(d, dtype=np.float32)
+    with LiecContext(N, d, wc, sc, wk, sk, lr) as ctx:
+        ctx.set_random(case, 5)
+        if "blocksign" in (wc, sc):
+            ctx.set_blocks(off)
+        for t in range(3):
+            g = src.grads(t)
+            if case % 3 == 0:
+                g = workloads.inject_ties(g, seed=t, frac_zero=0.2, frac_dup=0.3)
+            ctx.step(g, x, e)
+            tr = oracle.step_blocks(g.cpu().numpy(), xo, eo, wc, sc, lr, off, wk, sk, rng=(case, 5 + t))
+            assert H.bit_equal(e.cpu().numpy(), eo), f"step {t}: server error"
+            assert H.bit_equal(x.cpu().numpy(), xo), f"step {t}: models"
+        assert ctx.info().nonfinite == 0
+
+
 # ---- the step under HIP graph capture ----------------------------------------------------------------
 @pytest.mark.parametrize("wc,sc", [("sign", "sign"), ("topk", "topk"), ("topk", "sign"), ("randk", "randk")])
 def test_step_captured_in_a_hip_graph_replays_like_eager_steps(wc, sc):
