@@ -18,8 +18,10 @@ IDENTITY, SIGN, TOPK, BLOCKSIGN, RANDK = 0, 1, 2, 3, 4
 _NAMES = {"identity": IDENTITY, "sign": SIGN, "topk": TOPK, "blocksign": BLOCKSIGN, "randk": RANDK}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "liec_oracle.c")
-_LIB = os.path.join(_HERE, "libliec_oracle.so")
+# LIEC_ORACLE_SRC / LIEC_ORACLE_LIB point the wrapper at another copy of the C file (the mutation test
+# checks that the pins reject copies with a planted mistake); unset, the file next to this one is used.
+_SRC = os.environ.get("LIEC_ORACLE_SRC") or os.path.join(_HERE, "liec_oracle.c")
+_LIB = os.environ.get("LIEC_ORACLE_LIB") or os.path.join(_HERE, "libliec_oracle.so")
 _lib = None
 
 

@@ -218,3 +218,28 @@ def test_server_average_adds_in_worker_order_then_one_fma(oracle):
     P = P[::-1].copy()
     v = oracle.server_average(P, e)
     assert v[0] == np.float32(np.float32(1.0 + 2.0 ** -23) * np.float32(1.0 / 3.0))
+
+
+def test_server_average_multiplies_and_adds_the_global_error_with_one_rounding(oracle):
+    # acc = 3, 1/N = fl32(1/3) = 11184811 * 2^-25: the exact product is 1 + 2^-25, which a separate
+    # multiply would round to 1 before the error is added; one fused operation keeps it
+    P = np.ones((3, 1), dtype=np.float32)
+    v = oracle.server_average(P, np.array([-1.0], dtype=np.float32))
+    assert v[0] == np.float32(2.0 ** -25)
+    # and the same through a whole step with the identity operator on both sides: x = -lr * v
+    g = np.ones((3, 1), dtype=np.float32)
+    x = np.zeros((3, 1), dtype=np.float32)
+    e = np.array([-1.0], dtype=np.float32)
+    oracle.step(g, x, e, "identity", "identity", 1.0)
+    assert np.all(x == np.float32(-(2.0 ** -25))) and e[0] == 0.0
+
+
+def test_worker_update_is_one_fused_multiply_add(oracle):
+    # lr = fl32(0.1) = 13421773 * 2^-27 and u = 3: the exact product 40265319 * 2^-27 is not an fp32
+    # number (a separate multiply would round it to fl32(0.3) = 40265320 * 2^-27); subtracting it from
+    # x = fl32(0.3) with a single rounding leaves exactly 2^-27
+    lr = np.float32(0.1)
+    x = np.array([0.3], dtype=np.float32)
+    zero = np.zeros(1, dtype=np.float32)
+    oracle.worker_update(zero, zero, np.array([3.0], dtype=np.float32), float(lr), x)
+    assert x[0] == np.float32(2.0 ** -27)

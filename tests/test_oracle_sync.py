@@ -79,3 +79,19 @@ def test_lemma3_and_drift_reset_across_mixed_chains(oracle, wc, sc, period):
         lhs = x.astype(np.float64).mean(axis=0) - virt
         scale = max(np.abs(x).max(), np.abs(e).max(), 1.0)
         assert np.abs(lhs - eta * e).max() <= (t + 1) * 4 * 2.0 ** -23 * scale
+
+
+def test_averaging_iteration_rounds_once_per_fused_operation(oracle):
+    # same numbers as the compressed iteration's pins: 3 * fl32(1/3) - 1 = 2^-25 only if the multiply
+    # and the add of the global error round once ...
+    g = np.ones((3, 1), dtype=np.float32)
+    x = np.zeros((3, 1), dtype=np.float32)
+    e = np.array([-1.0], dtype=np.float32)
+    oracle.step_sync(g, x, e, 1.0)
+    assert np.all(x == np.float32(-(2.0 ** -25))) and e[0] == 0.0
+    # ... and fl32(0.3) - fl32(0.1) * 3 = 2^-27 only if the update does
+    g = np.array([[3.0]], dtype=np.float32)
+    x = np.array([[0.3]], dtype=np.float32)
+    e = np.zeros(1, dtype=np.float32)
+    oracle.step_sync(g, x, e, float(np.float32(0.1)))
+    assert x[0, 0] == np.float32(2.0 ** -27)
