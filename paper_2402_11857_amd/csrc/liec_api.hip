@@ -20,32 +20,31 @@ namespace {
 // Kernel slots for per-kernel timing: worker side, aggregation, server side, update.
 enum Slot : int {
     S_W_L1 = 0, S_W_L1_FINAL,
-    S_W_SEL,                       // 13 slots of the worker-side top-k / random-k search
-    S_AGGREGATE = S_W_SEL + 13,
+    S_W_SEL,                       // kSelSlots slots of the worker-side top-k / random-k search
+    S_AGGREGATE = S_W_SEL + 10,
     S_S_L1, S_S_L1_FINAL,
-    S_S_SEL,                       // 13 slots of the server-side top-k / random-k search
-    S_UPDATE = S_S_SEL + 13,
+    S_S_SEL,                       // kSelSlots slots of the server-side top-k / random-k search
+    S_UPDATE = S_S_SEL + 10,
     S_SYNC,
     S_COUNT
 };
 
-const char* const kWorkerSel[13] = {"worker_filter_warm", "worker_check_warm", "worker_hist0", "worker_pick_band",
-                                    "worker_filter_cold", "worker_check_cold", "worker_list_hist0", "worker_list_hist1",
-                                    "worker_list_hist2", "worker_list_ties", "worker_list_finish", "worker_slow_select",
-                                    "worker_randk_mark"};
-const char* const kServerSel[13] = {"server_filter_warm", "server_check_warm", "server_hist0", "server_pick_band",
-                                    "server_filter_cold", "server_check_cold", "server_list_hist0", "server_list_hist1",
-                                    "server_list_hist2", "server_list_ties", "server_list_finish", "server_slow_select",
-                                    "server_randk_mark"};
+constexpr int kSelSlots = 10;
+const char* const kWorkerSel[kSelSlots] = {"worker_filter_warm", "worker_hist0", "worker_pick_band", "worker_filter_cold",
+                                           "worker_list_hist0", "worker_list_hist1", "worker_list_ties", "worker_list_finish",
+                                           "worker_slow_select", "worker_randk_mark"};
+const char* const kServerSel[kSelSlots] = {"server_filter_warm", "server_hist0", "server_pick_band", "server_filter_cold",
+                                           "server_list_hist0", "server_list_hist1", "server_list_ties", "server_list_finish",
+                                           "server_slow_select", "server_randk_mark"};
 
 const char* slot_name(int s) {
     if (s == S_W_L1) return "worker_l1_bits";
     if (s == S_W_L1_FINAL) return "worker_l1_final";
-    if (s >= S_W_SEL && s < S_W_SEL + 13) return kWorkerSel[s - S_W_SEL];
+    if (s >= S_W_SEL && s < S_W_SEL + kSelSlots) return kWorkerSel[s - S_W_SEL];
     if (s == S_AGGREGATE) return "server_aggregate";
     if (s == S_S_L1) return "server_l1";
     if (s == S_S_L1_FINAL) return "server_l1_final";
-    if (s >= S_S_SEL && s < S_S_SEL + 13) return kServerSel[s - S_S_SEL];
+    if (s >= S_S_SEL && s < S_S_SEL + kSelSlots) return kServerSel[s - S_S_SEL];
     if (s == S_SYNC) return "sync";
     return "update";
 }
@@ -75,7 +74,6 @@ struct liec_ctx {
     uint32_t agg_blocks = 0;                   // aggregation kernel
     uint32_t cold_row_blocks = 0, cold_srv_blocks = 0;   // first-digit histogram (rarely needed)
     uint32_t list_blocks = 0;                  // kernels over the candidate lists
-    uint32_t part_stride = 0;                  // max(filter_row_blocks, filter_srv_blocks)
     uint32_t cap = 0;                          // candidate list capacity per row
 
     // device scratch
@@ -88,9 +86,8 @@ struct liec_ctx {
     uint32_t rk_wlo = 0, rk_whi = 0, rk_slo = 0, rk_shi = 0;   // random-k: threshold bands of the worker / server draws
     uint64_t* gbits = nullptr;                 // [N * nwt * 4] group bitmap of the candidates (top-k workers)
     uint2* list = nullptr;                     // [(N + 1) * cap] candidates (key, index)
-    uint32_t* sure_partial = nullptr;          // [(N + 1) * part_stride]
     uint32_t* ghist = nullptr;                 // [(N + 1) * kHistBins]
-    uint32_t* lhist = nullptr;                 // [(N + 1) * 3 * kHistBins]
+    uint32_t* lhist = nullptr;                 // [(N + 1) * 2 * kListBins]
     uint32_t* tiebuf = nullptr;                // [(N + 1) * kTieCap]
     int64_t scratch_bytes = 0;
 
@@ -158,7 +155,6 @@ void free_scratch(liec_ctx* c) {
     (void)hipFree(c->rk_state);
     (void)hipFree(c->gbits);
     (void)hipFree(c->list);
-    (void)hipFree(c->sure_partial);
     (void)hipFree(c->ghist);
     (void)hipFree(c->lhist);
     (void)hipFree(c->tiebuf);
@@ -177,7 +173,8 @@ void randk_band(int64_t d, int64_t k, uint32_t* lo, uint32_t* hi) {
     const double range = 2147483648.0, dd = (double)d, kk = (double)k;
     const double centre = range * (1.0 - kk / dd);
     const double sigma = range * std::sqrt(kk * (dd - kk) / dd) / dd;
-    const double margin = 8.0 * sigma + 4.0 * range / dd + 16.0;
+    double margin = 8.0 * sigma + 4.0 * range / dd + 16.0;
+    if (margin > 33554432.0) margin = 33554432.0;      // 2^25: the list select spans bands of 2^26 keys
     const double l = std::floor(centre - margin), h = std::ceil(centre + margin);
     *lo = l < 0.0 ? 0u : (uint32_t)l;
     *hi = h > range ? 0x80000000u : (uint32_t)h;
@@ -207,7 +204,7 @@ struct Launcher {
 };
 
 // Top-k threshold search (Definition 2) of `rows` rows of `src`; per-row state lives at row0 + r.
-// The host enqueues the same twelve kernels every step; each one acts only on the rows whose mode
+// The host enqueues the same nine kernels every step; each one acts only on the rows whose state
 // asks for it, so the warm path costs one pass over the data and the others return at once.
 // RK: the same search over the priorities of a random-k draw (Definition 3), which read nothing from
 // `src`, followed by the kernel that completes the kept bitmap.
@@ -220,44 +217,35 @@ void launch_select(Launcher& L, const float* src, size_t row_stride, uint32_t ro
     const dim3 grid(blocks, rows), cold_grid(cold_blocks, rows), list_grid(c->list_blocks, rows);
     L.begin(slot0 + 0);
     k_filter<VEC, RK><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kWarm, gbits, c->bits, c->list,
-                                                c->cap, c->sure_partial, rk);
+                                                c->cap, rk);
     L.end();
     L.begin(slot0 + 1);
-    k_check<<<rows, kBlock, 0, st>>>(row0, c->desc, kWarm, c->sure_partial, blocks, c->cap, k);
+    k_hist0<VEC, RK><<<cold_grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, c->ghist, c->cap, k, rk);
     L.end();
     L.begin(slot0 + 2);
-    k_hist0<VEC, RK><<<cold_grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, c->ghist, rk);
-    L.end();
-    L.begin(slot0 + 3);
     k_pick_band<<<rows, kBlock, 0, st>>>(row0, c->desc, c->ghist, c->cap, k);
     L.end();
-    L.begin(slot0 + 4);
+    L.begin(slot0 + 3);
     k_filter<VEC, RK><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kColdBand, gbits, c->bits,
-                                                c->list, c->cap, c->sure_partial, rk);
+                                                c->list, c->cap, rk);
+    L.end();
+    L.begin(slot0 + 4);
+    k_list_hist<0><<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, k, c->lhist);
     L.end();
     L.begin(slot0 + 5);
-    k_check<<<rows, kBlock, 0, st>>>(row0, c->desc, kColdBand, c->sure_partial, blocks, c->cap, k);
+    k_list_hist<1><<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, k, c->lhist);
     L.end();
     L.begin(slot0 + 6);
-    k_list_hist<0><<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, c->lhist);
+    k_list_ties<<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, k, c->lhist, c->tiebuf);
     L.end();
     L.begin(slot0 + 7);
-    k_list_hist<1><<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, c->lhist);
+    k_list_finish<<<rows, kBlock, 0, st>>>(row0, c->desc, c->lhist, c->tiebuf, c->cap, k, rk.fix_lo, rk.fix_hi);
     L.end();
     L.begin(slot0 + 8);
-    k_list_hist<2><<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, c->lhist);
-    L.end();
-    L.begin(slot0 + 9);
-    k_list_ties<<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, c->lhist, c->tiebuf);
-    L.end();
-    L.begin(slot0 + 10);
-    k_list_finish<<<rows, kBlock, 0, st>>>(row0, c->desc, c->lhist, c->tiebuf, c->cap, rk.fix_lo, rk.fix_hi);
-    L.end();
-    L.begin(slot0 + 11);
     k_slow_select<VEC, RK><<<rows, 1024, 0, st>>>(src, row_stride, d, row0, c->desc, k, rk);
     L.end();
     if (RK) {
-        L.begin(slot0 + 12);
+        L.begin(slot0 + 9);
         k_rk_mark<<<dim3(cold_blocks, rows), kBlock, 0, st>>>(d, c->nwt, row0, c->desc, c->list, c->cap, c->bits, rk);
         L.end();
     }
@@ -462,7 +450,6 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     c->agg_blocks = balanced(16384u);
     c->cold_row_blocks = clampu(2048u / un, 1u, blk_iters);
     c->cold_srv_blocks = clampu(2048u, 1u, blk_iters);
-    c->part_stride = c->filter_row_blocks > c->filter_srv_blocks ? c->filter_row_blocks : c->filter_srv_blocks;
     c->cap = (uint32_t)((d / 16 + 4096 < d) ? d / 16 + 4096 : d);
     c->list_blocks = clampu((c->cap + 2047u) / 2048u, 1u, 64u);
 
@@ -480,9 +467,8 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     if (e == hipSuccess) e = hipMemsetAsync(c->rk_state, 0, sizeof(RkState), c->stream);
     if (e == hipSuccess && worker_comp == LIEC_COMP_TOPK) e = dev_alloc(c, &c->gbits, (size_t)N * c->nwt * 4);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->list, rows * c->cap);
-    if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->sure_partial, rows * c->part_stride);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->ghist, rows * kHistBins);
-    if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->lhist, rows * 3 * kHistBins);
+    if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->lhist, rows * 2 * kListBins);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->tiebuf, rows * kTieCap);
     if (e == hipSuccess) {
         std::vector<RowDesc> init(rows);
@@ -498,7 +484,7 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
         e = hipMemcpy(c->desc, init.data(), rows * sizeof(RowDesc), hipMemcpyHostToDevice);
     }
     if (e == hipSuccess && any_topk) e = hipMemsetAsync(c->ghist, 0, rows * kHistBins * sizeof(uint32_t), c->stream);
-    if (e == hipSuccess && any_topk) e = hipMemsetAsync(c->lhist, 0, rows * 3 * kHistBins * sizeof(uint32_t), c->stream);
+    if (e == hipSuccess && any_topk) e = hipMemsetAsync(c->lhist, 0, rows * 2 * kListBins * sizeof(uint32_t), c->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -566,6 +552,8 @@ liec_status liec_force_search_mode(liec_ctx* c, int32_t mode) {
         if (!selects_k(r < (size_t)c->N ? c->worker_comp : c->server_comp)) continue;
         h[r].mode = (uint32_t)mode;
         h[r].n_cand = 0;
+        clear_sure(h[r]);
+        h[r].n_ties = 0;
     }
     if (hipMemcpy(c->desc, h.data(), h.size() * sizeof(RowDesc), hipMemcpyHostToDevice) != hipSuccess) {
         c->broken = true;

@@ -9,6 +9,7 @@
 // accessed with non-temporal hints.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 namespace liec {
@@ -17,7 +18,10 @@ constexpr int kBlock = 256;             // threads per block (4 waves)
 constexpr int kChunk = 256;             // columns per wave and load instruction
 constexpr int kWaveTile = 1024;         // columns per wave iteration
 constexpr int kColTile = 1024;          // columns per block of the update kernel
-constexpr int kHistBins = 4096;         // widest radix digit (12 bits)
+constexpr int kHistBins = 4096;         // first radix digit of a whole row (12 bits)
+constexpr int kSureStripes = 16;        // counters per row for the keys above the band
+constexpr int kListBits = 13;           // widest radix digit of the list select (two digits cover a band of 2^26 keys)
+constexpr int kListBins = 1 << kListBits;
 constexpr int kStage = 512;             // per-wave LDS staging slots of the candidate filter
 constexpr int kTieCap = 4096;           // ties at the threshold the fast path resolves
 constexpr uint32_t kBandMargin = 1u << 18;   // least half width, in key units, of the predicted band (about 2 % in value)
@@ -27,10 +31,9 @@ enum Comp : int { kIdentity = 0, kSign = 1, kTopk = 2, kBlockSign = 3, kRandk = 
 
 // Progress of a row's top-k threshold search within one step.
 enum SelMode : uint32_t {
-    kWarm = 0,      // a band [lo, hi) predicted from the previous step is to be filtered
+    kWarm = 0,      // a band [lo, hi) predicted from the previous step is filtered
     kCold = 1,      // no usable prediction: the first radix digit of the whole row is needed
-    kColdBand = 2,  // band = the first-digit bin holding rank k; to be filtered
-    kList = 3,      // candidates of the band are listed; select among them
+    kColdBand = 2,  // band = the first-digit bin holding rank k; filtered by the second filter pass
     kSlow = 4       // needs the general (single block, multi pass) search over the row
 };
 
@@ -47,15 +50,43 @@ struct RowDesc {
     uint32_t lo, hi;       // candidate band: keys in [lo, hi) are listed, keys >= hi are surely kept
     uint32_t mode;         // SelMode
     uint32_t n_cand;       // candidates appended so far (may exceed the capacity: overflow)
+    uint32_t n_sure[kSureStripes];   // keys at or above the band seen by the filter pass; block b of the filter adds
+                           // to stripe b % kSureStripes (one address would serialise the blocks' atomics)
     uint32_t n_ties;       // ties collected
     uint32_t n_list;       // candidates that were listed when the search finished (random-k marks the kept ones)
     uint32_t dense;        // the row's candidate bitmap is not valid: test every column
-    uint32_t sel_prefix[3];  // list select: key prefix before digit p
-    uint32_t sel_rank[3];    // list select: rank inside the prefix before digit p
+    uint32_t sel_bin;      // list select: first digit of (tau - lo)
+    uint32_t sel_rank;     // list select: rank of tau inside that digit's bin
     uint32_t prev_tau;     // tau of the step before (valid when have_prev)
     uint32_t have_prev;
     uint32_t was_cold;     // this step's band came from the first-digit histogram, not from a prediction
 };
+
+__host__ __device__ __forceinline__ uint32_t sure_count(const RowDesc& r) {
+    uint32_t n = 0;
+#pragma unroll
+    for (int q = 0; q < kSureStripes; ++q) n += r.n_sure[q];
+    return n;
+}
+__host__ __device__ __forceinline__ void clear_sure(RowDesc& r) {
+#pragma unroll
+    for (int q = 0; q < kSureStripes; ++q) r.n_sure[q] = 0;
+}
+
+// After a filter pass: the band is usable when its list did not overflow and rank k falls inside it.
+__device__ __forceinline__ bool band_ok(const RowDesc& r, uint32_t cap, uint32_t k) {
+    const uint32_t n_sure = sure_count(r);
+    return r.n_cand <= cap && n_sure < k && (uint64_t)k <= (uint64_t)n_sure + r.n_cand &&
+           r.hi - r.lo <= (1u << (2 * kListBits));       // the list select's two digits must span the band
+}
+// Rows that need the first-digit histogram: no prediction, or the predicted band failed.
+__device__ __forceinline__ bool wants_cold(const RowDesc& r, uint32_t cap, uint32_t k) {
+    return r.mode == kCold || (r.mode == kWarm && !band_ok(r, cap, k));
+}
+// Rows whose candidate list holds rank k (evaluated after both filter passes).
+__device__ __forceinline__ bool listable(const RowDesc& r, uint32_t cap, uint32_t k) {
+    return (r.mode == kWarm || r.mode == kColdBand) && band_ok(r, cap, k);
+}
 
 // Radix digits of the 31-bit magnitude key, most significant first.
 __host__ __device__ constexpr int digit_shift(int pass) { return pass == 0 ? 19 : (pass == 1 ? 9 : 0); }
@@ -173,7 +204,7 @@ __device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* lds_wave
     return r;
 }
 
-// Walks a histogram of nbins (512, 1024 or 4096) counts from the top bin down to the bin that
+// Walks a histogram of nbins (a power of two from 256 to 8192) counts from the top bin down to the bin that
 // holds the entry of rank `rank` (1-based, largest first).  Needs blockDim.x >= 256; every thread
 // of the block must call it.  part: 256 words of LDS, res: 3 words of LDS.
 struct Pick {
@@ -181,12 +212,12 @@ struct Pick {
 };
 __device__ __forceinline__ Pick block_pick(const uint32_t* __restrict__ h, int nbins, uint32_t rank,
                                            uint32_t* part, uint32_t* res) {
-    const int per = nbins >> 8;   // 2, 4 or 16 bins per thread
+    const int per = nbins >> 8;   // 1 .. 32 bins per thread
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    uint32_t local[16];
+    uint32_t local[32];
     uint32_t sum = 0;
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
+    for (int q = 0; q < 32; ++q) {
         local[q] = (tid < 256 && q < per) ? h[tid * per + q] : 0u;
         sum += local[q];
     }
@@ -211,7 +242,7 @@ __device__ __forceinline__ Pick block_pick(const uint32_t* __restrict__ h, int n
             uint32_t run = above, bin = tid * per, cnt = local[0];
             bool done = false;
 #pragma unroll
-            for (int q = 15; q >= 0; --q) {
+            for (int q = 31; q >= 0; --q) {
                 if (q < per) {
                     if (!done && run + local[q] >= rank) {
                         bin = tid * per + q;
@@ -396,13 +427,16 @@ __global__ __launch_bounds__(kBlock) void k_l1_items_final(const double* __restr
 //      per wave tile, bit l of word u set when any of the 4 columns 1024t + 256u + 4l .. + 3 has
 //      key >= lo (a quarter of the bytes a per-column bitmap would take; writes are what a
 //      read stream pays most for).
-//      The band is predicted from the previous step's tau (kWarm); when there is none, or the
-//      prediction fails (k_check), the band is the first-radix-digit bin holding rank k, found by
-//      k_hist0 + k_pick_band over the whole row (kCold -> kColdBand), and the row is filtered again.
-//   2. k_list_hist / k_list_ties / k_list_finish run a 3-digit radix select on the listed keys
-//      and order the ties by index.
+//      The band is predicted from the previous step's tau (kWarm).  It is usable when the list
+//      did not overflow and rank k falls inside it (band_ok); when there is no prediction, or it is not
+//      usable, the band becomes the first-radix-digit bin holding rank k, found by k_hist0 +
+//      k_pick_band over the whole row (-> kColdBand), and the row is filtered again.
+//   2. k_list_hist<0>, k_list_hist<1>, k_list_ties and k_list_finish run a 2-digit radix select on
+//      the listed keys, taken relative to the band's lower end, and order the ties by index.
 //   3. Rows the list cannot hold (massive ties, degenerate data) take k_slow_select.
-// All decisions are taken on the device per row; the host always enqueues the same kernels.
+// All decisions are taken on the device per row, each kernel re-deriving from the row's counters
+// whether it has work; only the one-block-per-row kernels (k_pick_band, k_list_finish,
+// k_slow_select) change a row's mode.  The host always enqueues the same kernels.
 // `row0` is added to blockIdx.y to address per-row state (the server's vector uses row N).
 // ---------------------------------------------------------------------------------------------
 // One chunk (256 columns, 4 per lane) of the filter: updates the per-lane count of keys >= hi and the
@@ -439,7 +473,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
                                                     uint32_t nwt, uint32_t row0, RowDesc* __restrict__ desc,
                                                     uint32_t expect_mode, uint64_t* __restrict__ gbits,
                                                     uint16_t* __restrict__ kbits, uint2* __restrict__ list, uint32_t cap,
-                                                    uint32_t* __restrict__ sure_partial, RkDraw rk) {
+                                                    RkDraw rk) {
     __shared__ uint2 stage[4][kStage];
     __shared__ uint32_t wsure[4];
     const uint32_t row = row0 + blockIdx.y;
@@ -512,6 +546,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
             if (gbits && lane < 4) gbits[((size_t)blockIdx.y * nwt + t) * 4 + lane] = word;
         }
     }
+    // keys at or above 0x7f800000 are Inf / NaN (magnitude keys only: priorities use the whole range)
+    if (!RK && __ballot(kmax >= 0x7f800000u) && lane == 0) atomicOr(&desc[row].nonfinite_acc, 1u);
     if (cnt) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         uint32_t base = 0;
@@ -520,50 +556,24 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
         for (uint32_t s = lane; s < cnt; s += 64)
             if (base + s < cap) out[base + s] = st[s];
     }
-    // keys at or above 0x7f800000 are Inf / NaN (magnitude keys only: priorities use the whole range)
-    if (!RK && __ballot(kmax >= 0x7f800000u) && lane == 0) atomicOr(&desc[row].nonfinite_acc, 1u);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) n_hi += __shfl_down(n_hi, o, 64);
     if (lane == 0) wsure[wave] = n_hi;
     __syncthreads();
-    if (threadIdx.x == 0)
-        sure_partial[(size_t)row * gridDim.x + blockIdx.x] = wsure[0] + wsure[1] + wsure[2] + wsure[3];
-}
-
-// grid = rows.  After a filter pass over rows in `expect_mode`: the band is usable when the list did
-// not overflow and rank k falls inside it.
-__global__ __launch_bounds__(kBlock) void k_check(uint32_t row0, RowDesc* __restrict__ desc, uint32_t expect_mode,
-                                                   const uint32_t* __restrict__ sure_partial, uint32_t nparts,
-                                                   uint32_t cap, uint32_t k) {
-    __shared__ uint32_t lds_w[4];
-    const uint32_t row = row0 + blockIdx.x;
-    if (desc[row].mode != expect_mode) return;
-    uint32_t acc = 0;
-    for (uint32_t q = threadIdx.x; q < nparts; q += kBlock) acc += sure_partial[(size_t)row * nparts + q];
-    const uint32_t n_sure = block_sum_u32(acc, lds_w);
     if (threadIdx.x == 0) {
-        RowDesc r = desc[row];
-        const bool ok = r.n_cand <= cap && n_sure < k && (uint64_t)k <= (uint64_t)n_sure + r.n_cand;
-        if (ok) {
-            r.mode = kList;
-            r.sel_prefix[0] = 0;
-            r.sel_rank[0] = k - n_sure;
-        } else {
-            r.mode = expect_mode == kWarm ? kCold : kSlow;
-            r.n_cand = 0;
-        }
-        desc[row] = r;
+        const uint32_t n = wsure[0] + wsure[1] + wsure[2] + wsure[3];
+        if (n) atomicAdd(&desc[row].n_sure[blockIdx.x % kSureStripes], n);
     }
 }
 
-// First radix digit (12 bits) of every key of the rows in kCold mode.  grid = (blocks, rows).
+// First radix digit (12 bits) of every key of the rows that have no usable band.  grid = (blocks, rows).
 template <bool VEC, bool RK>
 __global__ __launch_bounds__(kBlock) void k_hist0(const float* __restrict__ src, size_t row_stride, uint32_t d,
                                                    uint32_t nwt, uint32_t row0, const RowDesc* __restrict__ desc,
-                                                   uint32_t* __restrict__ hist, RkDraw rk) {
+                                                   uint32_t* __restrict__ hist, uint32_t cap, uint32_t k, RkDraw rk) {
     __shared__ uint32_t h[kHistBins];
     const uint32_t row = row0 + blockIdx.y;
-    if (desc[row].mode != kCold) return;
+    if (!wants_cold(desc[row], cap, k)) return;
     const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
     for (int b = threadIdx.x; b < kHistBins; b += kBlock) h[b] = 0;
     __syncthreads();
@@ -606,12 +616,12 @@ __global__ __launch_bounds__(kBlock) void k_hist0(const float* __restrict__ src,
     }
 }
 
-// grid = rows.  For rows in kCold mode: the band becomes the first-digit bin that holds rank k.
+// grid = rows.  For the rows k_hist0 worked on: the band becomes the first-digit bin that holds rank k.
 __global__ __launch_bounds__(kBlock) void k_pick_band(uint32_t row0, RowDesc* __restrict__ desc,
                                                        uint32_t* __restrict__ hist, uint32_t cap, uint32_t k) {
     __shared__ uint32_t part[256], res[3];
     const uint32_t row = row0 + blockIdx.x;
-    if (desc[row].mode != kCold) return;
+    if (!wants_cold(desc[row], cap, k)) return;
     uint32_t* __restrict__ h = hist + (size_t)row * kHistBins;
     const Pick p = block_pick(h, kHistBins, k, part, res);
     for (int b = threadIdx.x; b < kHistBins; b += kBlock) h[b] = 0;
@@ -620,74 +630,105 @@ __global__ __launch_bounds__(kBlock) void k_pick_band(uint32_t row0, RowDesc* __
         r.lo = p.bin << 19;
         r.hi = (p.bin + 1) << 19;            // 0x80000000 for the top bin: no key reaches it
         r.n_cand = 0;
+        clear_sure(r);
         r.was_cold = 1;
         r.mode = p.count <= cap ? kColdBand : kSlow;
         desc[row] = r;
     }
 }
 
-// Radix digit P (0, 1, 2) of the listed keys whose higher digits equal the prefix found so far.
-// Each block first redoes the pick of digit P - 1 from that digit's finished histogram.
-// grid = (blocks, rows); lhist holds 3 histograms of kHistBins per row: [row][P][bin].
+// Blocks of a list kernel that take part for a list of n entries: one per 2048 entries, so that a short
+// list does not pay every block's fixed cost (histogram pick, LDS clear, flush).
+__device__ __forceinline__ uint32_t list_blocks_for(uint32_t n, uint32_t grid) {
+    const uint32_t want = (n + 2047u) / 2048u;
+    return want < 1u ? 1u : (want > grid ? grid : want);
+}
+
+// List select: the keys of a band are taken relative to its lower end; the b bits that the band's width
+// needs (b <= 26) are split into a low digit of ceil(b/2) bits and a high digit of the rest, so a narrow
+// band (the usual 2^19 keys) gets two short histograms and a wide one still fits kListBins bins each.
+struct ListDigits {
+    int low_bits;
+    uint32_t low_bins, high_bins;    // histogram sizes, at least 256 (what block_pick walks)
+};
+__device__ __forceinline__ ListDigits list_digits(const RowDesc& r) {
+    const uint32_t width = r.hi - r.lo;                     // 1 .. 2^26 for a listable row
+    const int b = width > 1 ? 32 - __clz((int)(width - 1)) : 1;
+    ListDigits g;
+    g.low_bits = (b + 1) / 2;
+    g.low_bins = max(256u, 1u << g.low_bits);
+    g.high_bins = max(256u, 1u << (b - g.low_bits));
+    return g;
+}
+
+// P = 0: histogram of the high digit of every listed key.  P = 1: each block first redoes the pick of
+// the high digit from its finished histogram, then counts the low digits of the keys in that bin.
+// grid = (blocks, rows); lhist: [row][P][kListBins].
 template <int P>
 __global__ __launch_bounds__(kBlock) void k_list_hist(uint32_t row0, RowDesc* __restrict__ desc,
-                                                       const uint2* __restrict__ list, uint32_t cap,
+                                                       const uint2* __restrict__ list, uint32_t cap, uint32_t k,
                                                        uint32_t* __restrict__ lhist) {
-    __shared__ uint32_t h[kHistBins];
+    __shared__ uint32_t h[kListBins];
     __shared__ uint32_t part[256], res[3];
     const uint32_t row = row0 + blockIdx.y;
-    if (desc[row].mode != kList) return;
-    uint32_t* __restrict__ hrow = lhist + (size_t)row * 3 * kHistBins;
-    uint32_t prefix = 0;
-    if constexpr (P > 0) {
-        constexpr int Q = P - 1;
-        const Pick p = block_pick(hrow + Q * kHistBins, 1 << digit_bits(Q), desc[row].sel_rank[Q], part, res);
-        prefix = desc[row].sel_prefix[Q] | (p.bin << digit_shift(Q));
+    if (!listable(desc[row], cap, k)) return;
+    const uint32_t n = desc[row].n_cand;                       // <= cap for a listable row
+    const uint32_t nb = list_blocks_for(n, gridDim.x);
+    if (blockIdx.x >= nb) return;
+    uint32_t* __restrict__ hrow = lhist + (size_t)row * 2 * kListBins;
+    const uint32_t lo = desc[row].lo;
+    const ListDigits dg = list_digits(desc[row]);
+    const int nbins = (int)(P == 0 ? dg.high_bins : dg.low_bins);
+    uint32_t bin0 = 0;
+    if constexpr (P == 1) {
+        const Pick p = block_pick(hrow, (int)dg.high_bins, k - sure_count(desc[row]), part, res);
+        bin0 = p.bin;
         if (blockIdx.x == 0 && threadIdx.x == 0) {
-            desc[row].sel_prefix[P] = prefix;
-            desc[row].sel_rank[P] = p.rank_in;
+            desc[row].sel_bin = p.bin;
+            desc[row].sel_rank = p.rank_in;
         }
     }
-    constexpr int nbins = 1 << digit_bits(P);
-    constexpr int shift = digit_shift(P);
-    constexpr int hi_shift = P == 0 ? 31 : digit_shift(P - 1);
     for (int b = threadIdx.x; b < nbins; b += kBlock) h[b] = 0;
     __syncthreads();
-    const uint32_t n = min(desc[row].n_cand, cap);
     const uint2* __restrict__ in = list + (size_t)row * cap;
-    for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < n; e += gridDim.x * kBlock) {
-        const uint32_t key = in[e].x;
-        if (((key ^ prefix) >> hi_shift) == 0) atomicAdd(&h[(key >> shift) & (nbins - 1)], 1u);
+    const uint32_t low_mask = (1u << dg.low_bits) - 1u;
+    for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < n; e += nb * kBlock) {
+        const uint32_t rel = in[e].x - lo;
+        if (P == 0) atomicAdd(&h[rel >> dg.low_bits], 1u);
+        else if ((rel >> dg.low_bits) == bin0) atomicAdd(&h[rel & low_mask], 1u);
     }
     __syncthreads();
-    uint32_t* __restrict__ out = hrow + P * kHistBins;
+    uint32_t* __restrict__ out = hrow + P * kListBins;
     for (int b = threadIdx.x; b < nbins; b += kBlock) {
         const uint32_t c = h[b];
         if (c) atomicAdd(&out[b], c);
     }
 }
 
-// Picks the last digit (-> tau, how many ties are kept, how many there are) and collects the
+// Picks the low digit (-> tau, how many of its ties are kept, how many there are) and collects the
 // indices of the listed entries whose key equals tau.  grid = (blocks, rows).
 __global__ __launch_bounds__(kBlock) void k_list_ties(uint32_t row0, RowDesc* __restrict__ desc,
-                                                       const uint2* __restrict__ list, uint32_t cap,
+                                                       const uint2* __restrict__ list, uint32_t cap, uint32_t k,
                                                        const uint32_t* __restrict__ lhist,
                                                        uint32_t* __restrict__ tiebuf) {
     __shared__ uint32_t part[256], res[3];
     const uint32_t row = row0 + blockIdx.y;
-    if (desc[row].mode != kList) return;
-    const uint32_t* __restrict__ hrow = lhist + (size_t)row * 3 * kHistBins;
-    const Pick p = block_pick(hrow + 2 * kHistBins, 1 << digit_bits(2), desc[row].sel_rank[2], part, res);
-    const uint32_t tau = desc[row].sel_prefix[2] | p.bin;
+    if (!listable(desc[row], cap, k)) return;
+    const uint32_t n = desc[row].n_cand;
+    const uint32_t nb = list_blocks_for(n, gridDim.x);
+    if (blockIdx.x >= nb) return;
+    const uint32_t* __restrict__ hrow = lhist + (size_t)row * 2 * kListBins;
+    const ListDigits dg = list_digits(desc[row]);
+    const Pick p = block_pick(hrow + kListBins, (int)dg.low_bins, desc[row].sel_rank, part, res);
+    const uint32_t tau = desc[row].lo + ((desc[row].sel_bin << dg.low_bits) | p.bin);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         desc[row].tau = tau;
         desc[row].rank = p.rank_in;
         desc[row].ties = p.count;
     }
-    const uint32_t n = min(desc[row].n_cand, cap);
     const uint2* __restrict__ in = list + (size_t)row * cap;
     uint32_t* __restrict__ tb = tiebuf + (size_t)row * kTieCap;
-    for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < n; e += gridDim.x * kBlock) {
+    for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < n; e += nb * kBlock) {
         const uint2 kv = in[e];
         if (kv.x == tau) {
             const uint32_t pos = atomicAdd(&desc[row].n_ties, 1u);
@@ -712,7 +753,7 @@ __device__ __forceinline__ void predict_band(RowDesc& r, uint32_t fix_lo, uint32
     int64_t margin = 2 * (delta < 0 ? -delta : delta);
     if (margin < (int64_t)kBandMargin) margin = kBandMargin;
     if (r.was_cold && margin < 4 * (int64_t)kBandMargin) margin = 4 * (int64_t)kBandMargin;
-    if (margin > (int64_t)1 << 26) margin = (int64_t)1 << 26;
+    if (margin > (int64_t)1 << 25) margin = (int64_t)1 << 25;   // two list digits cover a band of 2^26 keys
     int64_t centre = tau + delta;
     if (centre < 0) centre = 0;
     if (centre > 0x7fffffffll) centre = 0x7fffffffll;
@@ -725,17 +766,30 @@ __device__ __forceinline__ void predict_band(RowDesc& r, uint32_t fix_lo, uint32
 }
 
 // grid = rows.  Orders the collected ties by index, sets the cut-off, clears the list state and
-// predicts the next step's band.  Rows with more ties than the buffer holds go to the slow search.
+// predicts the next step's band.  Rows whose band failed twice, or with more ties than the buffer
+// holds, go to the slow search.
 __global__ __launch_bounds__(kBlock) void k_list_finish(uint32_t row0, RowDesc* __restrict__ desc,
                                                          uint32_t* __restrict__ lhist,
-                                                         const uint32_t* __restrict__ tiebuf, uint32_t cap,
+                                                         const uint32_t* __restrict__ tiebuf, uint32_t cap, uint32_t k,
                                                          uint32_t fix_lo, uint32_t fix_hi) {
     __shared__ uint32_t t_idx[kTieCap];
     __shared__ uint32_t s_cut;
     const uint32_t row = row0 + blockIdx.x;
-    if (desc[row].mode != kList) return;
-    uint32_t* __restrict__ hrow = lhist + (size_t)row * 3 * kHistBins;
-    for (int b = threadIdx.x; b < 3 * kHistBins; b += kBlock) hrow[b] = 0;
+    if (desc[row].mode == kSlow) return;
+    if (!listable(desc[row], cap, k)) {                        // uniform for the block
+        if (threadIdx.x == 0) {
+            RowDesc r = desc[row];
+            r.n_cand = 0;
+            clear_sure(r);
+            r.n_ties = 0;
+            r.n_list = 0;
+            r.mode = kSlow;
+            desc[row] = r;
+        }
+        return;
+    }
+    uint32_t* __restrict__ hrow = lhist + (size_t)row * 2 * kListBins;
+    for (int b = threadIdx.x; b < 2 * kListBins; b += kBlock) hrow[b] = 0;
     const uint32_t ties = desc[row].ties, want = desc[row].rank;
     const bool fits = ties <= (uint32_t)kTieCap;
     if (fits) {
@@ -753,8 +807,9 @@ __global__ __launch_bounds__(kBlock) void k_list_finish(uint32_t row0, RowDesc* 
     }
     if (threadIdx.x == 0) {
         RowDesc r = desc[row];
-        r.n_list = r.n_cand < cap ? r.n_cand : cap;
+        r.n_list = r.n_cand;
         r.n_cand = 0;
+        clear_sure(r);
         r.n_ties = 0;
         if (fits) {
             r.cutoff = s_cut;
@@ -876,6 +931,7 @@ __global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ 
         r.nonfinite = s_bad | r.nonfinite_acc;
         r.nonfinite_acc = 0;
         r.n_cand = 0;
+        clear_sure(r);
         r.n_ties = 0;
         r.n_list = 0;
         r.have_prev = 0;
