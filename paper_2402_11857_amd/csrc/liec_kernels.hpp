@@ -298,7 +298,9 @@ __global__ __launch_bounds__(kBlock) void k_l1_bits(const float* __restrict__ sr
             m |= (a[u].z < 0.f ? 1u : 0u) << (4 * u + 2);
             m |= (a[u].w < 0.f ? 1u : 0u) << (4 * u + 3);
         }
-        bits[((size_t)row * nwt + t) * 64 + lane] = (uint16_t)m;
+        // streaming hint on the bits store: 3.5 % faster than a plain store (the store still costs this
+        // pass a fifth of its time: without it the kernel reads at 6.8 TB/s)
+        __builtin_nontemporal_store((uint16_t)m, &bits[((size_t)row * nwt + t) * 64 + lane]);
 #if defined(__HIP_DEVICE_COMPILE__)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // let the small store land before the next loads (~2 % faster)
 #endif
@@ -1180,7 +1182,9 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
             v.y = __fmaf_rn(acc[u].y, inv_n, e.y);
             v.z = __fmaf_rn(acc[u].z, inv_n, e.z);
             v.w = __fmaf_rn(acc[u].w, inv_n, e.w);
-            st4<VEC>(v_out, j, d, v);
+            // with the gathering operators a streaming store of v measured 10 % faster, with the others slower
+            if (WC == kTopk || WC == kRandk) st4<VEC, true>(v_out, j, d, v);
+            else st4<VEC>(v_out, j, d, v);
             if (SRV_L1) {
                 if (j < d) l1 += (double)fabsf(v.x);
                 if (j + 1 < d) l1 += (double)fabsf(v.y);
