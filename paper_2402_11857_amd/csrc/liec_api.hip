@@ -438,16 +438,21 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     c->ncol_tiles = (uint32_t)((d + kColTile - 1) / kColTile);
     const uint32_t blk_iters = (c->nwt + 3) / 4;               // block iterations that cover one row
     auto clampu = [](uint32_t v, uint32_t lo, uint32_t hi) { return v < lo ? lo : (v > hi ? hi : v); };
-    // Many short-lived blocks stream best here; give every block the same whole number of iterations.
+    // Grid sizes come from sweeps on the VGG-16- and ResNet-shaped workloads.  Every block gets the same
+    // whole number of iterations.
     auto balanced = [&](uint32_t max_blocks) {
         const uint32_t per = (blk_iters + max_blocks - 1) / max_blocks;
         return (blk_iters + per - 1) / per;
     };
-    c->row_blocks = balanced(clampu(262144u / un, 1u, 16384u));
-    // the filter pays one list flush (a global atomic) per wave: fewer, longer-lived blocks
-    c->filter_row_blocks = balanced(clampu(32768u / un, 1u, 8192u));
+    // the scaled-sign pass streams best as one 4096-column iteration per block
+    c->row_blocks = balanced(1u << 20);
+    // the filter pays one list flush (a global atomic) per wave: about 1024 long-lived blocks per row
+    // (more when there are too few rows to fill the chip)
+    c->filter_row_blocks = balanced(clampu(4096u / un, 1024u, 4096u));
     c->filter_srv_blocks = balanced(8192u);
-    c->agg_blocks = balanced(16384u);
+    // the aggregation reads sign bits fastest with many short blocks, and gathers fastest with fewer
+    const bool gathers = worker_comp == LIEC_COMP_TOPK || worker_comp == LIEC_COMP_RANDK;
+    c->agg_blocks = balanced(gathers ? 16384u : 65536u);
     c->cold_row_blocks = clampu(2048u / un, 1u, blk_iters);
     c->cold_srv_blocks = clampu(2048u, 1u, blk_iters);
     c->cap = (uint32_t)((d / 16 + 4096 < d) ? d / 16 + 4096 : d);
