@@ -446,10 +446,11 @@ __global__ __launch_bounds__(kBlock) void k_l1_items_final(const double* __restr
 // the ballots of the candidates lo <= key < hi.  FULL: every column of the chunk is below d.
 template <bool FULL>
 __device__ __forceinline__ uint64_t filter_chunk(const uint32_t (&keys)[4], uint32_t j, uint32_t d, uint32_t lo, uint32_t hi,
-                                                 uint64_t (&bc)[4], uint64_t& any_cand,
+                                                 uint32_t& cand4, uint64_t& any_cand,
                                                  uint32_t& n_hi, uint32_t& kmax, uint32_t& hi4) {
-    uint64_t any_lo = 0;
-    any_cand = 0;
+    // per lane: which of its 4 columns reach the band (lo4) and which lie above it (hi4); two ballots per
+    // chunk tell the wave whether anything has to be listed (the per-column ballots are made only then)
+    uint32_t lo4 = 0;
     hi4 = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -458,13 +459,12 @@ __device__ __forceinline__ uint64_t filter_chunk(const uint32_t (&keys)[4], uint
         const bool ge_lo = valid && key >= lo, ge_hi = valid && key >= hi;
         kmax = max(kmax, valid ? key : 0u);
         n_hi += ge_hi ? 1u : 0u;
+        lo4 |= (ge_lo ? 1u : 0u) << q;
         hi4 |= (ge_hi ? 1u : 0u) << q;
-        const uint64_t bl = __ballot(ge_lo), bh = __ballot(ge_hi);
-        any_lo |= bl;
-        bc[q] = bl & ~bh;
-        any_cand |= bc[q];
     }
-    return any_lo;
+    cand4 = lo4 & ~hi4;
+    any_cand = __ballot(cand4 != 0);
+    return __ballot(lo4 != 0);
 }
 
 // RK: the keys are the priorities of a random-k draw (nothing is read from src), and instead of the
@@ -515,13 +515,16 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
                 keys[2] = key_of(a[u].z);
                 keys[3] = key_of(a[u].w);
             }
-            uint64_t bc[4], any_cand;
-            uint32_t hi4;
-            const uint64_t any_lo = full ? filter_chunk<true>(keys, j, d, lo, hi, bc, any_cand, n_hi, kmax, hi4)
-                                         : filter_chunk<false>(keys, j, d, lo, hi, bc, any_cand, n_hi, kmax, hi4);
+            uint64_t any_cand;
+            uint32_t cand4, hi4;
+            const uint64_t any_lo = full ? filter_chunk<true>(keys, j, d, lo, hi, cand4, any_cand, n_hi, kmax, hi4)
+                                         : filter_chunk<false>(keys, j, d, lo, hi, cand4, any_cand, n_hi, kmax, hi4);
             word = lane == (uint32_t)u ? any_lo : word;
             sure16 |= hi4 << (4 * u);
             if (any_cand) {                                     // wave-uniform
+                uint64_t bc[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) bc[q] = __ballot((cand4 >> q) & 1u);
                 const uint32_t m = __popcll(bc[0]) + __popcll(bc[1]) + __popcll(bc[2]) + __popcll(bc[3]);
                 if (cnt + m > kStage) {                         // flush the staged candidates
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
