@@ -25,11 +25,11 @@ N_GRAD_BUFFERS = 4          # distinct gradient batches rotated through the time
 REPEATS = 5                 # timed regions per workload; the median one is reported
 # HBM bytes one launch of the update kernel moves, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this script, each counter scaled by what it reads for the 1 GiB copy probe (profiles/liec_step_<workload>.md)
-UPDATE_TRAFFIC_BYTES = {"c5_vgg16_mixed": 28.402e9, "c5_vgg16_sign": 28.401e9, "c3_resnet18_sign": 2.394e9,
-                        "c4_resnet50_topk": 10.238e9, "c4_resnet50_randk": 10.349e9}
+UPDATE_TRAFFIC_BYTES = {"c5_vgg16_mixed": 28.406e9, "c5_vgg16_sign": 28.401e9, "c3_resnet18_sign": 2.394e9,
+                        "c4_resnet50_topk": 10.237e9, "c4_resnet50_randk": 10.349e9}
 # the same counters summed over every kernel of one steady-state step (same profiles): what the whole
 # step moves, to be read next to its algorithmic bytes
-STEP_TRAFFIC_BYTES = {"c5_vgg16_mixed": 40.08e9, "c5_vgg16_sign": 39.04e9, "c3_resnet18_sign": 3.291e9,
+STEP_TRAFFIC_BYTES = {"c5_vgg16_mixed": 40.10e9, "c5_vgg16_sign": 39.02e9, "c3_resnet18_sign": 3.291e9,
                       "c4_resnet50_topk": 14.10e9, "c4_resnet50_randk": 10.87e9}
 
 
