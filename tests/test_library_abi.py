@@ -90,3 +90,22 @@ def test_product_never_imports_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h")):
                 src = open(os.path.join(base, f)).read()
                 assert "oracle" not in src.lower(), f"{f} mentions the oracle"
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/liec.h must be usable from C: no C++ types, every declaration a plain C prototype."""
+    import subprocess
+
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "liec.h"\n'
+                   "int main(void) {\n"
+                   "    liec_ctx *c = 0;\n"
+                   "    liec_info info;\n"
+                   "    liec_status (*step)(liec_ctx *, const float *, float *, float *) = liec_step;\n"
+                   "    (void)c; (void)info; (void)step;\n"
+                   "    return (int)LIEC_COMP_RANDK - 4;\n"
+                   "}\n")
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    run = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src)],
+                         capture_output=True, text=True)
+    assert run.returncode == 0, run.stderr
