@@ -203,6 +203,17 @@ liec_status liec_pack_topk_message(liec_ctx *ctx, const float *grads, int32_t wo
 liec_status liec_unpack_topk_message(liec_ctx *ctx, const uint32_t *idx, const float *val, int64_t k,
                                      float *p_out);
 
+/*
+ * Telemetry: the l2 norm of a DEVICE vector of n fp32 values, e.g. of server_err:
+ * the norm of the error variable is what Lemma 1 bounds and what the paper plots
+ * to show the effect of immediate compensation.  Summed in fp64 in a fixed order
+ * on the context's stream (after the work already enqueued there, using the
+ * context's scratch: do not call it between liec_step's kernels from another
+ * thread), then the stream is synchronised and the norm written to the HOST
+ * double *norm_out.  Not part of the step.
+ */
+liec_status liec_l2_norm(liec_ctx *ctx, const float *vec, int64_t n, double *norm_out);
+
 /* Learning-rate schedules (the paper decays eta during training): takes effect
  * from the next liec_step. */
 liec_status liec_set_lr(liec_ctx *ctx, float lr);

@@ -91,6 +91,8 @@ def lib():
         L.liec_set_random.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint64]
         L.liec_get_random.restype = ctypes.c_int
         L.liec_get_random.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
+        L.liec_l2_norm.restype = ctypes.c_int
+        L.liec_l2_norm.argtypes = [vp, vp, i64, ctypes.POINTER(ctypes.c_double)]
         L.liec_force_search_mode.restype = ctypes.c_int
         L.liec_force_search_mode.argtypes = [vp, i32]
         L.liec_get_info.restype = ctypes.c_int
@@ -283,6 +285,14 @@ class LiecContext:
 
     def get_random(self) -> Tuple[int, int]:
         return liec_get_random(self._h)
+
+    def l2_norm(self, vec: torch.Tensor) -> float:
+        """l2 norm of a contiguous fp32 device tensor (e.g. the server error), summed in fp64."""
+        if not (vec.is_cuda and vec.dtype == torch.float32 and vec.is_contiguous()):
+            raise TypeError("l2_norm needs a contiguous fp32 device tensor")
+        out = ctypes.c_double()
+        _check(lib().liec_l2_norm(self._h, vec.data_ptr(), vec.numel(), ctypes.byref(out)), "liec_l2_norm")
+        return float(out.value)
 
     def force_search_mode(self, mode: int) -> None:
         _check(lib().liec_force_search_mode(self._h, mode), "liec_force_search_mode")

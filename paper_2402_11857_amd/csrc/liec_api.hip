@@ -814,6 +814,24 @@ liec_status liec_unpack_topk_message(liec_ctx* c, const uint32_t* idx, const flo
     return LIEC_OK;
 }
 
+liec_status liec_l2_norm(liec_ctx* c, const float* vec, int64_t n, double* norm_out) {
+    if (!c || !vec || !norm_out || n < 1 || ((uintptr_t)vec & 3u)) return LIEC_EINVAL;
+    if (c->broken) return LIEC_EDEVICE;
+    // s_partial holds agg_blocks doubles; one more double behind the worker partials receives the sum
+    const uint32_t blocks = (uint32_t)std::min<int64_t>((n + kBlock - 1) / kBlock, (int64_t)std::min<uint32_t>(c->agg_blocks, 4096u));
+    k_sumsq<<<blocks, kBlock, 0, c->stream>>>(vec, (uint64_t)n, c->s_partial);
+    k_sumsq_final<<<1, kBlock, 0, c->stream>>>(c->s_partial, blocks, c->w_partial);
+    double sum = 0.0;
+    if (hipGetLastError() != hipSuccess ||
+        hipMemcpyAsync(&sum, c->w_partial, sizeof sum, hipMemcpyDeviceToHost, c->stream) != hipSuccess ||
+        hipStreamSynchronize(c->stream) != hipSuccess) {
+        c->broken = true;
+        return LIEC_EDEVICE;
+    }
+    *norm_out = std::sqrt(sum);
+    return LIEC_OK;
+}
+
 liec_status liec_set_lr(liec_ctx* c, float lr) {
     if (!c || !finite_f(lr)) return LIEC_EINVAL;
     c->lr = lr;

@@ -448,6 +448,31 @@ def test_random_shapes_and_operator_pairs(case):
         assert ctx.info().nonfinite == 0
 
 
+def test_error_norm_telemetry():
+    """The l2 norm of the error variable (what Lemma 1 bounds) against a float64 sum of the oracle's state."""
+    _say("case l2 norm")
+    w = workloads.scaled(WL["c2_topk_mid"], N=4, d=300_001, worker_comp="topk", server_comp="topk", worker_k=3000, server_k=3000)
+    src = workloads.GradientSource(w, seed=2, device=DEV)
+    x = torch.zeros((w.N, w.d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(w.d, dtype=torch.float32, device=DEV)
+    xo, eo = np.zeros((w.N, w.d), dtype=np.float32), np.zeros(w.d, dtype=np.float32)
+    with _ctx(w) as ctx:
+        assert ctx.l2_norm(e) == 0.0
+        for t in range(4):
+            g = src.grads(t)
+            ctx.step(g, x, e)
+            H.oracle_step_rows(g.cpu().numpy(), xo, eo, "topk", "topk", w.lr, w.worker_k, w.server_k)
+            ref = float(np.sqrt(np.sum(eo.astype(np.float64) ** 2)))
+            assert abs(ctx.l2_norm(e) - ref) <= 1e-12 * ref, f"step {t}"
+        for n in (1, 5, 1023, 300_001):
+            v = torch.randn(n, dtype=torch.float32, device=DEV)
+            ref = float(np.sqrt(np.sum(v.cpu().numpy().astype(np.float64) ** 2)))
+            assert abs(ctx.l2_norm(v) - ref) <= 1e-12 * ref
+        ctx.step(src.grads(4), x, e)                      # the scratch it borrowed is the step's again
+        H.oracle_step_rows(src.grads(4).cpu().numpy(), xo, eo, "topk", "topk", w.lr, w.worker_k, w.server_k)
+        assert H.bit_equal(x.cpu().numpy(), xo) and H.bit_equal(e.cpu().numpy(), eo)
+
+
 # ---- the step under HIP graph capture ----------------------------------------------------------------
 @pytest.mark.parametrize("wc,sc", [("sign", "sign"), ("topk", "topk"), ("topk", "sign"), ("randk", "randk")])
 def test_step_captured_in_a_hip_graph_replays_like_eager_steps(wc, sc):
