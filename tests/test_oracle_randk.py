@@ -170,3 +170,25 @@ def test_bad_k_is_rejected():
     for k in (0, 9, -1):
         with pytest.raises(ValueError):
             oracle.compress("randk", v, k)
+
+
+def test_lemma_1_bound_on_the_global_error_with_random_k():
+    # Lemma 1 (needs Assumption 4, which random-k satisfies with delta = k/d):
+    #   E||e_t||^2 <= 4 (1 - delta) (2 (2 - delta) + delta^2 (N - 1)) M^2 / (delta^2 N),
+    # M^2 a bound on ||g_i||^2.  Checked at every step of a long chain, on the running mean over steps
+    # (the expectation is over the draws) and, with the bound's slack, on every single step.
+    N, d, k, T, lr = 4, 400, 100, 300, 0.05
+    delta = k / d
+    g_rng = np.random.default_rng(6)
+    x = np.zeros((N, d), dtype=np.float32)
+    e = np.zeros(d, dtype=np.float32)
+    m2, norms = 0.0, []
+    for t in range(T):
+        g = g_rng.standard_normal((N, d)).astype(np.float32)
+        m2 = max(m2, float((g.astype(np.float64) ** 2).sum(axis=1).max()))
+        oracle.step(g, x, e, "randk", "randk", lr, worker_k=k, server_k=k, rng=(31, t))
+        norms.append(float((e.astype(np.float64) ** 2).sum()))
+    bound = 4 * (1 - delta) * (2 * (2 - delta) + delta ** 2 * (N - 1)) * m2 / (delta ** 2 * N)
+    assert max(norms) <= bound
+    assert np.mean(norms[T // 2:]) <= bound
+    assert np.mean(norms[T // 2:]) > 0.0          # the error is really carried from step to step
