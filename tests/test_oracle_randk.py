@@ -192,3 +192,36 @@ def test_lemma_1_bound_on_the_global_error_with_random_k():
     assert max(norms) <= bound
     assert np.mean(norms[T // 2:]) <= bound
     assert np.mean(norms[T // 2:]) > 0.0          # the error is really carried from step to step
+
+
+def test_generator_is_the_one_the_public_header_states():
+    """include/liec.h states the generator in words and formulas; this re-states those formulas with
+    Python integers (a cross-language check of wrap-around and shifts, not a pin of the design)."""
+    M64, M32 = (1 << 64) - 1, (1 << 32) - 1
+
+    def mix(z):
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M64
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M64
+        return z ^ (z >> 31)
+
+    def priority(seed, draw, row, j):
+        G = 0x9E3779B97F4A7C15
+        s = mix((mix((mix((seed + G) & M64) + draw + G) & M64) + row + G) & M64)
+        h = (j ^ (s & M32)) & M32
+        h ^= h >> 16
+        h = (h * 0x85EBCA6B) & M32
+        h ^= h >> 13
+        h = (h + (s >> 32)) & M32
+        h = (h * 0xC2B2AE35) & M32
+        h ^= h >> 16
+        return h >> 1
+
+    rng = np.random.default_rng(12)
+    for _ in range(40):
+        seed, draw = int(rng.integers(0, 1 << 63)) * 2 + 1, int(rng.integers(0, 1 << 62))
+        row, d = int(rng.integers(0, 70)), int(rng.integers(1, 300))
+        got = oracle.randk_priorities(d, (seed, draw, row))
+        assert got.tolist() == [priority(seed, draw, row, j) for j in range(d)]
+    # the largest values of every argument
+    got = oracle.randk_priorities(3, (M64, M64, M32))
+    assert got.tolist() == [priority(M64, M64, M32, j) for j in range(3)]
