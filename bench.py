@@ -20,7 +20,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 DEFAULT_WORKLOAD = "c5_vgg16_mixed"   # the largest configuration; fits one GPU (grads 8.25 GiB)
-ALSO = ["c3_resnet18_sign", "c3_resnet18_blocksign", "c4_resnet50_topk", "c4_resnet50_randk", "c5_vgg16_sign"]
+ALSO = ["c3_resnet18_sign", "c3_resnet18_blocksign", "c4_resnet50_topk", "c4_resnet50_randk", "c5_vgg16_sign",
+        "c1_tiny_sign", "c2_topk_mid"]
+# small configurations whose tensors fit the caches and whose step is a chain of short dependent kernels
+CACHE_RESIDENT = {"c1_tiny_sign": "1 MiB of gradients: cache-resident, bound by the gaps between 5 dependent kernels",
+                  "c2_topk_mid": "32 MiB of gradients: cache-resident, bound by the gaps between 20 dependent kernels"}
 N_GRAD_BUFFERS = 4          # distinct gradient batches rotated through the timed steps
 REPEATS = 5                 # timed regions per workload; the median one is reported
 # HBM bytes one launch of the update kernel moves, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
@@ -218,6 +222,8 @@ def main() -> int:
                           "update_gbps": round(r["update_gbps"], 1),
                           "averaging_iteration_ms": round(r["sync_ms"], 4),
                           "kernels_ms_per_step": {k: round(v, 4) for k, v in r["kernels_ms_per_step"].items()}}
+            if name in CACHE_RESIDENT:
+                also[name]["note"] = CACHE_RESIDENT[name]
             log(f"{name}: {r['ms_per_step']:.3f} ms/step, {r['alg_gbps']:.0f} GB/s algorithmic")
     cpu = None
     if not args.no_cpu_baseline:
