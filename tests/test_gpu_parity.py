@@ -759,15 +759,15 @@ def _full_size_steps(name, steps, seed=0):
 
 
 def test_full_size_c3_resnet18_sign():
-    _full_size_steps("c3_resnet18_sign", steps=3)
+    _full_size_steps("c3_resnet18_sign", steps=5)
 
 
 def test_full_size_c4_resnet50_topk():
-    _full_size_steps("c4_resnet50_topk", steps=2)
+    _full_size_steps("c4_resnet50_topk", steps=3)       # cold, predicted band, band extrapolated from two thresholds
 
 
 def test_full_size_c5_vgg16_mixed():
-    _full_size_steps("c5_vgg16_mixed", steps=2)       # step 0 takes the cold path, step 1 the predicted band
+    _full_size_steps("c5_vgg16_mixed", steps=3)       # cold, predicted band, band extrapolated from two thresholds
 
 
 def test_full_size_c5_vgg16_sign():
