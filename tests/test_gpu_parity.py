@@ -448,6 +448,21 @@ def test_random_shapes_and_operator_pairs(case):
         assert ctx.info().nonfinite == 0
 
 
+@pytest.mark.parametrize("wc,sc", [("topk", "topk"), ("topk", "sign")])
+def test_threshold_prediction_survives_jumps_of_the_gradient_scale(wc, sc):
+    """The band predicted from the last thresholds misses when the gradients' scale jumps; the step must
+    then find the threshold the long way and still match the oracle (drifts are followed by the trend)."""
+    _say(f"case scale jumps {wc}/{sc}")
+    w = workloads.scaled(WL["c2_topk_mid"], N=3, d=180_000, worker_comp=wc, server_comp=sc, worker_k=1800,
+                         server_k=4000 if sc == "topk" else 0)
+    scales = [1.0, 1.0, 4.0, 4.2, 4.4, 0.05, 0.05, 0.049, 1e-6, 3.0]
+
+    def mutate(g, t):
+        return g * scales[t]
+
+    assert _run_chain(w, steps=len(scales), seed=17, mutate=mutate)
+
+
 def test_error_norm_telemetry():
     """The l2 norm of the error variable (what Lemma 1 bounds) against a float64 sum of the oracle's state."""
     _say("case l2 norm")
