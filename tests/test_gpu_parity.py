@@ -463,6 +463,27 @@ def test_threshold_prediction_survives_jumps_of_the_gradient_scale(wc, sc):
     assert _run_chain(w, steps=len(scales), seed=17, mutate=mutate)
 
 
+@pytest.mark.parametrize("wc,sc", [("sign", "sign"), ("topk", "topk"), ("identity", "identity")])
+def test_subnormal_and_huge_magnitudes(wc, sc):
+    """fp32 subnormals must be kept, not flushed, and magnitudes near the top of the range must not overflow
+    the fp64 L1 sums: gradients span 1e-44 .. 1e37."""
+    _say(f"case subnormal / huge {wc}/{sc}")
+    w = workloads.scaled(WL["c2_topk_mid"], N=3, d=20_000, worker_comp=wc, server_comp=sc,
+                         worker_k=300 if wc == "topk" else 0, server_k=700 if sc == "topk" else 0, lr=0.5)
+
+    def mutate(g, t):
+        g = g.clone()
+        g[:, 0::3] *= 1e-41          # subnormal range
+        g[:, 1::3] *= 1e-38          # around the smallest normal number
+        if t == 1:
+            g[:, 2::3] *= 1e34       # large but finite: sums of 2e4 of them stay finite in fp32 messages too
+        tiny = g[:, 0::3].abs()
+        assert ((tiny > 0) & (tiny < 1.1754944e-38)).float().mean() > 0.9, "the inputs must really be subnormal"
+        return g
+
+    assert _run_chain(w, steps=3, seed=23, mutate=mutate)
+
+
 def test_error_norm_telemetry():
     """The l2 norm of the error variable (what Lemma 1 bounds) against a float64 sum of the oracle's state."""
     _say("case l2 norm")
