@@ -484,6 +484,86 @@ def test_subnormal_and_huge_magnitudes(wc, sc):
     assert _run_chain(w, steps=3, seed=23, mutate=mutate)
 
 
+def test_largest_dimension_the_library_accepts():
+    """d just below the limit of liec_create (2^31 - 2^20): column indices and tile counts near the top
+    of the 32-bit range; one worker, scaled sign on both sides, every element compared."""
+    import oracle
+    from paper_2402_11857_amd import LiecContext, LiecError
+
+    d = (1 << 31) - (1 << 20) - 4
+    _say(f"case largest dimension d={d}")
+    with pytest.raises(LiecError):
+        LiecContext(1, d + 4, "sign", "sign", 0, 0, 0.1)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(77)
+    g = torch.empty((1, d), dtype=torch.float32, device=DEV)
+    g.normal_(generator=gen)
+    g[0, -5:] = torch.tensor([3.0, -0.0, 0.0, -2.0, 1.5], device=DEV)      # the last columns, exactly known
+    x = torch.zeros((1, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    with LiecContext(1, d, "sign", "sign", 0, 0, 0.1) as ctx:
+        ctx.step(g, x, e)
+        torch.cuda.synchronize()
+        scale = ctx.worker_desc()["scale"][0]
+        assert ctx.info().nonfinite == 0
+    gh = g.cpu().numpy()
+    del g
+    xo, eo = np.zeros((1, d), dtype=np.float32), np.zeros(d, dtype=np.float32)
+    tr = oracle.step(gh, xo, eo, "sign", "sign", 0.1)
+    _say("  oracle step done")
+    assert scale == np.float32(tr.worker[0].scale)
+    assert H.bit_equal(e.cpu().numpy(), eo)
+    assert H.bit_equal(x.cpu().numpy(), xo)
+
+
+def test_largest_dimension_with_top_k():
+    """The same dimension with top-k on both sides.  A full sort of 2^31 keys is beyond what the oracle
+    finishes in the time a test has, so Definition 2 is checked through what is unique in it: the k-th
+    largest key (numpy's selection), the number of larger keys, the cut-off among the ties, and then
+    every element of the new state recomputed from those with single IEEE operations."""
+    from paper_2402_11857_amd import LiecContext
+
+    d, kw, ks, lr = (1 << 31) - (1 << 20) - 4, 100_000, 40_000, np.float32(0.1)
+    _say(f"case largest dimension, top-k d={d}")
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(78)
+    g = torch.empty((1, d), dtype=torch.float32, device=DEV)
+    g.normal_(generator=gen)
+    g[0, -3:] = torch.tensor([9.0, -9.0, 9.0], device=DEV)          # ties of the largest magnitude in the last columns
+    x = torch.zeros((1, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    with LiecContext(1, d, "topk", "topk", kw, ks, float(lr)) as ctx:
+        ctx.step(g, x, e)
+        torch.cuda.synchronize()
+        wd, info = ctx.worker_desc(), ctx.info()
+        assert info.nonfinite == 0
+    gh = g.cpu().numpy()[0]
+    del g
+
+    def select(vals, k):
+        keys = vals.view(np.uint32) & np.uint32(0x7FFFFFFF)
+        tau = np.partition(keys, vals.size - k)[vals.size - k]
+        above = int((keys > tau).sum())
+        ties = np.flatnonzero(keys == tau)
+        cut = int(ties[k - above - 1])
+        mask = keys > tau
+        mask[ties[:k - above]] = True
+        return int(tau), cut, mask
+
+    tau_w, cut_w, mask_w = select(gh, kw)
+    _say("  worker selection done")
+    assert (wd["tau_key"][0], wd["cutoff"][0]) == (tau_w, cut_w)
+    p1 = np.where(mask_w, gh, np.float32(0.0))
+    v = (np.float32(0.0) + p1) * np.float32(1.0) + np.float32(0.0)   # +0 + p, then fma(acc, 1/N = 1, e = 0)
+    tau_s, cut_s, mask_s = select(v, ks)
+    _say("  server selection done")
+    assert (info.server_tau_key, info.server_cutoff) == (tau_s, cut_s)
+    p = np.where(mask_s, v, np.float32(0.0))
+    assert H.bit_equal(e.cpu().numpy(), v - p)
+    u = p + (gh - p1)
+    assert H.bit_equal(x.cpu().numpy()[0], (-lr) * u + np.float32(0.0))
+
+
 def test_error_norm_telemetry():
     """The l2 norm of the error variable (what Lemma 1 bounds) against a float64 sum of the oracle's state."""
     _say("case l2 norm")
