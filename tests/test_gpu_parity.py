@@ -484,6 +484,16 @@ def test_subnormal_and_huge_magnitudes(wc, sc):
     assert _run_chain(w, steps=3, seed=23, mutate=mutate)
 
 
+@pytest.mark.parametrize("N,d,wc,sc", [(65535, 5, "sign", "sign"), (65535, 8, "identity", "sign"), (20_000, 9, "topk", "topk"),
+                                        (20_000, 12, "randk", "sign")])
+def test_largest_worker_counts(N, d, wc, sc):
+    """As many rows as a launch grid's second dimension holds (liec_create's limit on N), short rows."""
+    _say(f"case many workers N={N} d={d} {wc}/{sc}")
+    w = workloads.scaled(WL["c2_topk_mid"], N=N, d=d, worker_comp=wc, server_comp=sc,
+                         worker_k=2 if wc in ("topk", "randk") else 0, server_k=3 if sc == "topk" else 0, lr=0.05)
+    assert _run_chain(w, steps=2, seed=N + d, rk_seed=4, check_descs=False)
+
+
 def test_largest_dimension_the_library_accepts():
     """d just below the limit of liec_create (2^31 - 2^20): column indices and tile counts near the top
     of the 32-bit range; one worker, scaled sign on both sides, every element compared."""
