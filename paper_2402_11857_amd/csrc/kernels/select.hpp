@@ -1,0 +1,583 @@
+// Threshold search behind top-k (Definition 2) and random-k (Definition 3).
+#pragma once
+#include "common.hpp"
+
+namespace liec {
+
+// ---------------------------------------------------------------------------------------------
+// Top-k (Definition 2).  The k-th largest magnitude key tau of a row and the index cut-off
+// among its ties are found without sorting:
+//   1. k_filter streams the row once against a band [lo, hi) of keys expected to hold tau:
+//      keys >= hi are only counted, keys inside the band are appended to a candidate list
+//      (key, index), and a group bitmap is written for the aggregation kernel: 4 words of 64 bits
+//      per wave tile, bit l of word u set when any of the 4 columns 1024t + 256u + 4l .. + 3 has
+//      key >= lo (a quarter of the bytes a per-column bitmap would take; writes are what a
+//      read stream pays most for).
+//      The band is predicted from the previous step's tau (kWarm).  It is usable when the list
+//      did not overflow and rank k falls inside it (band_ok); when there is no prediction, or it is not
+//      usable, the band becomes the first-radix-digit bin holding rank k, found by k_hist0 +
+//      k_pick_band over the whole row (-> kColdBand), and the row is filtered again.
+//   2. k_list_hist<0>, k_list_hist<1>, k_list_ties and k_list_finish run a 2-digit radix select on
+//      the listed keys, taken relative to the band's lower end, and order the ties by index.
+//   3. Rows the list cannot hold (massive ties, degenerate data) take k_slow_select.
+// All decisions are taken on the device per row, each kernel re-deriving from the row's counters
+// whether it has work; only the one-block-per-row kernels (k_pick_band, k_list_finish,
+// k_slow_select) change a row's mode.  The host always enqueues the same kernels.
+// `row0` is added to blockIdx.y to address per-row state (the server's vector uses row N).
+// ---------------------------------------------------------------------------------------------
+// One chunk (256 columns, 4 per lane) of the filter: updates the per-lane count of keys >= hi and the
+// running maximum key, returns the ballot of "any of my 4 columns has key >= lo" and, per component,
+// the ballots of the candidates lo <= key < hi.  FULL: every column of the chunk is below d.
+template <bool FULL>
+__device__ __forceinline__ uint64_t filter_chunk(const uint32_t (&keys)[4], uint32_t j, uint32_t d, uint32_t lo, uint32_t hi,
+                                                 uint32_t& cand4, uint64_t& any_cand,
+                                                 uint32_t& n_hi, uint32_t& kmax, uint32_t& hi4) {
+    // per lane: which of its 4 columns reach the band (lo4) and which lie above it (hi4); two ballots per
+    // chunk tell the wave whether anything has to be listed (the per-column ballots are made only then)
+    uint32_t lo4 = 0;
+    hi4 = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t key = keys[q];
+        const bool valid = FULL || j + q < d;
+        const bool ge_lo = valid && key >= lo, ge_hi = valid && key >= hi;
+        kmax = max(kmax, valid ? key : 0u);
+        n_hi += ge_hi ? 1u : 0u;
+        lo4 |= (ge_lo ? 1u : 0u) << q;
+        hi4 |= (ge_hi ? 1u : 0u) << q;
+    }
+    cand4 = lo4 & ~hi4;
+    any_cand = __ballot(cand4 != 0);
+    return __ballot(lo4 != 0);
+}
+
+// RK: the keys are the priorities of a random-k draw (nothing is read from src), and instead of the
+// group bitmap the kernel writes, per column, whether its key is at or above the band (lane-major
+// half-words like the sign bits, at row `row` of kbits); k_rk_mark later adds the kept candidates.
+template <bool VEC, bool RK>
+__global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src, size_t row_stride, uint32_t d,
+                                                    uint32_t nwt, uint32_t row0, RowDesc* __restrict__ desc,
+                                                    uint32_t expect_mode, uint64_t* __restrict__ gbits,
+                                                    uint16_t* __restrict__ kbits, uint2* __restrict__ list, uint32_t cap,
+                                                    RkDraw rk) {
+    __shared__ uint2 stage[4][kStage];
+    __shared__ uint32_t wsure[4];
+    const uint32_t row = row0 + blockIdx.y;
+    if (desc[row].mode != expect_mode) return;                 // uniform for the block
+    const uint32_t lo = desc[row].lo, hi = desc[row].hi;
+    const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
+    uint2* __restrict__ out = list + (size_t)row * cap;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    uint32_t k0 = 0, k1 = 0;
+    if (RK) {
+        const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
+        k0 = (uint32_t)stream;
+        k1 = (uint32_t)(stream >> 32);
+    }
+    uint2* st = stage[wave];
+    uint32_t cnt = 0;                                           // staged candidates (wave-uniform)
+    uint32_t n_hi = 0, kmax = 0;                                // per lane: keys >= hi seen, largest key seen
+    for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
+        float4 a[4];
+        if (!RK) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
+        }
+        const bool full = (t + 1) * (uint32_t)kWaveTile <= d;  // wave-uniform
+        uint64_t word = 0;                                      // lane u (< 4) ends up holding group word u
+        uint32_t sure16 = 0;                                    // RK: bit 4u + q: my column q of chunk u has key >= hi
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
+            uint32_t keys[4];
+            if (RK) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) keys[q] = rk_priority(k0, k1, j + q);
+            } else {
+                keys[0] = key_of(a[u].x);
+                keys[1] = key_of(a[u].y);
+                keys[2] = key_of(a[u].z);
+                keys[3] = key_of(a[u].w);
+            }
+            uint64_t any_cand;
+            uint32_t cand4, hi4;
+            const uint64_t any_lo = full ? filter_chunk<true>(keys, j, d, lo, hi, cand4, any_cand, n_hi, kmax, hi4)
+                                         : filter_chunk<false>(keys, j, d, lo, hi, cand4, any_cand, n_hi, kmax, hi4);
+            word = lane == (uint32_t)u ? any_lo : word;
+            sure16 |= hi4 << (4 * u);
+            if (any_cand) {                                     // wave-uniform
+                uint64_t bc[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) bc[q] = __ballot((cand4 >> q) & 1u);
+                const uint32_t m = __popcll(bc[0]) + __popcll(bc[1]) + __popcll(bc[2]) + __popcll(bc[3]);
+                if (cnt + m > kStage) {                         // flush the staged candidates
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    uint32_t base = 0;
+                    if (lane == 0) base = atomicAdd(&desc[row].n_cand, cnt);
+                    base = __builtin_amdgcn_readfirstlane(base);
+                    for (uint32_t s = lane; s < cnt; s += 64)
+                        if (base + s < cap) out[base + s] = st[s];
+                    cnt = 0;
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                }
+                uint32_t off = cnt;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if ((bc[q] >> lane) & 1) st[off + lanes_below(bc[q])] = make_uint2(keys[q], j + q);
+                    off += __popcll(bc[q]);
+                }
+                cnt += m;
+            }
+        }
+        if (RK) {
+            kbits[((size_t)row * nwt + t) * 64 + lane] = (uint16_t)sure16;
+        } else {
+            if (gbits && lane < 4) gbits[((size_t)blockIdx.y * nwt + t) * 4 + lane] = word;
+        }
+    }
+    // keys at or above 0x7f800000 are Inf / NaN (magnitude keys only: priorities use the whole range)
+    if (!RK && __ballot(kmax >= 0x7f800000u) && lane == 0) atomicOr(&desc[row].nonfinite_acc, 1u);
+    if (cnt) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(&desc[row].n_cand, cnt);
+        base = __builtin_amdgcn_readfirstlane(base);
+        for (uint32_t s = lane; s < cnt; s += 64)
+            if (base + s < cap) out[base + s] = st[s];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) n_hi += __shfl_down(n_hi, o, 64);
+    if (lane == 0) wsure[wave] = n_hi;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t n = wsure[0] + wsure[1] + wsure[2] + wsure[3];
+        if (n) atomicAdd(&desc[row].n_sure[blockIdx.x % kSureStripes], n);
+    }
+}
+
+// First radix digit (12 bits) of every key of the rows that have no usable band.  grid = (blocks, rows).
+template <bool VEC, bool RK>
+__global__ __launch_bounds__(kBlock) void k_hist0(const float* __restrict__ src, size_t row_stride, uint32_t d,
+                                                   uint32_t nwt, uint32_t row0, const RowDesc* __restrict__ desc,
+                                                   uint32_t* __restrict__ hist, uint32_t cap, uint32_t k, RkDraw rk) {
+    __shared__ uint32_t h[kHistBins];
+    const uint32_t row = row0 + blockIdx.y;
+    if (!wants_cold(desc[row], cap, k)) return;
+    const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
+    for (int b = threadIdx.x; b < kHistBins; b += kBlock) h[b] = 0;
+    __syncthreads();
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    uint32_t k0 = 0, k1 = 0;
+    if (RK) {
+        const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
+        k0 = (uint32_t)stream;
+        k1 = (uint32_t)(stream >> 32);
+    }
+    for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
+        float4 a[4];
+        if (!RK) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
+            uint32_t keys[4];
+            if (RK) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) keys[q] = rk_priority(k0, k1, j + q);
+            } else {
+                keys[0] = key_of(a[u].x);
+                keys[1] = key_of(a[u].y);
+                keys[2] = key_of(a[u].z);
+                keys[3] = key_of(a[u].w);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (j + q < d) atomicAdd(&h[keys[q] >> 19], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t* __restrict__ out = hist + (size_t)row * kHistBins;
+    for (int b = threadIdx.x; b < kHistBins; b += kBlock) {
+        const uint32_t c = h[b];
+        if (c) atomicAdd(&out[b], c);
+    }
+}
+
+// grid = rows.  For the rows k_hist0 worked on: the band becomes the first-digit bin that holds rank k.
+__global__ __launch_bounds__(kBlock) void k_pick_band(uint32_t row0, RowDesc* __restrict__ desc,
+                                                       uint32_t* __restrict__ hist, uint32_t cap, uint32_t k) {
+    __shared__ uint32_t part[256], res[3];
+    const uint32_t row = row0 + blockIdx.x;
+    if (!wants_cold(desc[row], cap, k)) return;
+    uint32_t* __restrict__ h = hist + (size_t)row * kHistBins;
+    const Pick p = block_pick(h, kHistBins, k, part, res);
+    for (int b = threadIdx.x; b < kHistBins; b += kBlock) h[b] = 0;
+    if (threadIdx.x == 0) {
+        RowDesc r = desc[row];
+        r.lo = p.bin << 19;
+        r.hi = (p.bin + 1) << 19;            // 0x80000000 for the top bin: no key reaches it
+        r.n_cand = 0;
+        clear_sure(r);
+        r.was_cold = 1;
+        r.mode = p.count <= cap ? kColdBand : kSlow;
+        desc[row] = r;
+    }
+}
+
+// Blocks of a list kernel that take part for a list of n entries: one per 2048 entries, so that a short
+// list does not pay every block's fixed cost (histogram pick, LDS clear, flush).
+__device__ __forceinline__ uint32_t list_blocks_for(uint32_t n, uint32_t grid) {
+    const uint32_t want = (n + 2047u) / 2048u;
+    return want < 1u ? 1u : (want > grid ? grid : want);
+}
+
+// List select: the keys of a band are taken relative to its lower end; the b bits that the band's width
+// needs (b <= 26) are split into a low digit of ceil(b/2) bits and a high digit of the rest, so a narrow
+// band (the usual 2^19 keys) gets two short histograms and a wide one still fits kListBins bins each.
+struct ListDigits {
+    int low_bits;
+    uint32_t low_bins, high_bins;    // histogram sizes, at least 256 (what block_pick walks)
+};
+__device__ __forceinline__ ListDigits list_digits(const RowDesc& r) {
+    const uint32_t width = r.hi - r.lo;                     // 1 .. 2^26 for a listable row
+    const int b = width > 1 ? 32 - __clz((int)(width - 1)) : 1;
+    ListDigits g;
+    g.low_bits = (b + 1) / 2;
+    g.low_bins = max(256u, 1u << g.low_bits);
+    g.high_bins = max(256u, 1u << (b - g.low_bits));
+    return g;
+}
+
+// P = 0: histogram of the high digit of every listed key.  P = 1: each block first redoes the pick of
+// the high digit from its finished histogram, then counts the low digits of the keys in that bin.
+// grid = (blocks, rows); lhist: [row][P][kListBins].
+template <int P>
+__global__ __launch_bounds__(kBlock) void k_list_hist(uint32_t row0, RowDesc* __restrict__ desc,
+                                                       const uint2* __restrict__ list, uint32_t cap, uint32_t k,
+                                                       uint32_t* __restrict__ lhist) {
+    __shared__ uint32_t h[kListBins];
+    __shared__ uint32_t part[256], res[3];
+    const uint32_t row = row0 + blockIdx.y;
+    if (!listable(desc[row], cap, k)) return;
+    const uint32_t n = desc[row].n_cand;                       // <= cap for a listable row
+    const uint32_t nb = list_blocks_for(n, gridDim.x);
+    if (blockIdx.x >= nb) return;
+    uint32_t* __restrict__ hrow = lhist + (size_t)row * 2 * kListBins;
+    const uint32_t lo = desc[row].lo;
+    const ListDigits dg = list_digits(desc[row]);
+    const int nbins = (int)(P == 0 ? dg.high_bins : dg.low_bins);
+    uint32_t bin0 = 0;
+    if constexpr (P == 1) {
+        const Pick p = block_pick(hrow, (int)dg.high_bins, k - sure_count(desc[row]), part, res);
+        bin0 = p.bin;
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            desc[row].sel_bin = p.bin;
+            desc[row].sel_rank = p.rank_in;
+        }
+    }
+    for (int b = threadIdx.x; b < nbins; b += kBlock) h[b] = 0;
+    __syncthreads();
+    const uint2* __restrict__ in = list + (size_t)row * cap;
+    const uint32_t low_mask = (1u << dg.low_bits) - 1u;
+    for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < n; e += nb * kBlock) {
+        const uint32_t rel = in[e].x - lo;
+        if (P == 0) atomicAdd(&h[rel >> dg.low_bits], 1u);
+        else if ((rel >> dg.low_bits) == bin0) atomicAdd(&h[rel & low_mask], 1u);
+    }
+    __syncthreads();
+    uint32_t* __restrict__ out = hrow + P * kListBins;
+    for (int b = threadIdx.x; b < nbins; b += kBlock) {
+        const uint32_t c = h[b];
+        if (c) atomicAdd(&out[b], c);
+    }
+}
+
+// Picks the low digit (-> tau, how many of its ties are kept, how many there are) and collects the
+// indices of the listed entries whose key equals tau.  grid = (blocks, rows).
+__global__ __launch_bounds__(kBlock) void k_list_ties(uint32_t row0, RowDesc* __restrict__ desc,
+                                                       const uint2* __restrict__ list, uint32_t cap, uint32_t k,
+                                                       const uint32_t* __restrict__ lhist,
+                                                       uint32_t* __restrict__ tiebuf) {
+    __shared__ uint32_t part[256], res[3];
+    const uint32_t row = row0 + blockIdx.y;
+    if (!listable(desc[row], cap, k)) return;
+    const uint32_t n = desc[row].n_cand;
+    const uint32_t nb = list_blocks_for(n, gridDim.x);
+    if (blockIdx.x >= nb) return;
+    const uint32_t* __restrict__ hrow = lhist + (size_t)row * 2 * kListBins;
+    const ListDigits dg = list_digits(desc[row]);
+    const Pick p = block_pick(hrow + kListBins, (int)dg.low_bins, desc[row].sel_rank, part, res);
+    const uint32_t tau = desc[row].lo + ((desc[row].sel_bin << dg.low_bits) | p.bin);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        desc[row].tau = tau;
+        desc[row].rank = p.rank_in;
+        desc[row].ties = p.count;
+    }
+    const uint2* __restrict__ in = list + (size_t)row * cap;
+    uint32_t* __restrict__ tb = tiebuf + (size_t)row * kTieCap;
+    for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < n; e += nb * kBlock) {
+        const uint2 kv = in[e];
+        if (kv.x == tau) {
+            const uint32_t pos = atomicAdd(&desc[row].n_ties, 1u);
+            if (pos < kTieCap) tb[pos] = kv.y;
+        }
+    }
+}
+
+// Band for the next step: centred on tau extrapolated by its last change, at least kBandMargin wide
+// on either side, wider when tau is moving or when the last prediction failed.
+__device__ __forceinline__ void predict_band(RowDesc& r, uint32_t fix_lo, uint32_t fix_hi) {
+    if (fix_hi) {                                   // random-k: the band does not depend on the data
+        r.lo = fix_lo;
+        r.hi = fix_hi;
+        r.prev_tau = r.tau;
+        r.have_prev = 1;
+        r.was_cold = 0;
+        return;
+    }
+    const int64_t tau = (int64_t)r.tau;
+    const int64_t delta = r.have_prev ? tau - (int64_t)r.prev_tau : 0;
+    int64_t margin = 2 * (delta < 0 ? -delta : delta);
+    if (margin < (int64_t)kBandMargin) margin = kBandMargin;
+    if (r.was_cold && margin < 4 * (int64_t)kBandMargin) margin = 4 * (int64_t)kBandMargin;
+    if (margin > (int64_t)1 << 25) margin = (int64_t)1 << 25;   // two list digits cover a band of 2^26 keys
+    int64_t centre = tau + delta;
+    if (centre < 0) centre = 0;
+    if (centre > 0x7fffffffll) centre = 0x7fffffffll;
+    const int64_t lo = centre - margin, hi = centre + margin;
+    r.lo = lo < 0 ? 0u : (uint32_t)lo;
+    r.hi = hi > 0x80000000ll ? 0x80000000u : (uint32_t)hi;
+    r.prev_tau = r.tau;
+    r.have_prev = 1;
+    r.was_cold = 0;
+}
+
+// grid = rows.  Orders the collected ties by index, sets the cut-off, clears the list state and
+// predicts the next step's band.  Rows whose band failed twice, or with more ties than the buffer
+// holds, go to the slow search.
+__global__ __launch_bounds__(kBlock) void k_list_finish(uint32_t row0, RowDesc* __restrict__ desc,
+                                                         uint32_t* __restrict__ lhist,
+                                                         const uint32_t* __restrict__ tiebuf, uint32_t cap, uint32_t k,
+                                                         uint32_t fix_lo, uint32_t fix_hi) {
+    __shared__ uint32_t t_idx[kTieCap];
+    __shared__ uint32_t s_cut;
+    const uint32_t row = row0 + blockIdx.x;
+    if (desc[row].mode == kSlow) return;
+    if (!listable(desc[row], cap, k)) {                        // uniform for the block
+        if (threadIdx.x == 0) {
+            RowDesc r = desc[row];
+            r.n_cand = 0;
+            clear_sure(r);
+            r.n_ties = 0;
+            r.n_list = 0;
+            r.mode = kSlow;
+            desc[row] = r;
+        }
+        return;
+    }
+    uint32_t* __restrict__ hrow = lhist + (size_t)row * 2 * kListBins;
+    for (int b = threadIdx.x; b < 2 * kListBins; b += kBlock) hrow[b] = 0;
+    const uint32_t ties = desc[row].ties, want = desc[row].rank;
+    const bool fits = ties <= (uint32_t)kTieCap;
+    if (fits) {
+        const uint32_t* __restrict__ tb = tiebuf + (size_t)row * kTieCap;
+        for (uint32_t q = threadIdx.x; q < ties; q += kBlock) t_idx[q] = tb[q];
+        if (threadIdx.x == 0) s_cut = 0xffffffffu;
+        __syncthreads();
+        for (uint32_t q = threadIdx.x; q < ties; q += kBlock) {
+            const uint32_t mine = t_idx[q];
+            uint32_t below = 0;
+            for (uint32_t r = 0; r < ties; ++r) below += t_idx[r] < mine;
+            if (below + 1 == want) s_cut = mine;            // indices are distinct: one writer
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        RowDesc r = desc[row];
+        r.n_list = r.n_cand;
+        r.n_cand = 0;
+        clear_sure(r);
+        r.n_ties = 0;
+        if (fits) {
+            r.cutoff = s_cut;
+            r.dense = 0;
+            r.nonfinite = r.nonfinite_acc;
+            r.nonfinite_acc = 0;
+            predict_band(r, fix_lo, fix_hi);
+            r.mode = kWarm;
+        } else {
+            r.mode = kSlow;
+        }
+        desc[row] = r;
+    }
+}
+
+// General search for rows in kSlow mode, one block of 1024 threads per row: three radix digits
+// over the whole row, then the ties in index order.  Slow by design; only degenerate rows (a
+// threshold shared by thousands of entries) come here.  grid = rows.
+template <bool VEC, bool RK>
+__global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ src, size_t row_stride, uint32_t d,
+                                                       uint32_t row0, RowDesc* __restrict__ desc, uint32_t k,
+                                                       RkDraw rk) {
+    __shared__ uint32_t h[kHistBins];
+    __shared__ uint32_t part[256], res[3];
+    __shared__ uint32_t wtot[16];
+    __shared__ uint32_t s_cut, s_bad;
+    const uint32_t row = row0 + blockIdx.x;
+    if (desc[row].mode != kSlow) return;
+    const float* __restrict__ g = src + (size_t)blockIdx.x * row_stride;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t k0 = 0, k1 = 0;
+    if (RK) {
+        const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
+        k0 = (uint32_t)stream;
+        k1 = (uint32_t)(stream >> 32);
+    }
+    // the 4 keys of columns j .. j + 3 (columns at or beyond d give unspecified keys; callers test j + q < d)
+    auto keys_at = [&](uint32_t j, uint32_t (&key)[4]) {
+        if (RK) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) key[q] = rk_priority(k0, k1, j + q);
+        } else {
+            const float4 a = ld4<VEC>(g, j, d);
+            key[0] = key_of(a.x);
+            key[1] = key_of(a.y);
+            key[2] = key_of(a.z);
+            key[3] = key_of(a.w);
+        }
+    };
+    uint32_t prefix = 0, rank = k, ties = 0;
+    if (tid == 0) s_bad = 0;
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = digit_shift(pass), nbins = 1 << digit_bits(pass);
+        const int hi_shift = pass == 0 ? 31 : digit_shift(pass - 1);
+        for (int b = tid; b < nbins; b += 1024) h[b] = 0;
+        __syncthreads();
+        for (uint32_t j = tid * 4; j < d; j += 4096) {
+            uint32_t key[4];
+            keys_at(j, key);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (j + q < d && ((key[q] ^ prefix) >> hi_shift) == 0) atomicAdd(&h[(key[q] >> shift) & (nbins - 1)], 1u);
+        }
+        __syncthreads();
+        if (pass == 0 && !RK) {                       // keys >= 0x7f800000 (Inf/NaN) sit in the bins from 0xff0 up
+            bool bad = false;
+            for (int b = 0xff0 + (int)tid; b < kHistBins; b += 1024) bad |= h[b] != 0;
+            if (bad) s_bad = 1;
+        }
+        const Pick p = block_pick(h, nbins, rank, part, res);
+        prefix |= p.bin << shift;
+        rank = p.rank_in;
+        ties = p.count;
+    }
+    // the rank-th entry with key == prefix, in index order
+    if (tid == 0) s_cut = 0xffffffffu;
+    __syncthreads();
+    uint32_t seen = 0;
+    for (uint32_t base = 0; base < d; base += 4096) {          // uniform trip count and exit
+        const uint32_t j = base + tid * 4;
+        uint32_t key[4];
+        keys_at(j, key);
+        const bool m0 = j < d && key[0] == prefix, m1 = j + 1 < d && key[1] == prefix;
+        const bool m2 = j + 2 < d && key[2] == prefix, m3 = j + 3 < d && key[3] == prefix;
+        const uint32_t mine = m0 + m1 + m2 + m3;
+        uint32_t incl = mine;                                   // inclusive scan inside the wave
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t up = __shfl_up(incl, o, 64);
+            if ((int)lane >= o) incl += up;
+        }
+        if (lane == 63) wtot[wave] = incl;
+        __syncthreads();
+        uint32_t before = seen, total = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < (int)wave) before += wtot[w];
+            total += wtot[w];
+        }
+        before += incl - mine;
+        if (before < rank && rank <= before + mine) {
+            uint32_t need = rank - before, idx = j + 3;
+            if (m0 && --need == 0) idx = j;
+            else if (m1 && --need == 0) idx = j + 1;
+            else if (m2 && --need == 0) idx = j + 2;
+            s_cut = idx;
+        }
+        seen += total;
+        __syncthreads();
+        if (seen >= rank) break;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        RowDesc r = desc[row];
+        r.tau = prefix;
+        r.rank = rank;
+        r.ties = ties;
+        r.cutoff = s_cut;
+        r.dense = 1;
+        r.nonfinite = s_bad | r.nonfinite_acc;
+        r.nonfinite_acc = 0;
+        r.n_cand = 0;
+        clear_sure(r);
+        r.n_ties = 0;
+        r.n_list = 0;
+        r.have_prev = 0;
+        r.was_cold = 0;
+        r.mode = kCold;
+        if (RK) {                              // the band of a random-k draw is known without a prediction
+            r.lo = rk.fix_lo;
+            r.hi = rk.fix_hi;
+            r.mode = kWarm;
+        }
+        desc[row] = r;
+    }
+}
+
+// Random-k: completes the kept bitmap of each row once (tau, cut-off) are known.  k_filter has set the
+// bits of the columns whose key is above the band; here the listed candidates that are kept get
+// theirs (atomic OR on the 32-bit word holding the lane's half-word).  Rows that went through the
+// slow search have no valid list: every block recomputes the priorities of its tiles and writes
+// whole half-words.  grid = (blocks, rows).
+__global__ __launch_bounds__(kBlock) void k_rk_mark(uint32_t d, uint32_t nwt, uint32_t row0, const RowDesc* __restrict__ desc,
+                                                     const uint2* __restrict__ list, uint32_t cap,
+                                                     uint16_t* __restrict__ kbits, RkDraw rk) {
+    const uint32_t row = row0 + blockIdx.y;
+    const uint32_t tau = desc[row].tau, cut = desc[row].cutoff;
+    if (!desc[row].dense) {
+        const uint32_t n = desc[row].n_list;
+        const uint2* __restrict__ in = list + (size_t)row * cap;
+        uint32_t* __restrict__ words = reinterpret_cast<uint32_t*>(kbits + (size_t)row * nwt * 64);
+        for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < n; e += gridDim.x * kBlock) {
+            const uint2 kv = in[e];
+            if (kv.x > tau || (kv.x == tau && kv.y <= cut)) {
+                const uint32_t t = kv.y / kWaveTile, o = kv.y % kWaveTile;
+                const uint32_t u = o / kChunk, l = (o % kChunk) / 4, q = o % 4;
+                const uint32_t half = t * 64 + l;                     // half-word of the row holding the column
+                atomicOr(&words[half >> 1], 1u << ((half & 1) * 16 + 4 * u + q));
+            }
+        }
+        return;
+    }
+    const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
+    const uint32_t k0 = (uint32_t)stream, k1 = (uint32_t)(stream >> 32);
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
+        uint32_t m = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t j = t * kWaveTile + u * kChunk + lane * 4 + q;
+                const uint32_t key = rk_priority(k0, k1, j);
+                m |= ((j < d && (key > tau || (key == tau && j <= cut))) ? 1u : 0u) << (4 * u + q);
+            }
+        kbits[((size_t)row * nwt + t) * 64 + lane] = (uint16_t)m;
+    }
+}
+
+// One thread, after the last kernel of a step that used the draw.
+__global__ void k_rk_advance(RkState* __restrict__ state) { state->draw += 1; }
+
+}  // namespace liec
