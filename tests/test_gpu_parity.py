@@ -268,6 +268,17 @@ def test_step_rejects_bad_buffers_and_reports_nonfinite_input():
         assert ctx.info_status()[1] == 4
 
 
+def test_out_of_memory_is_reported_and_leaves_the_library_usable():
+    _say("case out of memory")
+    from paper_2402_11857_amd import LiecContext, LiecError
+
+    with pytest.raises(LiecError) as err:          # the candidate lists alone would take about 1 TB
+        LiecContext(1000, 2_000_000_000, "topk", "topk", 1000, 1000, 0.1)
+    assert err.value.status == 2
+    w = workloads.scaled(WL["c1_tiny_sign"], N=2, d=5000)
+    assert _run_chain(w, steps=2, seed=1)
+
+
 def test_per_kernel_timing_and_scratch_accounting():
     _say("case profile api")
     w = workloads.scaled(WL["c2_topk_mid"], N=4, d=200_000, worker_comp="topk", server_comp="sign", worker_k=2000)
