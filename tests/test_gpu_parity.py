@@ -268,6 +268,33 @@ def test_step_rejects_bad_buffers_and_reports_nonfinite_input():
         assert ctx.info_status()[1] == 4
 
 
+def test_two_contexts_on_two_streams_do_not_interfere():
+    """The library keeps no global state: two contexts with different operators, sizes and streams,
+    stepping in turns without synchronising in between, give what each gives alone."""
+    _say("case two contexts")
+    wa = workloads.scaled(WL["c2_topk_mid"], N=4, d=150_000, worker_comp="topk", server_comp="sign", worker_k=1500)
+    wb = workloads.scaled(WL["c2_topk_mid"], N=3, d=90_001, worker_comp="randk", server_comp="topk", worker_k=900, server_k=2000)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    srcs = [workloads.GradientSource(w, seed=5 + q, device=DEV) for q, w in enumerate((wa, wb))]
+    gs = [[src.grads(t) for t in range(4)] for src in srcs]
+    xs = [torch.zeros((w.N, w.d), dtype=torch.float32, device=DEV) for w in (wa, wb)]
+    es = [torch.zeros(w.d, dtype=torch.float32, device=DEV) for w in (wa, wb)]
+    torch.cuda.synchronize()
+    with _ctx(wa, stream=sa) as ca, _ctx(wb, stream=sb) as cb:
+        cb.set_random(3, 0)
+        for t in range(4):
+            ca.step(gs[0][t], xs[0], es[0])
+            cb.step(gs[1][t], xs[1], es[1])
+        sa.synchronize()
+        sb.synchronize()
+    for q, w in enumerate((wa, wb)):
+        xo, eo = np.zeros((w.N, w.d), dtype=np.float32), np.zeros(w.d, dtype=np.float32)
+        for t in range(4):
+            H.oracle_step_rows(gs[q][t].cpu().numpy(), xo, eo, w.worker_comp, w.server_comp, w.lr, w.worker_k, w.server_k,
+                               rng=(3, t))
+        assert H.bit_equal(xs[q].cpu().numpy(), xo) and H.bit_equal(es[q].cpu().numpy(), eo), f"context {q}"
+
+
 def test_out_of_memory_is_reported_and_leaves_the_library_usable():
     _say("case out of memory")
     from paper_2402_11857_amd import LiecContext, LiecError
