@@ -133,6 +133,19 @@ __host__ __device__ __forceinline__ uint32_t rk_priority(uint32_t k0, uint32_t k
     return h >> 1;
 }
 
+// The index whose 32-bit word (priority with its dropped bit put back) is y: every step of rk_priority
+// undone in reverse order (the multipliers' inverses modulo 2^32; x ^= x >> 13 is undone by two
+// shifts, x ^= x >> 16 by itself).
+__host__ __device__ __forceinline__ uint32_t rk_index_of(uint32_t k0, uint32_t k1, uint32_t y) {
+    uint32_t h = y ^ (y >> 16);
+    h *= 0x7ED1B41Du;                  // 0xC2B2AE35^-1
+    h -= k1;
+    h = h ^ (h >> 13) ^ (h >> 26);
+    h *= 0xA5CB9243u;                  // 0x85EBCA6B^-1
+    h ^= h >> 16;
+    return h ^ k0;
+}
+
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 // 4 consecutive floats starting at column j of a row of length d; zero beyond d.

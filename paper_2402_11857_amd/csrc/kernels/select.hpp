@@ -155,6 +155,85 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
     }
 }
 
+// Random-k when the band is thin against the row (k * 2^32 / d well below d): instead of computing the
+// priority of every column, walk the 32-bit words y whose priority y >> 1 is at or above the band's
+// lower end and invert the permutation; words that land on a column below d are the row's keys >= lo.
+// The work is O(k * 2^32 / d) per row instead of O(d).  Same outputs as k_filter<., true>: the count of
+// keys above the band, the candidate list, and the bits of the columns above the band -- set with
+// atomic ORs into a bitmap that k_rk_zero cleared.  grid = (blocks, rows).
+__global__ __launch_bounds__(kBlock) void k_rk_zero(uint32_t nwt, uint32_t row0, const RowDesc* __restrict__ desc,
+                                                     uint32_t expect_mode, uint16_t* __restrict__ kbits) {
+    const uint32_t row = row0 + blockIdx.y;
+    if (desc[row].mode != expect_mode) return;
+    uint32_t* __restrict__ words = reinterpret_cast<uint32_t*>(kbits + (size_t)row * nwt * 64);
+    const uint32_t n = nwt * 32;
+    for (uint32_t q = blockIdx.x * kBlock + threadIdx.x; q < n; q += gridDim.x * kBlock) words[q] = 0u;
+}
+
+__global__ __launch_bounds__(kBlock) void k_rk_filter_inverse(uint32_t d, uint32_t nwt, uint32_t row0,
+                                                               RowDesc* __restrict__ desc, uint32_t expect_mode,
+                                                               uint16_t* __restrict__ kbits, uint2* __restrict__ list,
+                                                               uint32_t cap, RkDraw rk) {
+    __shared__ uint2 stage[4][kStage];
+    __shared__ uint32_t wsure[4];
+    const uint32_t row = row0 + blockIdx.y;
+    if (desc[row].mode != expect_mode) return;                 // uniform for the block
+    const uint32_t lo = desc[row].lo, hi = desc[row].hi;
+    uint2* __restrict__ out = list + (size_t)row * cap;
+    uint32_t* __restrict__ words = reinterpret_cast<uint32_t*>(kbits + (size_t)row * nwt * 64);
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
+    const uint32_t k0 = (uint32_t)stream, k1 = (uint32_t)(stream >> 32);
+    const uint64_t y_begin = 2ull * lo, y_end = 1ull << 32;    // words whose priority is at least lo
+    uint2* st = stage[wave];
+    uint32_t cnt = 0, n_hi = 0;
+    for (uint64_t base = y_begin + ((uint64_t)blockIdx.x * 4 + wave) * 64; base < y_end; base += (uint64_t)gridDim.x * kBlock) {
+        const uint64_t y64 = base + lane;
+        const uint32_t y = (uint32_t)y64, key = y >> 1;
+        const uint32_t j = rk_index_of(k0, k1, y);
+        const bool ok = y64 < y_end && j < d;
+        const bool ge_hi = ok && key >= hi;
+        if (ge_hi) {
+            const uint32_t t = j / kWaveTile, o = j % kWaveTile;
+            const uint32_t half = t * 64 + (o % kChunk) / 4;              // half-word of the row holding the column
+            atomicOr(&words[half >> 1], 1u << ((half & 1) * 16 + 4 * (o / kChunk) + o % 4));
+            ++n_hi;
+        }
+        const uint64_t bc = __ballot(ok && !ge_hi);             // candidates: lo <= key < hi
+        if (bc) {                                               // wave-uniform
+            const uint32_t m = __popcll(bc);
+            if (cnt + m > kStage) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                uint32_t at = 0;
+                if (lane == 0) at = atomicAdd(&desc[row].n_cand, cnt);
+                at = __builtin_amdgcn_readfirstlane(at);
+                for (uint32_t s = lane; s < cnt; s += 64)
+                    if (at + s < cap) out[at + s] = st[s];
+                cnt = 0;
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+            if ((bc >> lane) & 1) st[cnt + lanes_below(bc)] = make_uint2(key, j);
+            cnt += m;
+        }
+    }
+    if (cnt) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        uint32_t at = 0;
+        if (lane == 0) at = atomicAdd(&desc[row].n_cand, cnt);
+        at = __builtin_amdgcn_readfirstlane(at);
+        for (uint32_t s = lane; s < cnt; s += 64)
+            if (at + s < cap) out[at + s] = st[s];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) n_hi += __shfl_down(n_hi, o, 64);
+    if (lane == 0) wsure[wave] = n_hi;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t n = wsure[0] + wsure[1] + wsure[2] + wsure[3];
+        if (n) atomicAdd(&desc[row].n_sure[blockIdx.x % kSureStripes], n);
+    }
+}
+
 // First radix digit (12 bits) of every key of the rows that have no usable band.  grid = (blocks, rows).
 template <bool VEC, bool RK>
 __global__ __launch_bounds__(kBlock) void k_hist0(const float* __restrict__ src, size_t row_stride, uint32_t d,

@@ -84,6 +84,7 @@ struct liec_ctx {
     uint16_t* bits = nullptr;                  // [(N or N + 1) * nwt * 64] sign bits (sign operators) / kept bits (random-k; row N: server)
     RkState* rk_state = nullptr;               // random-k: seed and number of the next draw (device)
     uint32_t rk_wlo = 0, rk_whi = 0, rk_slo = 0, rk_shi = 0;   // random-k: threshold bands of the worker / server draws
+    bool rk_winv = false, rk_sinv = false;     // random-k: the band is thin enough to walk the priorities instead of the columns
     uint64_t* gbits = nullptr;                 // [N * nwt * 4] group bitmap of the candidates (top-k workers)
     uint2* list = nullptr;                     // [(N + 1) * cap] candidates (key, index)
     uint32_t* ghist = nullptr;                 // [(N + 1) * kHistBins]
@@ -210,14 +211,23 @@ struct Launcher {
 // `src`, followed by the kernel that completes the kept bitmap.
 template <bool VEC, bool RK>
 void launch_select(Launcher& L, const float* src, size_t row_stride, uint32_t rows, uint32_t row0, uint32_t k,
-                   uint64_t* gbits, uint32_t blocks, uint32_t cold_blocks, int slot0, RkDraw rk) {
+                   uint64_t* gbits, uint32_t blocks, uint32_t cold_blocks, int slot0, RkDraw rk, bool rk_inverse = false) {
     liec_ctx* c = L.c;
     const uint32_t d = (uint32_t)c->d;
     hipStream_t st = c->stream;
     const dim3 grid(blocks, rows), cold_grid(cold_blocks, rows), list_grid(c->list_blocks, rows);
+    // random-k with a thin band: clear the kept bitmap, then walk the priorities above the band
+    // few, long-lived blocks (every wave ends with a list flush): one per 32768 words to invert
+    const uint64_t inv_words = 2ull * (0x80000000ull - rk.fix_lo);
+    const dim3 inv_grid((uint32_t)std::min<uint64_t>(std::max<uint64_t>(inv_words / 32768, 128), 1024), rows), zero_grid(std::min<uint32_t>((c->nwt * 32 + kBlock - 1) / kBlock, 4096u), rows);
     L.begin(slot0 + 0);
-    k_filter<VEC, RK><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kWarm, gbits, c->bits, c->list,
-                                                c->cap, rk);
+    if (RK && rk_inverse) {
+        k_rk_zero<<<zero_grid, kBlock, 0, st>>>(c->nwt, row0, c->desc, kWarm, c->bits);
+        k_rk_filter_inverse<<<inv_grid, kBlock, 0, st>>>(d, c->nwt, row0, c->desc, kWarm, c->bits, c->list, c->cap, rk);
+    } else {
+        k_filter<VEC, RK><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kWarm, gbits, c->bits, c->list,
+                                                    c->cap, rk);
+    }
     L.end();
     L.begin(slot0 + 1);
     k_hist0<VEC, RK><<<cold_grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, c->ghist, c->cap, k, rk);
@@ -226,8 +236,13 @@ void launch_select(Launcher& L, const float* src, size_t row_stride, uint32_t ro
     k_pick_band<<<rows, kBlock, 0, st>>>(row0, c->desc, c->ghist, c->cap, k);
     L.end();
     L.begin(slot0 + 3);
-    k_filter<VEC, RK><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kColdBand, gbits, c->bits,
-                                                c->list, c->cap, rk);
+    if (RK && rk_inverse) {
+        k_rk_zero<<<zero_grid, kBlock, 0, st>>>(c->nwt, row0, c->desc, kColdBand, c->bits);
+        k_rk_filter_inverse<<<inv_grid, kBlock, 0, st>>>(d, c->nwt, row0, c->desc, kColdBand, c->bits, c->list, c->cap, rk);
+    } else {
+        k_filter<VEC, RK><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kColdBand, gbits, c->bits,
+                                                    c->list, c->cap, rk);
+    }
     L.end();
     L.begin(slot0 + 4);
     k_list_hist<0><<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, k, c->lhist);
@@ -331,7 +346,7 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
     } else if (c->worker_comp == kRandk) {
         launch_select<VEC, true>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, nullptr,
                                  c->filter_row_blocks, c->cold_row_blocks, S_W_SEL,
-                                 RkDraw{c->rk_state, c->rk_wlo, c->rk_whi});
+                                 RkDraw{c->rk_state, c->rk_wlo, c->rk_whi}, c->rk_winv);
     }
 
     // ---- server: v = e + mean_i p^i, then the descriptor of C_s(v) ---------------------------------
@@ -356,7 +371,7 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
     } else if (c->server_comp == kRandk) {
         launch_select<VEC, true>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, nullptr,
                                  c->filter_srv_blocks, c->cold_srv_blocks, S_S_SEL,
-                                 RkDraw{c->rk_state, c->rk_slo, c->rk_shi});
+                                 RkDraw{c->rk_state, c->rk_slo, c->rk_shi}, c->rk_sinv);
     }
 
     // ---- p = C_s(v), e <- v - p, x^i <- x^i - lr (p + (g_i - p^i)) ---------------------------------
@@ -425,6 +440,10 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     c->server_k = selects_k((int)server_comp) ? server_k : 0;
     if (worker_comp == LIEC_COMP_RANDK) randk_band(d, worker_k, &c->rk_wlo, &c->rk_whi);
     if (server_comp == LIEC_COMP_RANDK) randk_band(d, server_k, &c->rk_slo, &c->rk_shi);
+    // 2 * (2^31 - lo) words carry a priority at or above the band: inverting them beats hashing d columns
+    // when they are well under d (each inverted word also costs an atomic when it lands on a column)
+    c->rk_winv = worker_comp == LIEC_COMP_RANDK && 2.0 * (2147483648.0 - (double)c->rk_wlo) < 0.5 * (double)d;
+    c->rk_sinv = server_comp == LIEC_COMP_RANDK && 2.0 * (2147483648.0 - (double)c->rk_slo) < 0.5 * (double)d;
     c->lr = lr;
     c->stream = (hipStream_t)hip_stream;
     if (hipGetDevice(&c->device) != hipSuccess) {

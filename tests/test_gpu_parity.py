@@ -352,6 +352,16 @@ def test_random_k_extreme_k(d, k):
     assert _run_chain(w, steps=3, seed=3, rk_seed=1)
 
 
+@pytest.mark.parametrize("modes", [None, [1, 0, 4]])
+def test_random_k_with_a_thin_band_walks_the_priorities(modes):
+    """k * 2^32 / d far below d: the library inverts the priority permutation over the words above the
+    band instead of hashing every column; same kept sets, in every search mode."""
+    _say(f"case randk thin band modes={modes}")
+    w = workloads.scaled(WL["c2_topk_mid"], N=3, d=4_000_003, worker_comp="randk", server_comp="randk",
+                         worker_k=400, server_k=1000)
+    assert _run_chain(w, steps=3, seed=12, rk_seed=99, force_mode=modes)
+
+
 @pytest.mark.parametrize("modes", [[1, 0, 1], [4, 0, 4], [0, 4, 1]])
 @pytest.mark.parametrize("wc,sc", [("randk", "randk"), ("topk", "topk")])
 def test_every_search_mode_gives_the_same_result(wc, sc, modes):
