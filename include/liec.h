@@ -120,6 +120,17 @@ liec_status liec_step(liec_ctx *ctx, const float *grads, float *x, float *server
 liec_status liec_step_sync(liec_ctx *ctx, const float *grads, float *x, float *server_err);
 
 /*
+ * liec_iteration: iteration t (0-based) of Algorithm 1 as a whole: the averaging
+ * iteration (liec_step_sync) when period >= 2 and (t + 1) is a multiple of
+ * period, the compressed iteration (liec_step) otherwise; period = 0 means no
+ * averaging iterations.  The paper sets the period to floor(1 / delta) and uses
+ * 32 and 100 in its experiments.  LIEC_EINVAL for t < 0, period < 0 or period = 1;
+ * otherwise as the call it forwards to.
+ */
+liec_status liec_iteration(liec_ctx *ctx, int64_t t, int64_t period, const float *grads, float *x,
+                           float *server_err);
+
+/*
  * liec_set_blocks: the block table of Blockwise-SignSGD (Definition 5), needed
  * before the first liec_step of a context that uses LIEC_COMP_BLOCKSIGN on
  * either side (liec_step returns LIEC_EINVAL without it).

@@ -68,6 +68,8 @@ def lib():
         L.liec_step.argtypes = [vp, vp, vp, vp]
         L.liec_step_sync.restype = ctypes.c_int
         L.liec_step_sync.argtypes = [vp, vp, vp, vp]
+        L.liec_iteration.restype = ctypes.c_int
+        L.liec_iteration.argtypes = [vp, i64, i64, vp, vp, vp]
         L.liec_set_blocks.restype = ctypes.c_int
         L.liec_set_blocks.argtypes = [vp, ctypes.POINTER(i64), i32]
         L.liec_get_block_scales.restype = ctypes.c_int
@@ -246,6 +248,12 @@ class LiecContext:
     def step_sync(self, grads: torch.Tensor, x: torch.Tensor, server_err: torch.Tensor) -> None:
         liec_step_sync(self._h, _dev_ptr(grads, (self.N, self.d), "grads"), _dev_ptr(x, (self.N, self.d), "x"),
                        _dev_ptr(server_err, (self.d,), "server_err"))
+
+    def iteration(self, t: int, period: int, grads: torch.Tensor, x: torch.Tensor, server_err: torch.Tensor) -> None:
+        """Iteration t of Algorithm 1: averaging iteration when (t + 1) % period == 0, compressed otherwise."""
+        _check(lib().liec_iteration(self._h, t, period, _dev_ptr(grads, (self.N, self.d), "grads"),
+                                    _dev_ptr(x, (self.N, self.d), "x"), _dev_ptr(server_err, (self.d,), "server_err")),
+               "liec_iteration")
 
     def set_blocks(self, offsets) -> None:
         self._nblocks = len(list(offsets)) - 1

@@ -628,6 +628,12 @@ liec_status liec_step_sync(liec_ctx* c, const float* grads, float* x, float* ser
     return LIEC_OK;
 }
 
+liec_status liec_iteration(liec_ctx* c, int64_t t, int64_t period, const float* grads, float* x, float* server_err) {
+    if (t < 0 || period < 0 || period == 1) return LIEC_EINVAL;
+    if (period >= 2 && (t + 1) % period == 0) return liec_step_sync(c, grads, x, server_err);
+    return liec_step(c, grads, x, server_err);
+}
+
 liec_status liec_set_blocks(liec_ctx* c, const int64_t* offsets, int32_t nblocks) {
     if (!c || !offsets || nblocks < 1 || nblocks > 65536) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;

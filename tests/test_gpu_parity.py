@@ -873,11 +873,10 @@ def test_mixed_chain_with_averaging_period(wc, sc):
         for t in range(13):
             g = src.grads(t)
             gh = g.cpu().numpy()
+            ctx.iteration(t, 4, g, x, e)               # Algorithm 1 as a whole: the library picks the branch
             if (t + 1) % 4 == 0:
-                ctx.step_sync(g, x, e)
                 oracle.step_sync(gh, xo, eo, w.lr)
             else:
-                ctx.step(g, x, e)
                 H.oracle_step_rows(gh, xo, eo, wc, sc, w.lr, w.worker_k, w.server_k)
             assert H.bit_equal(x.cpu().numpy(), xo) and H.bit_equal(e.cpu().numpy(), eo), f"step {t}"
 
