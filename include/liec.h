@@ -80,7 +80,11 @@ typedef struct {
  *   1 <= d < 2^31 - 2^20   model dimension (columns); also N * (d / 1024 + 4097) < 2^31
  *   k           kept entries for LIEC_COMP_TOPK / LIEC_COMP_RANDK, 1 <= k <= d; ignored otherwise
  *   lr          learning rate eta, finite
- * Allocates O(N * d / 8 + d) bytes of device scratch.  Uses the current HIP device.
+ * Allocates the context's device scratch: 4d bytes for v; N * d / 8 for sign or
+ * random-k bitmaps; with top-k or random-k on either side also (N + 1) * (d / 2 +
+ * 32 KiB) for the candidate lists, N * d / 32 for the group bitmap and about
+ * 100 KiB per row of histograms (liec_scratch_bytes reports the total).  Uses the
+ * current HIP device.
  */
 liec_status liec_create(liec_ctx **out, int32_t N, int64_t d, liec_comp compressor, int64_t k,
                         float lr);
