@@ -83,8 +83,9 @@ typedef struct {
  * Allocates the context's device scratch: 4d bytes for v; N * d / 8 for sign or
  * random-k bitmaps; with top-k or random-k on either side also (N + 1) * (d / 2 +
  * 32 KiB) for the candidate lists, N * d / 32 for the group bitmap and about
- * 100 KiB per row of histograms (liec_scratch_bytes reports the total).  Uses the
- * current HIP device.
+ * 100 KiB per row of histograms (liec_scratch_bytes reports the total).  The
+ * context belongs to the HIP device that is current at this call: every later call
+ * on it makes that device current for its own duration and puts the caller's back.
  */
 liec_status liec_create(liec_ctx **out, int32_t N, int64_t d, liec_comp compressor, int64_t k,
                         float lr);
@@ -92,7 +93,7 @@ liec_status liec_create(liec_ctx **out, int32_t N, int64_t d, liec_comp compress
 /*
  * liec_create_ex: different operators / k on the two sides, and the HIP stream
  * (a hipStream_t passed as void*, NULL = null stream) all work is enqueued on.
- * The stream must outlive the context.
+ * The stream must belong to the device current at this call and outlive the context.
  */
 liec_status liec_create_ex(liec_ctx **out, int32_t N, int64_t d, liec_comp worker_comp,
                            int64_t worker_k, liec_comp server_comp, int64_t server_k, float lr,

@@ -117,6 +117,26 @@ namespace {
 
 bool finite_f(float v) { return std::isfinite(v); }
 
+// Makes the context's device current for the length of an entry point (a caller that drives several
+// devices may have switched since liec_create) and puts the caller's back on the way out.
+struct DeviceScope {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceScope(const liec_ctx* c) {
+        int cur = 0;
+        ok = hipGetDevice(&cur) == hipSuccess;
+        if (ok && cur != c->device) {
+            ok = hipSetDevice(c->device) == hipSuccess;
+            if (ok) prev = cur;
+        }
+    }
+    ~DeviceScope() {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+    DeviceScope(const DeviceScope&) = delete;
+    DeviceScope& operator=(const DeviceScope&) = delete;
+};
+
 template <typename T>
 hipError_t dev_alloc(liec_ctx* c, T** p, size_t count) {
     const size_t bytes = (count ? count : 1) * sizeof(T);
@@ -527,6 +547,8 @@ liec_status liec_create(liec_ctx** out, int32_t N, int64_t d, liec_comp compress
 liec_status liec_step(liec_ctx* c, const float* grads, float* x, float* server_err) {
     if (!c || !grads || !x || !server_err) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     const size_t nd = (size_t)c->N * (size_t)c->d * sizeof(float), db = (size_t)c->d * sizeof(float);
     if (overlap(grads, nd, x, nd) || overlap(grads, nd, server_err, db) || overlap(x, nd, server_err, db))
         return LIEC_EINVAL;
@@ -554,6 +576,8 @@ liec_status liec_step(liec_ctx* c, const float* grads, float* x, float* server_e
 liec_status liec_set_random(liec_ctx* c, uint64_t seed, uint64_t draw) {
     if (!c) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     const RkState st{seed, draw};
     if (hipStreamSynchronize(c->stream) != hipSuccess ||
         hipMemcpy(c->rk_state, &st, sizeof st, hipMemcpyHostToDevice) != hipSuccess) {
@@ -566,6 +590,8 @@ liec_status liec_set_random(liec_ctx* c, uint64_t seed, uint64_t draw) {
 liec_status liec_force_search_mode(liec_ctx* c, int32_t mode) {
     if (!c || (mode != (int32_t)kWarm && mode != (int32_t)kCold && mode != (int32_t)kSlow)) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     std::vector<RowDesc> h((size_t)c->N + 1);
     if (hipStreamSynchronize(c->stream) != hipSuccess ||
         hipMemcpy(h.data(), c->desc, h.size() * sizeof(RowDesc), hipMemcpyDeviceToHost) != hipSuccess) {
@@ -589,6 +615,8 @@ liec_status liec_force_search_mode(liec_ctx* c, int32_t mode) {
 liec_status liec_get_random(liec_ctx* c, uint64_t* seed, uint64_t* draw) {
     if (!c || !seed || !draw) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     RkState st{0, 0};
     if (hipStreamSynchronize(c->stream) != hipSuccess ||
         hipMemcpy(&st, c->rk_state, sizeof st, hipMemcpyDeviceToHost) != hipSuccess) {
@@ -603,6 +631,8 @@ liec_status liec_get_random(liec_ctx* c, uint64_t* seed, uint64_t* draw) {
 liec_status liec_step_sync(liec_ctx* c, const float* grads, float* x, float* server_err) {
     if (!c || !grads || !x || !server_err) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     const size_t nd = (size_t)c->N * (size_t)c->d * sizeof(float), db = (size_t)c->d * sizeof(float);
     if (overlap(grads, nd, x, nd) || overlap(grads, nd, server_err, db) || overlap(x, nd, server_err, db))
         return LIEC_EINVAL;
@@ -637,6 +667,8 @@ liec_status liec_iteration(liec_ctx* c, int64_t t, int64_t period, const float* 
 liec_status liec_set_blocks(liec_ctx* c, const int64_t* offsets, int32_t nblocks) {
     if (!c || !offsets || nblocks < 1 || nblocks > 65536) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     if (offsets[0] != 0 || offsets[nblocks] != c->d) return LIEC_EINVAL;
     for (int32_t b = 0; b < nblocks; ++b)
         if (offsets[b + 1] <= offsets[b]) return LIEC_EINVAL;
@@ -698,6 +730,8 @@ liec_status liec_set_blocks(liec_ctx* c, const int64_t* offsets, int32_t nblocks
 liec_status liec_get_block_scales(liec_ctx* c, float* worker_scales, float* server_scales) {
     if (!c || c->B == 0) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     hipError_t e = hipStreamSynchronize(c->stream);
     const size_t nb = (size_t)c->N * c->B;
     if (e == hipSuccess && worker_scales) {
@@ -752,6 +786,8 @@ liec_status liec_comm_cost(int32_t N, int64_t d, liec_comp worker_comp, int64_t 
 liec_status liec_pack_sign_bits(liec_ctx* c, int32_t worker, uint8_t* out) {
     if (!c || !out || worker < 0 || worker >= c->N) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     if ((c->worker_comp != kSign && c->worker_comp != kBlockSign) || c->steps_done == 0) return LIEC_EINVAL;
     const uint32_t nbytes = (uint32_t)((c->d + 7) / 8);
     k_pack_sign<<<(nbytes + kBlock - 1) / kBlock, kBlock, 0, c->stream>>>(c->bits + (size_t)worker * c->nwt * 64, nbytes, out);
@@ -766,6 +802,8 @@ liec_status liec_unpack_sign_message(liec_ctx* c, const uint8_t* bits, const flo
                                      float* p_out) {
     if (!c || !bits || !scales || !p_out) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     if (blockwise && c->B == 0) return LIEC_EINVAL;
     const uint32_t n = blockwise ? c->B : 1u;
     hipError_t e = hipSuccess;
@@ -797,6 +835,8 @@ liec_status liec_unpack_sign_message(liec_ctx* c, const uint8_t* bits, const flo
 liec_status liec_pack_topk_message(liec_ctx* c, const float* grads, int32_t worker, uint32_t* idx_out, float* val_out) {
     if (!c || !grads || !idx_out || !val_out || worker < 0 || worker >= c->N) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     if (!selects_k(c->worker_comp) || c->steps_done == 0 || ((uintptr_t)grads & 3u)) return LIEC_EINVAL;
     if (!c->wire_tiles) {
         if (hipStreamSynchronize(c->stream) != hipSuccess ||
@@ -828,6 +868,8 @@ liec_status liec_pack_topk_message(liec_ctx* c, const float* grads, int32_t work
 liec_status liec_unpack_topk_message(liec_ctx* c, const uint32_t* idx, const float* val, int64_t k, float* p_out) {
     if (!c || !idx || !val || !p_out || k < 0 || k > c->d) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     const uint32_t d = (uint32_t)c->d;
     k_fill_f32<<<std::min<uint32_t>((d + kBlock - 1) / kBlock, 8192u), kBlock, 0, c->stream>>>(p_out, d, 0.f);
     if (k > 0)
@@ -842,6 +884,8 @@ liec_status liec_unpack_topk_message(liec_ctx* c, const uint32_t* idx, const flo
 liec_status liec_l2_norm(liec_ctx* c, const float* vec, int64_t n, double* norm_out) {
     if (!c || !vec || !norm_out || n < 1 || ((uintptr_t)vec & 3u)) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     // s_partial holds agg_blocks doubles; one more double behind the worker partials receives the sum
     const uint32_t blocks = (uint32_t)std::min<int64_t>((n + kBlock - 1) / kBlock, (int64_t)std::min<uint32_t>(c->agg_blocks, 4096u));
     k_sumsq<<<blocks, kBlock, 0, c->stream>>>(vec, (uint64_t)n, c->s_partial);
@@ -866,6 +910,8 @@ liec_status liec_set_lr(liec_ctx* c, float lr) {
 liec_status liec_get_info(liec_ctx* c, liec_info* info) {
     if (!c || !info) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     std::vector<RowDesc> h((size_t)c->N + 1);
     if (hipStreamSynchronize(c->stream) != hipSuccess ||
         hipMemcpy(h.data(), c->desc, h.size() * sizeof(RowDesc), hipMemcpyDeviceToHost) != hipSuccess) {
@@ -911,6 +957,8 @@ liec_status liec_get_info(liec_ctx* c, liec_info* info) {
 liec_status liec_get_worker_desc(liec_ctx* c, float* scales, double* l1, uint32_t* tau, int64_t* cutoff) {
     if (!c) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     std::vector<RowDesc> h((size_t)c->N);
     if (hipStreamSynchronize(c->stream) != hipSuccess ||
         hipMemcpy(h.data(), c->desc, h.size() * sizeof(RowDesc), hipMemcpyDeviceToHost) != hipSuccess) {
@@ -931,6 +979,8 @@ liec_status liec_get_worker_desc(liec_ctx* c, float* scales, double* l1, uint32_
 liec_status liec_profile_begin(liec_ctx* c, int32_t max_steps, int32_t update_only) {
     if (!c || max_steps < 1) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     drop_prof(c);
     c->profiling = true;
     c->prof_update_only = update_only != 0;
@@ -942,6 +992,8 @@ liec_status liec_profile_end(liec_ctx* c, int32_t* n_slots, const char** names, 
                              int64_t* launches) {
     if (!c || !n_slots || !names || !total_ms || !launches) return LIEC_EINVAL;
     if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
     c->profiling = false;
     if (hipStreamSynchronize(c->stream) != hipSuccess) {
         c->broken = true;
@@ -973,6 +1025,7 @@ liec_status liec_profile_end(liec_ctx* c, int32_t* n_slots, const char** names, 
 
 void liec_destroy(liec_ctx* c) {
     if (!c) return;
+    DeviceScope on(c);
     (void)hipStreamSynchronize(c->stream);
     drop_prof(c);
     free_scratch(c);
