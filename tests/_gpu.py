@@ -14,6 +14,7 @@ import torch
 
 sys.path.insert(0, os.path.dirname(__file__))
 import _harness as H  # noqa: E402
+from _say import say  # noqa: E402,F401
 
 import workloads  # noqa: E402
 
@@ -27,10 +28,6 @@ def ctx_for(w, **kw):
     from paper_2402_11857_amd import LiecContext
 
     return LiecContext(w.N, w.d, w.worker_comp, w.server_comp, w.worker_k, w.server_k, w.lr, **kw)
-
-
-def say(msg):
-    print(msg, flush=True)
 
 
 def check_descriptors(ctx, w, wdesc, sdesc, g_host, v_host, label):

@@ -6,10 +6,16 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+if os.path.dirname(os.path.abspath(__file__)) not in sys.path:
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the GPU tests name each case on the real terminal before they touch the GPU (see _gpu.say)
+    import _say
+
+    _say.CAPTURE_MANAGER = config.pluginmanager.getplugin("capturemanager")
 
 
 @pytest.fixture(scope="session")
