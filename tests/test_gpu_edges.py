@@ -59,6 +59,76 @@ def test_random_shapes_and_operator_pairs(case):
         assert ctx.info().nonfinite == 0
 
 
+@pytest.mark.parametrize("case", range(40))
+def test_random_chains_with_drift_ties_and_averaging_iterations(case):
+    """Seeded chains of 4-8 iterations of Algorithm 1 as a whole (liec_iteration; period 0, 3 or 4) over random
+    shapes up to 3 million columns, random k (also 1, d - 1, d), every operator pair, with the gradient scale
+    drifting or jumping between iterations and ties injected, compared bit for bit after every iteration."""
+    import oracle
+    from paper_2402_11857_amd import LiecContext
+
+    rng = np.random.default_rng(50_000 + case)
+    wc, sc = ALL_OPS[int(rng.integers(5))], ALL_OPS[int(rng.integers(5))]
+    if rng.random() < 0.5:                       # weight the threshold searches
+        wc = str(rng.choice(["topk", "randk", "topk"]))
+    N = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16, 17, 31, 40]))
+    d = int(np.exp(rng.uniform(np.log(1), np.log(3_000_000 // max(1, N // 4)))))
+    if rng.random() < 0.3:
+        d = max(1, (d // 1024) * 1024 + int(rng.choice([0, 1, 3, 4, 1020, 1023])))
+
+    def pick_k():
+        r = rng.random()
+        if r < 0.2:
+            return int(rng.integers(1, d + 1))
+        if r < 0.3:
+            return int(rng.choice([1, d, max(1, d - 1), max(1, d // 2)]))
+        return max(1, d // int(rng.choice([10, 100, 200, 1000])))
+
+    wk = pick_k() if wc in ("topk", "randk") else 0
+    sk = pick_k() if sc in ("topk", "randk") else 0
+    lr = float(rng.choice([0.5, 0.1, 0.01]))
+    nb = int(rng.integers(1, min(d, 40) + 1))
+    off = sorted({0, d, *map(int, rng.integers(0, d + 1, size=nb - 1))})
+    steps = int(rng.integers(4, 9))
+    period = int(rng.choice([0, 0, 3, 4]))
+    drift = str(rng.choice(["none", "none", "slow", "jump"]))
+    ties = rng.random() < 0.3
+    say(f"case chain {case}: N={N} d={d} {wc}/{sc} k={wk}/{sk} lr={lr} blocks={len(off) - 1} steps={steps} "
+        f"period={period} drift={drift} ties={ties}")
+    w = workloads.scaled(WL["c2_topk_mid"], N=N, d=d, worker_comp=wc, server_comp=sc, worker_k=wk, server_k=sk, lr=lr)
+    src = workloads.GradientSource(w, seed=case, device=DEV)
+    x = torch.zeros((N, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    xo, eo = np.zeros((N, d), dtype=np.float32), np.zeros(d, dtype=np.float32)
+    draw, scale = 0, 1.0
+    with LiecContext(N, d, wc, sc, wk, sk, lr) as ctx:
+        ctx.set_random(case, 0)
+        if "blocksign" in (wc, sc):
+            ctx.set_blocks(off)
+        for t in range(steps):
+            g = src.grads(t)
+            if drift == "slow":
+                scale *= float(rng.choice([0.9, 1.05, 1.2]))
+            elif drift == "jump" and rng.random() < 0.4:
+                scale *= float(rng.choice([1e-3, 30.0, 1e3, 0.2]))
+            if scale != 1.0:
+                g = g * np.float32(scale)
+            if ties:
+                g = workloads.inject_ties(g, seed=t, frac_zero=float(rng.choice([0.0, 0.2, 0.9])),
+                                          frac_dup=float(rng.choice([0.0, 0.3])))
+            g = g.contiguous()
+            gh = g.cpu().numpy()
+            ctx.iteration(t, period, g, x, e)
+            if period >= 2 and (t + 1) % period == 0:
+                oracle.step_sync(gh, xo, eo, lr)
+            else:
+                oracle.step_blocks(gh, xo, eo, wc, sc, lr, off, wk, sk, rng=(case, draw))
+                draw += 1                        # only compressed iterations draw
+            assert H.bit_equal(e.cpu().numpy(), eo), f"iteration {t}: server error"
+            assert H.bit_equal(x.cpu().numpy(), xo), f"iteration {t}: models"
+        assert ctx.info().nonfinite == 0
+
+
 @pytest.mark.parametrize("wc,sc", [("topk", "topk"), ("topk", "sign")])
 def test_threshold_prediction_survives_jumps_of_the_gradient_scale(wc, sc):
     """The band predicted from the last thresholds misses when the gradients' scale jumps; the step must
