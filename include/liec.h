@@ -70,6 +70,10 @@ typedef struct {
     int64_t server_cutoff;    /* top-k / random-k on the server: largest kept index
                                  among entries whose key equals server_tau_key     */
     int32_t nonfinite;        /* 1 if a NaN/Inf reached an L1 sum or a top-k key   */
+    int32_t slow_rows;        /* top-k / random-k: rows (workers + server) whose last
+                                 threshold search fell to the general single-block
+                                 search -- constant or near-constant rows; results are
+                                 exact either way, such rows only take much longer   */
 } liec_info;
 
 /*

@@ -43,6 +43,7 @@ class LiecInfo(ctypes.Structure):
         ("server_tau_key", ctypes.c_uint32),
         ("server_cutoff", ctypes.c_int64),
         ("nonfinite", ctypes.c_int32),
+        ("slow_rows", ctypes.c_int32),
     ]
 
 

@@ -18,8 +18,9 @@ namespace liec {
 //      usable, the band becomes the first-radix-digit bin holding rank k, found by k_hist0 +
 //      k_pick_band over the whole row (-> kColdBand), and the row is filtered again.
 //   2. k_list_hist<0>, k_list_hist<1>, k_list_ties and k_list_finish run a 2-digit radix select on
-//      the listed keys, taken relative to the band's lower end, and order the ties by index.
-//   3. Rows the list cannot hold (massive ties, degenerate data) take k_slow_select.
+//      the listed keys, taken relative to the band's lower end, and order the ties by index (up to
+//      4096 of them through a buffer, more by a radix select over the listed indices).
+//   3. Rows whose band the list cannot hold (constant or near-constant rows) take k_slow_select.
 // All decisions are taken on the device per row, each kernel re-deriving from the row's counters
 // whether it has work; only the one-block-per-row kernels (k_pick_band, k_list_finish,
 // k_slow_select) change a row's mode.  The host always enqueues the same kernels.
@@ -374,7 +375,7 @@ __global__ __launch_bounds__(kBlock) void k_list_hist(uint32_t row0, RowDesc* __
 }
 
 // Picks the low digit (-> tau, how many of its ties are kept, how many there are) and collects the
-// indices of the listed entries whose key equals tau.  grid = (blocks, rows).
+// indices of the listed entries whose key equals tau when the tie buffer can hold them.  grid = (blocks, rows).
 __global__ __launch_bounds__(kBlock) void k_list_ties(uint32_t row0, RowDesc* __restrict__ desc,
                                                        const uint2* __restrict__ list, uint32_t cap, uint32_t k,
                                                        const uint32_t* __restrict__ lhist,
@@ -394,6 +395,7 @@ __global__ __launch_bounds__(kBlock) void k_list_ties(uint32_t row0, RowDesc* __
         desc[row].rank = p.rank_in;
         desc[row].ties = p.count;
     }
+    if (p.count > (uint32_t)kTieCap) return;                    // too many for the buffer: k_list_finish selects by index
     const uint2* __restrict__ in = list + (size_t)row * cap;
     uint32_t* __restrict__ tb = tiebuf + (size_t)row * kTieCap;
     for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < n; e += nb * kBlock) {
@@ -433,19 +435,24 @@ __device__ __forceinline__ void predict_band(RowDesc& r, uint32_t fix_lo, uint32
     r.was_cold = 0;
 }
 
-// grid = rows.  Orders the collected ties by index, sets the cut-off, clears the list state and
-// predicts the next step's band.  Rows whose band failed twice, or with more ties than the buffer
-// holds, go to the slow search.
-__global__ __launch_bounds__(kBlock) void k_list_finish(uint32_t row0, RowDesc* __restrict__ desc,
-                                                         uint32_t* __restrict__ lhist,
-                                                         const uint32_t* __restrict__ tiebuf, uint32_t cap, uint32_t k,
-                                                         uint32_t fix_lo, uint32_t fix_hi) {
-    __shared__ uint32_t t_idx[kTieCap];
+// grid = rows, 1024 threads.  Orders the collected ties by index, sets the cut-off, clears the list state
+// and predicts the next step's band.  When more entries share the threshold than the tie buffer holds
+// (quantised gradients: thousands of equal magnitudes), the cut-off -- the `rank`-th smallest index
+// among the listed entries whose key is tau -- comes from a three-digit radix select over those
+// indices, read from the candidate list itself.  Rows whose band failed twice go to the slow search.
+constexpr int kFinishBlock = 1024;
+__global__ __launch_bounds__(kFinishBlock) void k_list_finish(uint32_t row0, RowDesc* __restrict__ desc,
+                                                               uint32_t* __restrict__ lhist,
+                                                               const uint32_t* __restrict__ tiebuf,
+                                                               const uint2* __restrict__ list, uint32_t cap, uint32_t k,
+                                                               uint32_t fix_lo, uint32_t fix_hi) {
+    __shared__ uint32_t t_idx[kTieCap];                        // tie indices, or the digit histogram
+    __shared__ uint32_t part[256], res[3];
     __shared__ uint32_t s_cut;
-    const uint32_t row = row0 + blockIdx.x;
+    const uint32_t row = row0 + blockIdx.x, tid = threadIdx.x;
     if (desc[row].mode == kSlow) return;
     if (!listable(desc[row], cap, k)) {                        // uniform for the block
-        if (threadIdx.x == 0) {
+        if (tid == 0) {
             RowDesc r = desc[row];
             r.n_cand = 0;
             clear_sure(r);
@@ -457,38 +464,67 @@ __global__ __launch_bounds__(kBlock) void k_list_finish(uint32_t row0, RowDesc* 
         return;
     }
     uint32_t* __restrict__ hrow = lhist + (size_t)row * 2 * kListBins;
-    for (int b = threadIdx.x; b < 2 * kListBins; b += kBlock) hrow[b] = 0;
+    for (int b = tid; b < 2 * kListBins; b += kFinishBlock) hrow[b] = 0;
     const uint32_t ties = desc[row].ties, want = desc[row].rank;
-    const bool fits = ties <= (uint32_t)kTieCap;
-    if (fits) {
+    if (ties <= (uint32_t)kTieCap) {
         const uint32_t* __restrict__ tb = tiebuf + (size_t)row * kTieCap;
-        for (uint32_t q = threadIdx.x; q < ties; q += kBlock) t_idx[q] = tb[q];
-        if (threadIdx.x == 0) s_cut = 0xffffffffu;
+        for (uint32_t q = tid; q < ties; q += kFinishBlock) t_idx[q] = tb[q];
+        if (tid == 0) s_cut = 0xffffffffu;
         __syncthreads();
-        for (uint32_t q = threadIdx.x; q < ties; q += kBlock) {
+        for (uint32_t q = tid; q < ties; q += kFinishBlock) {
             const uint32_t mine = t_idx[q];
             uint32_t below = 0;
             for (uint32_t r = 0; r < ties; ++r) below += t_idx[r] < mine;
             if (below + 1 == want) s_cut = mine;            // indices are distinct: one writer
         }
         __syncthreads();
+    } else {
+        // Indices are below 2^31; taking 0x7fffffff - index as the key turns "want-th smallest index" into
+        // "want-th largest key", which is what block_pick finds.  Digits of 11, 10 and 10 bits.
+        const uint2* __restrict__ in = list + (size_t)row * cap;
+        const uint32_t n = desc[row].n_cand, tau = desc[row].tau;
+        uint32_t prefix = 0, rank = want;
+#pragma unroll 1
+        for (int pass = 0; pass < 3; ++pass) {
+            const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+            const int above = pass == 0 ? 31 : (pass == 1 ? 20 : 10);   // bits above this digit are the prefix
+            const int nbins = pass == 0 ? 2048 : 1024;
+            for (int b = tid; b < nbins; b += kFinishBlock) t_idx[b] = 0;
+            __syncthreads();
+            auto count = [&](uint2 kv) {
+                const uint32_t inv = 0x7fffffffu - kv.y;
+                if (kv.x == tau && (inv >> above) == prefix) atomicAdd(&t_idx[(inv >> shift) & (uint32_t)(nbins - 1)], 1u);
+            };
+            uint32_t e = tid;
+            for (; e + 3 * kFinishBlock < n; e += 4 * kFinishBlock) {   // four independent loads in flight
+                const uint2 a0 = in[e], a1 = in[e + kFinishBlock], a2 = in[e + 2 * kFinishBlock],
+                            a3 = in[e + 3 * kFinishBlock];
+                count(a0);
+                count(a1);
+                count(a2);
+                count(a3);
+            }
+            for (; e < n; e += kFinishBlock) count(in[e]);
+            __syncthreads();
+            const Pick p = block_pick(t_idx, nbins, rank, part, res);
+            prefix = (prefix << (pass == 0 ? 11 : 10)) | p.bin;
+            rank = p.rank_in;
+        }
+        if (tid == 0) s_cut = 0x7fffffffu - prefix;
+        __syncthreads();
     }
-    if (threadIdx.x == 0) {
+    if (tid == 0) {
         RowDesc r = desc[row];
         r.n_list = r.n_cand;
         r.n_cand = 0;
         clear_sure(r);
         r.n_ties = 0;
-        if (fits) {
-            r.cutoff = s_cut;
-            r.dense = 0;
-            r.nonfinite = r.nonfinite_acc;
-            r.nonfinite_acc = 0;
-            predict_band(r, fix_lo, fix_hi);
-            r.mode = kWarm;
-        } else {
-            r.mode = kSlow;
-        }
+        r.cutoff = s_cut;
+        r.dense = 0;
+        r.nonfinite = r.nonfinite_acc;
+        r.nonfinite_acc = 0;
+        predict_band(r, fix_lo, fix_hi);
+        r.mode = kWarm;
         desc[row] = r;
     }
 }

@@ -274,7 +274,7 @@ void launch_select(Launcher& L, const float* src, size_t row_stride, uint32_t ro
     k_list_ties<<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, k, c->lhist, c->tiebuf);
     L.end();
     L.begin(slot0 + 7);
-    k_list_finish<<<rows, kBlock, 0, st>>>(row0, c->desc, c->lhist, c->tiebuf, c->cap, k, rk.fix_lo, rk.fix_hi);
+    k_list_finish<<<rows, kFinishBlock, 0, st>>>(row0, c->desc, c->lhist, c->tiebuf, c->list, c->cap, k, rk.fix_lo, rk.fix_hi);
     L.end();
     L.begin(slot0 + 8);
     k_slow_select<VEC, RK><<<rows, 1024, 0, st>>>(src, row_stride, d, row0, c->desc, k, rk);
@@ -935,6 +935,8 @@ liec_status liec_get_info(liec_ctx* c, liec_info* info) {
         info->server_tau_key = s.tau;
         info->server_cutoff = (int64_t)s.cutoff;
     }
+    for (size_t r = 0; r < h.size(); ++r)
+        if (selects_k(r < (size_t)c->N ? c->worker_comp : c->server_comp) && h[r].dense) ++info->slow_rows;
     bool bad = (c->server_comp == kSign || c->server_comp == kTopk) && s.nonfinite;
     if (c->worker_comp == kSign || c->worker_comp == kTopk)
         for (int32_t i = 0; i < c->N; ++i) bad = bad || h[(size_t)i].nonfinite;

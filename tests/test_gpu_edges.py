@@ -130,6 +130,59 @@ def test_random_chains_with_drift_ties_and_averaging_iterations(case):
 
 
 @pytest.mark.parametrize("wc,sc", [("topk", "topk"), ("topk", "sign")])
+def test_quantised_gradients_with_thousands_of_ties_at_the_threshold(wc, sc):
+    """Gradients that carry 5 mantissa bits (as after a low-precision backward pass): about 10^4 entries of a
+    row share the threshold magnitude, more than the tie buffer holds.  The result must still be the oracle's,
+    and the rows must not fall to the general single-block search (slow_rows stays 0)."""
+    import oracle
+    from paper_2402_11857_amd import LiecContext
+
+    N, d = 3, 6_000_000
+    k = d // 100
+    say(f"case quantised gradients N={N} d={d} {wc}/{sc} k={k}")
+    w = workloads.scaled(WL["c1_tiny_sign"], N=N, d=d, worker_comp=wc, server_comp=sc, worker_k=k, server_k=k, lr=0.1)
+    src = workloads.GradientSource(w, seed=77, device=DEV)
+    x = torch.zeros((N, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    xo, eo = np.zeros((N, d), dtype=np.float32), np.zeros(d, dtype=np.float32)
+    with LiecContext(N, d, wc, sc, k, k if sc == "topk" else 0, 0.1) as ctx:
+        for t in range(3):
+            g = (src.grads(t).view(torch.int32) & -(1 << 18)).view(torch.float32).contiguous()
+            gh = g.cpu().numpy()
+            keys = gh.view(np.uint32) & np.uint32(0x7FFFFFFF)
+            for i in range(N):
+                tau = np.partition(keys[i], d - k)[d - k]
+                assert int((keys[i] == tau).sum()) > 4096, "the case must exceed the tie buffer"
+            ctx.step(g, x, e)
+            oracle.step(gh, xo, eo, wc, sc, 0.1, k, k if sc == "topk" else 0)
+            say(f"  step {t} done")
+            assert H.bit_equal(e.cpu().numpy(), eo), f"step {t}: server error"
+            assert H.bit_equal(x.cpu().numpy(), xo), f"step {t}: models"
+            info = ctx.info()
+            assert info.nonfinite == 0 and info.slow_rows == 0, f"step {t}: {info.slow_rows} rows took the slow search"
+
+
+def test_constant_rows_are_reported_as_slow_rows():
+    """Rows whose entries all share one magnitude cannot be listed: they take the general search, and the
+    context says so."""
+    from paper_2402_11857_amd import LiecContext
+
+    N, d, k = 2, 50_000, 500
+    say("case slow_rows telemetry")
+    g = torch.full((N, d), 0.25, dtype=torch.float32, device=DEV)
+    g[:, ::2] *= -1
+    x = torch.zeros((N, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    with LiecContext(N, d, "topk", "identity", k, 0, 0.1) as ctx:
+        ctx.step(g, x, e)
+        assert ctx.info().slow_rows == N
+        g2 = torch.randn((N, d), dtype=torch.float32, device=DEV)
+        ctx.step(g2, x, e)
+        ctx.step(g2, x, e)
+        assert ctx.info().slow_rows == 0
+
+
+@pytest.mark.parametrize("wc,sc", [("topk", "topk"), ("topk", "sign")])
 def test_threshold_prediction_survives_jumps_of_the_gradient_scale(wc, sc):
     """The band predicted from the last thresholds misses when the gradients' scale jumps; the step must
     then find the threshold the long way and still match the oracle (drifts are followed by the trend)."""
