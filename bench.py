@@ -94,6 +94,7 @@ def run_workload(w, steps: int, warmup: int, seed: int = 0):
         for t in range(ns):
             ctx.step_sync(grads[t % nbuf], x, e)
         sync_ms = ctx.profile_end()["sync"][0] / ns
+        wire = time_wire_forms(ctx, w, grads[0], x, e)
         scratch = ctx.scratch_bytes()
     ms_per_step = 1e3 * elapsed / steps
     out = {
@@ -104,12 +105,49 @@ def run_workload(w, steps: int, warmup: int, seed: int = 0):
         "scratch_bytes": scratch,
         "region_ms_per_step": [round(1e3 * r[0] / steps, 4) for r in regions],
         "sync_ms": sync_ms,
+        "wire": wire,
         "sync_gbps": dominant_kernel_bytes(w) / (sync_ms * 1e-3) / 1e9,   # same bytes: g, x in, x out, e in/out
     }
     out["update_avg_ms"] = upd_ms / upd_n
     out["update_gbps"] = dominant_kernel_bytes(w) / (upd_ms / upd_n * 1e-3) / 1e9
     del grads, x, e
     torch.cuda.empty_cache()
+    return out
+
+
+def time_wire_forms(ctx, w, g, x, e, reps: int = 5):
+    """Worker 0's uplink message of one more step put into its wire form and decompressed again (the step
+    itself never materialises messages); events on the null stream, which the context uses here."""
+    import torch
+
+    from paper_2402_11857_amd import liec_message_bytes
+
+    if w.worker_comp == "identity":
+        return None
+    ctx.step(g, x, e)
+    p_out = torch.empty(w.d, dtype=torch.float32, device=g.device)
+    nblocks = len(w.blocks) - 1 if w.blocks is not None else 0
+    if w.worker_comp in ("sign", "blocksign"):
+        bits = torch.empty((w.d + 7) // 8, dtype=torch.uint8, device=g.device)
+        blockwise = w.worker_comp == "blocksign"
+        scales = ctx.block_scales()[0][0] if blockwise else [ctx.worker_desc()["scale"][0]]
+        pack = lambda: ctx.pack_sign_bits(0, bits)                                    # noqa: E731
+        unpack = lambda: ctx.unpack_sign_message(bits, scales, blockwise, p_out)     # noqa: E731
+    else:
+        idx = torch.empty(w.worker_k, dtype=torch.int32, device=g.device)
+        val = torch.empty(w.worker_k, dtype=torch.float32, device=g.device)
+        pack = lambda: ctx.pack_topk_message(g, 0, idx, val)                          # noqa: E731
+        unpack = lambda: ctx.unpack_topk_message(idx, val, p_out)                    # noqa: E731
+    out = {"message_bytes": liec_message_bytes(w.worker_comp, w.d, w.worker_k, nblocks), "dense_bytes": 4 * w.d}
+    for name, fn in (("pack_ms", pack), ("unpack_ms", unpack)):
+        fn()
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        for _ in range(reps):
+            fn()
+        stop.record()
+        torch.cuda.synchronize()
+        out[name] = round(start.elapsed_time(stop) / reps, 4)
     return out
 
 
@@ -221,6 +259,7 @@ def main() -> int:
                           "alg_gbps": round(r["alg_gbps"], 1), "hbm_frac": round(r["alg_gbps"] / HBM_PEAK_GBPS, 4),
                           "update_gbps": round(r["update_gbps"], 1),
                           "averaging_iteration_ms": round(r["sync_ms"], 4),
+                          "wire_worker0": r["wire"],
                           "kernels_ms_per_step": {k: round(v, 4) for k, v in r["kernels_ms_per_step"].items()}}
             if name in CACHE_RESIDENT:
                 also[name]["note"] = CACHE_RESIDENT[name]
@@ -258,6 +297,7 @@ def main() -> int:
                      "avg_launch_ms": main_res["update_avg_ms"]},
         "kernels_ms_per_step_untimed_pass": {k: round(v, 4) for k, v in main_res["kernels_ms_per_step"].items()},
         "scratch_bytes": main_res["scratch_bytes"],
+        "wire_worker0": main_res["wire"],
         "averaging_iteration": {"ms": round(main_res["sync_ms"], 4), "alg_gbps": round(main_res["sync_gbps"], 1),
                                 "note": "Algorithm 1's uncompressed iteration, one in every `period` steps; not part of value"},
         # Algorithm 1 as a whole with the averaging periods of the paper's experiments, from the two measured times

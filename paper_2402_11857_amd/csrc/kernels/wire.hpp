@@ -9,7 +9,7 @@ namespace liec {
 // Wire form of a (blockwise) scaled-sign message: one bit per element, bit j % 8 of byte j / 8 set
 // when the element is negative.  k_pack_sign turns one row of the lane-major bitmap into that
 // form (one thread per output byte); k_unpack_sign expands wire bits and scale(s) into the dense
-// message p_j = -s or +s (one thread per column).
+// message p_j = -s or +s (one 128-bit store per 4 columns).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_pack_sign(const uint16_t* __restrict__ row_bits, uint32_t nbytes,
                                                        uint8_t* __restrict__ out) {
@@ -20,17 +20,30 @@ __global__ __launch_bounds__(kBlock) void k_pack_sign(const uint16_t* __restrict
     out[b] = (uint8_t)(((m0 >> (4 * u)) & 0xfu) | (((m1 >> (4 * u)) & 0xfu) << 4));
 }
 
+template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_unpack_sign(const uint8_t* __restrict__ bytes, uint32_t d,
                                                          const float* __restrict__ scales, BlockTable bt,
                                                          float* __restrict__ p) {
-    const uint32_t j = blockIdx.x * kBlock + threadIdx.x;
-    if (j >= d) return;
-    float s = scales[0];
-    if (bt.B) {
-        const uint32_t tb = bt.tile_blk[j / kColTile];
-        s = scales[(tb >> 31) ? block_of(bt, tb & 0x7fffffffu, j) : tb];
+    const uint32_t nq = (d + 3) / 4;                            // groups of 4 columns = half a wire byte
+    for (uint32_t q = blockIdx.x * kBlock + threadIdx.x; q < nq; q += gridDim.x * kBlock) {
+        const uint32_t j0 = q * 4;
+        const uint32_t m = (uint32_t)bytes[q >> 1] >> (4 * (q & 1u));
+        float v[4];
+        if (bt.B) {
+            const uint32_t tb = bt.tile_blk[j0 / kColTile], first = tb & 0x7fffffffu;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t j = j0 + c < d ? j0 + c : d - 1;
+                const float s = scales[(tb >> 31) ? block_of(bt, first, j) : first];
+                v[c] = ((m >> c) & 1u) ? -s : s;
+            }
+        } else {
+            const float s = scales[0];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) v[c] = ((m >> c) & 1u) ? -s : s;
+        }
+        st4<VEC>(p, j0, d, make_float4(v[0], v[1], v[2], v[3]));
     }
-    p[j] = ((bytes[j / 8] >> (j % 8)) & 1u) ? -s : s;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -824,7 +824,11 @@ liec_status liec_unpack_sign_message(liec_ctx* c, const uint8_t* bits, const flo
     BlockTable bt = block_table(c);
     if (!blockwise) bt.B = 0;
     const uint32_t d = (uint32_t)c->d;
-    k_unpack_sign<<<(d + kBlock - 1) / kBlock, kBlock, 0, c->stream>>>(bits, d, c->wire_scales, bt, p_out);
+    const uint32_t nq = (d + 3) / 4, grid = std::min<uint32_t>((nq + kBlock - 1) / kBlock, 16384u);
+    if (d % 4 == 0 && ((uintptr_t)p_out & 15u) == 0)
+        k_unpack_sign<true><<<grid, kBlock, 0, c->stream>>>(bits, d, c->wire_scales, bt, p_out);
+    else
+        k_unpack_sign<false><<<grid, kBlock, 0, c->stream>>>(bits, d, c->wire_scales, bt, p_out);
     if (hipGetLastError() != hipSuccess) {
         c->broken = true;
         return LIEC_EDEVICE;
