@@ -87,7 +87,7 @@ typedef struct {
  * Allocates the context's device scratch: 4d bytes for v; N * d / 8 for sign or
  * random-k bitmaps; with top-k or random-k on either side also (N + 1) * (d / 2 +
  * 32 KiB) for the candidate lists, N * d / 32 for the group bitmap and about
- * 100 KiB per row of histograms (liec_scratch_bytes reports the total).  The
+ * 120 KiB per row of histograms (liec_scratch_bytes reports the total).  The
  * context belongs to the HIP device that is current at this call: every later call
  * on it makes that device current for its own duration and puts the caller's back.
  */
@@ -264,10 +264,20 @@ liec_status liec_get_random(liec_ctx *ctx, uint64_t *seed, uint64_t *draw);
  * (Definition 3): makes every such row start the next liec_step's search in the
  * given mode -- 0: filter the band predicted by the previous step, 1: no
  * prediction (first radix digit over the whole row, then filter), 4: the general
- * one-block-per-row search.  The modes differ in cost only; the kept set is the
+ * search over the whole row.  The modes differ in cost only; the kept set is the
  * same in each.  Synchronises the stream.  LIEC_EINVAL for any other mode.
  */
 liec_status liec_force_search_mode(liec_ctx *ctx, int32_t mode);
+
+/*
+ * Testing aid for the general search (mode 4 above, also what constant or
+ * mostly-zero rows fall to): several thread blocks share a row and wait for one
+ * another between its phases; `polls` bounds each wait (default 65536, about 0.2 s).
+ * A wait that runs out is not an error: one block then repeats the search on its
+ * own, with the same result.  0 makes every wait run out at once, which is how the
+ * tests reach that path.  LIEC_EINVAL for a negative value.
+ */
+liec_status liec_set_search_wait(liec_ctx *ctx, int32_t polls);
 
 /* Synchronises the stream and copies the scalars of the last step to the host
  * struct `info`.  Returns LIEC_ENONFINITE (with `info` filled) if that step met

@@ -98,6 +98,8 @@ def lib():
         L.liec_l2_norm.argtypes = [vp, vp, i64, ctypes.POINTER(ctypes.c_double)]
         L.liec_force_search_mode.restype = ctypes.c_int
         L.liec_force_search_mode.argtypes = [vp, i32]
+        L.liec_set_search_wait.restype = ctypes.c_int
+        L.liec_set_search_wait.argtypes = [vp, i32]
         L.liec_get_info.restype = ctypes.c_int
         L.liec_get_info.argtypes = [vp, ctypes.POINTER(LiecInfo)]
         L.liec_get_worker_desc.restype = ctypes.c_int
@@ -305,6 +307,9 @@ class LiecContext:
 
     def force_search_mode(self, mode: int) -> None:
         _check(lib().liec_force_search_mode(self._h, mode), "liec_force_search_mode")
+
+    def set_search_wait(self, polls: int) -> None:
+        _check(lib().liec_set_search_wait(self._h, polls), "liec_set_search_wait")
 
     def info(self) -> LiecInfo:
         return liec_get_info(self._h)[0]

@@ -193,6 +193,19 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {   // set bits o
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
+// Histogram step of a whole wave (call it in wave-uniform control flow): adds one to LDS bin `bin` for every
+// lane with `valid`.  When all of them name the same bin -- a degenerate row puts whole waves on one
+// magnitude -- the wave issues one atomic instead of serialising 64 on one address.
+__device__ __forceinline__ void wave_count(uint32_t* h, bool valid, uint32_t bin, uint32_t lane) {
+    const uint32_t bin0 = __builtin_amdgcn_readfirstlane(bin);
+    const uint64_t act = __ballot(valid);
+    if (__ballot(valid && bin != bin0) == 0) {
+        if (lane == 0 && act) atomicAdd(&h[bin0], (uint32_t)__popcll(act));
+    } else if (valid) {
+        atomicAdd(&h[bin], 1u);
+    }
+}
+
 // Sum over the block in a fixed order (lanes by halving, then waves in order).  Valid on thread 0.
 __device__ __forceinline__ double block_sum_f64(double v, double* lds_waves) {
 #pragma unroll

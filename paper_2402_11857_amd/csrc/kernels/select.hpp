@@ -273,8 +273,7 @@ __global__ __launch_bounds__(kBlock) void k_hist0(const float* __restrict__ src,
                 keys[3] = key_of(a[u].w);
             }
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (j + q < d) atomicAdd(&h[keys[q] >> 19], 1u);
+            for (int q = 0; q < 4; ++q) wave_count(h, j + q < d, keys[q] >> 19, lane);
         }
     }
     __syncthreads();
@@ -445,11 +444,14 @@ __global__ __launch_bounds__(kFinishBlock) void k_list_finish(uint32_t row0, Row
                                                                uint32_t* __restrict__ lhist,
                                                                const uint32_t* __restrict__ tiebuf,
                                                                const uint2* __restrict__ list, uint32_t cap, uint32_t k,
-                                                               uint32_t fix_lo, uint32_t fix_hi) {
+                                                               uint32_t fix_lo, uint32_t fix_hi,
+                                                               uint32_t* __restrict__ slow_sync) {
     __shared__ uint32_t t_idx[kTieCap];                        // tie indices, or the digit histogram
     __shared__ uint32_t part[256], res[3];
     __shared__ uint32_t s_cut;
     const uint32_t row = row0 + blockIdx.x, tid = threadIdx.x;
+    // the meeting counter and give-up flag of the general search that may follow start every step at zero
+    if (slow_sync && tid < 2) slow_sync[(size_t)blockIdx.x * 2 + tid] = 0;
     if (desc[row].mode == kSlow) return;
     if (!listable(desc[row], cap, k)) {                        // uniform for the block
         if (tid == 0) {
@@ -529,73 +531,108 @@ __global__ __launch_bounds__(kFinishBlock) void k_list_finish(uint32_t row0, Row
     }
 }
 
-// General search for rows in kSlow mode, one block of 1024 threads per row: three radix digits
-// over the whole row, then the ties in index order.  Slow by design; only degenerate rows (a
-// threshold shared by thousands of entries) come here.  grid = rows.
+// ---------------------------------------------------------------------------------------------
+// General search for rows in kSlow mode: three radix digits over the whole row, then the ties in
+// index order.  Only degenerate rows come here (constant or mostly-zero rows, values on a handful of
+// levels: a threshold shared by more entries than the candidate list holds).
+//   grid = (B, rows), 1024 threads.  With B > 1 the B blocks of a row split it into contiguous ranges
+// and meet between the phases at a counter in the row's descriptor (every block adds one and polls
+// until all B have arrived); the histograms of the three digits and the blocks' tie counts live in
+// global memory.  The poll is bounded: when a wait runs out (blocks that could not all be resident
+// at once, a GPU shared with other work) the row is flagged, every block leaves, and block 0
+// repeats the search on its own with LDS histograms -- the B = 1 path.  Results are identical.
+// The host chooses B so that B * rows blocks fit the chip at one block per compute unit.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSlowMaxBlocks = 64;
+constexpr uint32_t kSlowHistWords = 4096 + 1024 + 512;        // the three digit histograms of a row
+
+struct SlowLds {
+    uint32_t h[kHistBins];
+    uint32_t part[256], res[3];
+    uint32_t wtot[16];
+    uint32_t cut, bad, ok;
+};
+
+// the 4 keys of columns j .. j + 3 (columns at or beyond d give unspecified keys; callers test j + q < d)
 template <bool VEC, bool RK>
-__global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ src, size_t row_stride, uint32_t d,
-                                                       uint32_t row0, RowDesc* __restrict__ desc, uint32_t k,
-                                                       RkDraw rk) {
-    __shared__ uint32_t h[kHistBins];
-    __shared__ uint32_t part[256], res[3];
-    __shared__ uint32_t wtot[16];
-    __shared__ uint32_t s_cut, s_bad;
-    const uint32_t row = row0 + blockIdx.x;
-    if (desc[row].mode != kSlow) return;
-    const float* __restrict__ g = src + (size_t)blockIdx.x * row_stride;
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    uint32_t k0 = 0, k1 = 0;
+__device__ __forceinline__ void slow_keys_at(const float* __restrict__ g, uint32_t d, uint32_t k0, uint32_t k1, uint32_t j,
+                                             uint32_t (&key)[4]) {
     if (RK) {
-        const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
-        k0 = (uint32_t)stream;
-        k1 = (uint32_t)(stream >> 32);
-    }
-    // the 4 keys of columns j .. j + 3 (columns at or beyond d give unspecified keys; callers test j + q < d)
-    auto keys_at = [&](uint32_t j, uint32_t (&key)[4]) {
-        if (RK) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) key[q] = rk_priority(k0, k1, j + q);
-        } else {
-            const float4 a = ld4<VEC>(g, j, d);
-            key[0] = key_of(a.x);
-            key[1] = key_of(a.y);
-            key[2] = key_of(a.z);
-            key[3] = key_of(a.w);
-        }
-    };
+        for (int q = 0; q < 4; ++q) key[q] = rk_priority(k0, k1, j + q);
+    } else {
+        const float4 a = ld4<VEC>(g, j, d);
+        key[0] = key_of(a.x);
+        key[1] = key_of(a.y);
+        key[2] = key_of(a.z);
+        key[3] = key_of(a.w);
+    }
+}
+
+// What either path leaves in the row's descriptor (one thread calls it).
+__device__ __forceinline__ void slow_write_result(RowDesc* __restrict__ desc, uint32_t row, uint32_t tau, uint32_t rank,
+                                                  uint32_t ties, uint32_t cut, uint32_t bad, bool is_rk, RkDraw rk) {
+    RowDesc r = desc[row];
+    r.tau = tau;
+    r.rank = rank;
+    r.ties = ties;
+    r.cutoff = cut;
+    r.dense = 1;
+    r.nonfinite = bad | r.nonfinite_acc;
+    r.nonfinite_acc = 0;
+    r.n_cand = 0;
+    clear_sure(r);
+    r.n_ties = 0;
+    r.n_list = 0;
+    r.have_prev = 0;
+    r.was_cold = 0;
+    r.mode = kCold;
+    if (is_rk) {                               // the band of a random-k draw is known without a prediction
+        r.lo = rk.fix_lo;
+        r.hi = rk.fix_hi;
+        r.mode = kWarm;
+    }
+    desc[row] = r;
+}
+
+// One block on its own, histograms in LDS.
+template <bool VEC, bool RK>
+__device__ void slow_single(SlowLds& s, const float* __restrict__ g, uint32_t d, uint32_t row, RowDesc* __restrict__ desc,
+                            uint32_t k, RkDraw rk, uint32_t k0, uint32_t k1) {
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint32_t prefix = 0, rank = k, ties = 0;
-    if (tid == 0) s_bad = 0;
+    if (tid == 0) s.bad = 0;
     for (int pass = 0; pass < 3; ++pass) {
         const int shift = digit_shift(pass), nbins = 1 << digit_bits(pass);
         const int hi_shift = pass == 0 ? 31 : digit_shift(pass - 1);
-        for (int b = tid; b < nbins; b += 1024) h[b] = 0;
+        for (int b = tid; b < nbins; b += 1024) s.h[b] = 0;
         __syncthreads();
         for (uint32_t j = tid * 4; j < d; j += 4096) {
             uint32_t key[4];
-            keys_at(j, key);
+            slow_keys_at<VEC, RK>(g, d, k0, k1, j, key);
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-                if (j + q < d && ((key[q] ^ prefix) >> hi_shift) == 0) atomicAdd(&h[(key[q] >> shift) & (nbins - 1)], 1u);
+                if (j + q < d && ((key[q] ^ prefix) >> hi_shift) == 0) atomicAdd(&s.h[(key[q] >> shift) & (nbins - 1)], 1u);
         }
         __syncthreads();
         if (pass == 0 && !RK) {                       // keys >= 0x7f800000 (Inf/NaN) sit in the bins from 0xff0 up
             bool bad = false;
-            for (int b = 0xff0 + (int)tid; b < kHistBins; b += 1024) bad |= h[b] != 0;
-            if (bad) s_bad = 1;
+            for (int b = 0xff0 + (int)tid; b < kHistBins; b += 1024) bad |= s.h[b] != 0;
+            if (bad) s.bad = 1;
         }
-        const Pick p = block_pick(h, nbins, rank, part, res);
+        const Pick p = block_pick(s.h, nbins, rank, s.part, s.res);
         prefix |= p.bin << shift;
         rank = p.rank_in;
         ties = p.count;
     }
     // the rank-th entry with key == prefix, in index order
-    if (tid == 0) s_cut = 0xffffffffu;
+    if (tid == 0) s.cut = 0xffffffffu;
     __syncthreads();
     uint32_t seen = 0;
     for (uint32_t base = 0; base < d; base += 4096) {          // uniform trip count and exit
         const uint32_t j = base + tid * 4;
         uint32_t key[4];
-        keys_at(j, key);
+        slow_keys_at<VEC, RK>(g, d, k0, k1, j, key);
         const bool m0 = j < d && key[0] == prefix, m1 = j + 1 < d && key[1] == prefix;
         const bool m2 = j + 2 < d && key[2] == prefix, m3 = j + 3 < d && key[3] == prefix;
         const uint32_t mine = m0 + m1 + m2 + m3;
@@ -605,12 +642,12 @@ __global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ 
             const uint32_t up = __shfl_up(incl, o, 64);
             if ((int)lane >= o) incl += up;
         }
-        if (lane == 63) wtot[wave] = incl;
+        if (lane == 63) s.wtot[wave] = incl;
         __syncthreads();
         uint32_t before = seen, total = 0;
         for (int w = 0; w < 16; ++w) {
-            if (w < (int)wave) before += wtot[w];
-            total += wtot[w];
+            if (w < (int)wave) before += s.wtot[w];
+            total += s.wtot[w];
         }
         before += incl - mine;
         if (before < rank && rank <= before + mine) {
@@ -618,36 +655,193 @@ __global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ 
             if (m0 && --need == 0) idx = j;
             else if (m1 && --need == 0) idx = j + 1;
             else if (m2 && --need == 0) idx = j + 2;
-            s_cut = idx;
+            s.cut = idx;
         }
         seen += total;
         __syncthreads();
         if (seen >= rank) break;
     }
     __syncthreads();
-    if (tid == 0) {
-        RowDesc r = desc[row];
-        r.tau = prefix;
-        r.rank = rank;
-        r.ties = ties;
-        r.cutoff = s_cut;
-        r.dense = 1;
-        r.nonfinite = s_bad | r.nonfinite_acc;
-        r.nonfinite_acc = 0;
-        r.n_cand = 0;
-        clear_sure(r);
-        r.n_ties = 0;
-        r.n_list = 0;
-        r.have_prev = 0;
-        r.was_cold = 0;
-        r.mode = kCold;
-        if (RK) {                              // the band of a random-k draw is known without a prediction
-            r.lo = rk.fix_lo;
-            r.hi = rk.fix_hi;
-            r.mode = kWarm;
+    if (tid == 0) slow_write_result(desc, row, prefix, rank, ties, s.cut, s.bad, RK, rk);
+}
+
+// Meeting point of the B blocks of a row: true when all have arrived `target / B` times, false when the
+// wait ran out or another block has given up (the row is then flagged).  Every thread calls it.
+__device__ __forceinline__ bool slow_meet(SlowLds& s, uint32_t* __restrict__ sync, uint32_t target, uint32_t spin_limit) {
+    __threadfence();                           // my stores and atomics are out before my block arrives
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        atomicAdd(&sync[0], 1u);                // sync[0]: arrivals, sync[1]: some block has given up
+        uint32_t ok = 0;
+        for (uint32_t spin = 0; spin < spin_limit; ++spin) {
+            if (__hip_atomic_load(&sync[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
+            if (__hip_atomic_load(&sync[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) {
+                ok = 1;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(16);
         }
-        desc[row] = r;
+        if (!ok) atomicExch(&sync[1], 1u);
+        s.ok = ok;
     }
+    __syncthreads();
+    __threadfence();                           // what the other blocks wrote before arriving is visible from here on
+    return s.ok != 0;
+}
+
+// The B blocks of a row together.  Returns false when a wait ran out (the descriptor is untouched then).
+template <bool VEC, bool RK>
+__device__ bool slow_multi(SlowLds& s, const float* __restrict__ g, uint32_t d, uint32_t nwt, uint32_t row,
+                           RowDesc* __restrict__ desc, uint32_t k, RkDraw rk, uint32_t k0, uint32_t k1,
+                           uint32_t* __restrict__ ghist, uint32_t* __restrict__ gcnt, uint32_t* __restrict__ sync,
+                           uint32_t spin_limit) {
+    const uint32_t B = gridDim.x, b = blockIdx.x;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t tpb = (nwt + B - 1) / B;                     // wave tiles per block: a contiguous range of the row
+    const uint32_t t0 = min(b * tpb, nwt), t1 = min(t0 + tpb, nwt);
+    uint32_t meetings = 0;
+    // whatever an earlier, abandoned search left in the global histograms goes first
+    for (uint32_t q = b * 1024 + tid; q < kSlowHistWords; q += B * 1024) ghist[q] = 0;
+    if (tid == 0) s.bad = 0;
+    if (!slow_meet(s, sync, B * ++meetings, spin_limit)) return false;
+    uint32_t prefix = 0, rank = k, ties = 0, off = 0;
+#pragma unroll 1
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = digit_shift(pass), nbins = 1 << digit_bits(pass);
+        const int hi_shift = pass == 0 ? 31 : digit_shift(pass - 1);
+        for (int q = tid; q < nbins; q += 1024) s.h[q] = 0;
+        __syncthreads();
+        for (uint32_t t = t0 + wave; t < t1; t += 16) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
+                uint32_t key[4];
+                slow_keys_at<VEC, RK>(g, d, k0, k1, j, key);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const bool valid = j + q < d && ((key[q] ^ prefix) >> hi_shift) == 0;
+                    const uint32_t bin = (key[q] >> shift) & (uint32_t)(nbins - 1);
+                    wave_count(s.h, valid, bin, lane);
+                }
+            }
+        }
+        __syncthreads();
+        for (int q = tid; q < nbins; q += 1024) {
+            const uint32_t c = s.h[q];
+            if (c) atomicAdd(&ghist[off + q], c);
+        }
+        if (!slow_meet(s, sync, B * ++meetings, spin_limit)) return false;
+        if (pass == 0 && !RK) {                       // keys >= 0x7f800000 (Inf/NaN) sit in the bins from 0xff0 up
+            if (tid < 16 && ghist[0xff0 + tid] != 0) s.bad = 1;
+        }
+        const Pick p = block_pick(ghist + off, nbins, rank, s.part, s.res);
+        prefix |= p.bin << shift;
+        rank = p.rank_in;
+        ties = p.count;
+        off += nbins;
+    }
+    // ties inside my range, then the block whose range holds the rank-th tie walks it in index order
+    uint32_t mine = 0;
+    for (uint32_t t = t0 + wave; t < t1; t += 16) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
+            uint32_t key[4];
+            slow_keys_at<VEC, RK>(g, d, k0, k1, j, key);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) mine += (j + q < d && key[q] == prefix) ? 1u : 0u;
+        }
+    }
+    const uint32_t total = block_sum_u32(mine, s.wtot);         // valid on thread 0
+    if (tid == 0) gcnt[b] = total;
+    if (!slow_meet(s, sync, B * ++meetings, spin_limit)) return false;
+    uint32_t before = 0;
+    for (uint32_t q = 0; q < b; ++q) before += gcnt[q];
+    const uint32_t here = gcnt[b];
+    if (!(before < rank && rank <= before + here)) return true;  // uniform for the block
+    const uint32_t need = rank - before;
+    if (tid == 0) s.cut = 0xffffffffu;
+    __syncthreads();
+    uint32_t seen = 0;
+    for (uint32_t tb = t0; tb < t1; tb += 16) {                 // uniform trip count and exit
+        const uint32_t t = tb + wave;
+        uint64_t kb[4][4];
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
+            uint32_t key[4] = {0, 0, 0, 0};
+            if (t < t1) slow_keys_at<VEC, RK>(g, d, k0, k1, j, key);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                kb[u][q] = __ballot(t < t1 && j + q < d && key[q] == prefix);
+                cnt += (uint32_t)__popcll(kb[u][q]);
+            }
+        }
+        if (lane == 0) s.wtot[wave] = cnt;
+        __syncthreads();
+        uint32_t below = seen, all = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < (int)wave) below += s.wtot[w];
+            all += s.wtot[w];
+        }
+        if (below < need && need <= below + cnt) {              // uniform for the wave: the tie is in my tile
+            uint32_t n = need - below;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t cu = (uint32_t)(__popcll(kb[u][0]) + __popcll(kb[u][1]) + __popcll(kb[u][2]) + __popcll(kb[u][3]));
+                if (n != 0 && n <= cu) {
+                    const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
+                    const uint32_t lb = lanes_below(kb[u][0]) + lanes_below(kb[u][1]) + lanes_below(kb[u][2]) + lanes_below(kb[u][3]);
+                    uint32_t r = n > lb ? n - lb : 0u;           // 1-based rank among my own ties, 0: before me
+                    uint32_t own = 0;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if ((kb[u][q] >> lane) & 1) {
+                            ++own;
+                            if (own == r) s.cut = j + q;
+                        }
+                    }
+                    n = 0;                                      // found in this chunk
+                } else if (n != 0) {
+                    n -= cu;
+                }
+            }
+        }
+        seen += all;
+        __syncthreads();
+        if (seen >= need) break;
+    }
+    __syncthreads();
+    if (tid == 0) slow_write_result(desc, row, prefix, rank, ties, s.cut, s.bad, RK, rk);
+    return true;
+}
+
+template <bool VEC, bool RK>
+__global__ __launch_bounds__(1024) void k_slow_select(const float* __restrict__ src, size_t row_stride, uint32_t d,
+                                                       uint32_t nwt, uint32_t row0, RowDesc* __restrict__ desc, uint32_t k,
+                                                       RkDraw rk, uint32_t* __restrict__ slow_hist,
+                                                       uint32_t* __restrict__ slow_cnt, uint32_t* __restrict__ slow_sync,
+                                                       uint32_t spin_limit) {
+    __shared__ SlowLds s;
+    const uint32_t row = row0 + blockIdx.y;
+    if (desc[row].mode != kSlow) return;
+    const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
+    uint32_t k0 = 0, k1 = 0;
+    if (RK) {
+        const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
+        k0 = (uint32_t)stream;
+        k1 = (uint32_t)(stream >> 32);
+    }
+    if (gridDim.x == 1) {
+        slow_single<VEC, RK>(s, g, d, row, desc, k, rk, k0, k1);
+        return;
+    }
+    const bool done = slow_multi<VEC, RK>(s, g, d, nwt, row, desc, k, rk, k0, k1,
+                                          slow_hist + (size_t)blockIdx.y * kSlowHistWords,
+                                          slow_cnt + (size_t)blockIdx.y * kSlowMaxBlocks,
+                                          slow_sync + (size_t)blockIdx.y * 2, spin_limit);
+    if (!done && blockIdx.x == 0) slow_single<VEC, RK>(s, g, d, row, desc, k, rk, k0, k1);
 }
 
 // Random-k: completes the kept bitmap of each row once (tau, cut-off) are known.  k_filter has set the

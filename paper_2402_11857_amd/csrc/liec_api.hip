@@ -90,6 +90,12 @@ struct liec_ctx {
     uint32_t* ghist = nullptr;                 // [(N + 1) * kHistBins]
     uint32_t* lhist = nullptr;                 // [(N + 1) * 2 * kListBins]
     uint32_t* tiebuf = nullptr;                // [(N + 1) * kTieCap]
+    // general (degenerate-row) search: B thread blocks share a row when B * rows fit the chip
+    uint32_t slow_bw = 1, slow_bs = 1;         // blocks per worker row / for the server's vector
+    uint32_t slow_spin = 1u << 16;             // bound, in polls, of the waits between those blocks
+    uint32_t* slow_hist = nullptr;             // [rows that share * kSlowHistWords] digit histograms
+    uint32_t* slow_cnt = nullptr;              // [rows that share * kSlowMaxBlocks] ties per block
+    uint32_t* slow_sync = nullptr;             // [rows that share * 2] arrivals, give-up flag
     int64_t scratch_bytes = 0;
 
     // blockwise scaled sign (Definition 5): block table and its scratch, set by liec_set_blocks
@@ -179,6 +185,9 @@ void free_scratch(liec_ctx* c) {
     (void)hipFree(c->ghist);
     (void)hipFree(c->lhist);
     (void)hipFree(c->tiebuf);
+    (void)hipFree(c->slow_hist);
+    (void)hipFree(c->slow_cnt);
+    (void)hipFree(c->slow_sync);
 }
 
 bool valid_comp(int c) {
@@ -274,10 +283,19 @@ void launch_select(Launcher& L, const float* src, size_t row_stride, uint32_t ro
     k_list_ties<<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, k, c->lhist, c->tiebuf);
     L.end();
     L.begin(slot0 + 7);
-    k_list_finish<<<rows, kFinishBlock, 0, st>>>(row0, c->desc, c->lhist, c->tiebuf, c->list, c->cap, k, rk.fix_lo, rk.fix_hi);
+    // scratch of the general search: the worker rows' slots come first, then the server's
+    const bool server_side = row0 != 0;
+    const uint32_t slow_b = server_side ? c->slow_bs : c->slow_bw;
+    const size_t slow_slot = server_side && c->slow_bw > 1 ? (size_t)c->N : 0;
+    uint32_t* const shist = slow_b > 1 ? c->slow_hist + slow_slot * kSlowHistWords : nullptr;
+    uint32_t* const scnt = slow_b > 1 ? c->slow_cnt + slow_slot * kSlowMaxBlocks : nullptr;
+    uint32_t* const ssync = slow_b > 1 ? c->slow_sync + slow_slot * 2 : nullptr;
+    k_list_finish<<<rows, kFinishBlock, 0, st>>>(row0, c->desc, c->lhist, c->tiebuf, c->list, c->cap, k, rk.fix_lo, rk.fix_hi,
+                                                 ssync);
     L.end();
     L.begin(slot0 + 8);
-    k_slow_select<VEC, RK><<<rows, 1024, 0, st>>>(src, row_stride, d, row0, c->desc, k, rk);
+    k_slow_select<VEC, RK><<<dim3(slow_b, rows), 1024, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, k, rk, shist, scnt,
+                                                                 ssync, c->slow_spin);
     L.end();
     if (RK) {
         L.begin(slot0 + 9);
@@ -514,6 +532,21 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->ghist, rows * kHistBins);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->lhist, rows * 2 * kListBins);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->tiebuf, rows * kTieCap);
+    if (e == hipSuccess && any_topk) {
+        // blocks that share a row meet inside the kernel, so all of them must be resident at once:
+        // at most one per compute unit
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || cus < 1) cus = 1;
+        c->slow_bw = clampu((uint32_t)cus / un, 1u, (uint32_t)kSlowMaxBlocks);
+        c->slow_bs = clampu((uint32_t)cus, 1u, (uint32_t)kSlowMaxBlocks);
+        const size_t slots = (c->slow_bw > 1 ? (size_t)N : 0) + (c->slow_bs > 1 ? 1 : 0);
+        if (slots) {
+            e = dev_alloc(c, &c->slow_hist, slots * kSlowHistWords);
+            if (e == hipSuccess) e = dev_alloc(c, &c->slow_cnt, slots * kSlowMaxBlocks);
+            if (e == hipSuccess) e = dev_alloc(c, &c->slow_sync, slots * 2);
+            if (e == hipSuccess) e = hipMemsetAsync(c->slow_sync, 0, slots * 2 * sizeof(uint32_t), c->stream);
+        }
+    }
     if (e == hipSuccess) {
         std::vector<RowDesc> init(rows);
         std::memset(init.data(), 0, rows * sizeof(RowDesc));
@@ -609,6 +642,12 @@ liec_status liec_force_search_mode(liec_ctx* c, int32_t mode) {
         c->broken = true;
         return LIEC_EDEVICE;
     }
+    return LIEC_OK;
+}
+
+liec_status liec_set_search_wait(liec_ctx* c, int32_t polls) {
+    if (!c || polls < 0) return LIEC_EINVAL;
+    c->slow_spin = (uint32_t)polls;
     return LIEC_OK;
 }
 

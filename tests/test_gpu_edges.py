@@ -162,6 +162,47 @@ def test_quantised_gradients_with_thousands_of_ties_at_the_threshold(wc, sc):
             assert info.nonfinite == 0 and info.slow_rows == 0, f"step {t}: {info.slow_rows} rows took the slow search"
 
 
+@pytest.mark.parametrize("kind", ["constant", "mostly_zero", "four_levels", "one_level_rest_noise"])
+@pytest.mark.parametrize("wait", [None, 0])
+def test_degenerate_rows_at_a_size_where_thread_blocks_share_a_row(kind, wait):
+    """Rows whose threshold is shared by more entries than the candidate list holds take the general search,
+    in which several thread blocks split a row (wait=None) or, when their bounded wait for one another runs
+    out (wait=0 forces that), one block does it alone.  Either way the result is the oracle's."""
+    import oracle
+    from paper_2402_11857_amd import LiecContext
+
+    N, d, k = 3, 2_600_003, 26_000
+    say(f"case degenerate rows, shared search: {kind} wait={wait}")
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(11)
+    x = torch.zeros((N, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    xo, eo = np.zeros((N, d), dtype=np.float32), np.zeros(d, dtype=np.float32)
+    with LiecContext(N, d, "topk", "topk", k, k, 0.1) as ctx:
+        if wait is not None:
+            ctx.set_search_wait(wait)
+        for t in range(2):
+            if kind == "constant":
+                g = torch.full((N, d), 0.5, dtype=torch.float32)
+                g[:, t::3] *= -1
+            elif kind == "mostly_zero":                     # fewer non-zeros than k: the threshold is zero
+                g = torch.zeros((N, d), dtype=torch.float32)
+                idx = torch.randint(0, d, (N, k // 3), generator=gen)
+                g.scatter_(1, idx, torch.randn((N, k // 3), generator=gen))
+            elif kind == "four_levels":
+                g = torch.randint(-2, 2, (N, d), generator=gen).to(torch.float32)
+            else:                                           # 99 % of the row on one magnitude above the noise
+                g = torch.randn((N, d), generator=gen) * 1e-3
+                mask = torch.rand((N, d), generator=gen) < 0.99
+                g[mask] = 1.0
+            g = g.to(DEV).contiguous()
+            ctx.step(g, x, e)
+            oracle.step(g.cpu().numpy(), xo, eo, "topk", "topk", 0.1, k, k)
+            assert H.bit_equal(e.cpu().numpy(), eo), f"step {t}: server error"
+            assert H.bit_equal(x.cpu().numpy(), xo), f"step {t}: models"
+            assert ctx.info().slow_rows >= N, "the worker rows must have taken the general search"
+
+
 def test_constant_rows_are_reported_as_slow_rows():
     """Rows whose entries all share one magnitude cannot be listed: they take the general search, and the
     context says so."""
