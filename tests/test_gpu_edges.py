@@ -59,11 +59,12 @@ def test_random_shapes_and_operator_pairs(case):
         assert ctx.info().nonfinite == 0
 
 
-@pytest.mark.parametrize("case", range(40))
-def test_random_chains_with_drift_ties_and_averaging_iterations(case):
-    """Seeded chains of 4-8 iterations of Algorithm 1 as a whole (liec_iteration; period 0, 3 or 4) over random
-    shapes up to 3 million columns, random k (also 1, d - 1, d), every operator pair, with the gradient scale
-    drifting or jumping between iterations and ties injected, compared bit for bit after every iteration."""
+def _random_chain(case, degenerate):
+    """One seeded chain of 4-8 iterations of Algorithm 1 as a whole (liec_iteration; period 0, 3 or 4) on a random
+    shape up to 3 million columns, random k (also 1, d - 1, d) and operator pair, with the gradient scale drifting
+    or jumping between iterations and ties injected; compared bit for bit after every iteration.  With
+    `degenerate` the gradients are also cut to a few mantissa bits, made constant, made sparse or rounded to a
+    few levels, and in half of the cases the general search runs with its single-block fallback forced."""
     import oracle
     from paper_2402_11857_amd import LiecContext
 
@@ -93,8 +94,10 @@ def test_random_chains_with_drift_ties_and_averaging_iterations(case):
     period = int(rng.choice([0, 0, 3, 4]))
     drift = str(rng.choice(["none", "none", "slow", "jump"]))
     ties = rng.random() < 0.3
+    kind = str(rng.choice(["quant", "const", "sparse", "levels"])) if degenerate else "none"
+    wait = 0 if degenerate and rng.random() < 0.5 else None
     say(f"case chain {case}: N={N} d={d} {wc}/{sc} k={wk}/{sk} lr={lr} blocks={len(off) - 1} steps={steps} "
-        f"period={period} drift={drift} ties={ties}")
+        f"period={period} drift={drift} ties={ties} gradients={kind} wait={wait}")
     w = workloads.scaled(WL["c2_topk_mid"], N=N, d=d, worker_comp=wc, server_comp=sc, worker_k=wk, server_k=sk, lr=lr)
     src = workloads.GradientSource(w, seed=case, device=DEV)
     x = torch.zeros((N, d), dtype=torch.float32, device=DEV)
@@ -103,6 +106,8 @@ def test_random_chains_with_drift_ties_and_averaging_iterations(case):
     draw, scale = 0, 1.0
     with LiecContext(N, d, wc, sc, wk, sk, lr) as ctx:
         ctx.set_random(case, 0)
+        if wait is not None:
+            ctx.set_search_wait(wait)
         if "blocksign" in (wc, sc):
             ctx.set_blocks(off)
         for t in range(steps):
@@ -116,6 +121,16 @@ def test_random_chains_with_drift_ties_and_averaging_iterations(case):
             if ties:
                 g = workloads.inject_ties(g, seed=t, frac_zero=float(rng.choice([0.0, 0.2, 0.9])),
                                           frac_dup=float(rng.choice([0.0, 0.3])))
+            if kind == "quant":                  # 7, 5, 2 or 0 mantissa bits
+                g = (g.contiguous().view(torch.int32) & -(1 << int(rng.choice([16, 18, 21, 23])))).view(torch.float32)
+            elif kind == "const" and rng.random() < 0.7:
+                g = torch.full_like(g, 0.5)
+                g[:, int(rng.integers(0, 3))::3] *= -1
+            elif kind == "sparse":
+                keep = torch.rand(g.shape, device=g.device) < float(rng.choice([1e-4, 1e-3, 1e-2]))
+                g = torch.where(keep, g, torch.zeros_like(g))
+            elif kind == "levels":
+                g = torch.round(g * float(rng.choice([0.7, 2.0, 8.0])))
             g = g.contiguous()
             gh = g.cpu().numpy()
             ctx.iteration(t, period, g, x, e)
@@ -127,6 +142,16 @@ def test_random_chains_with_drift_ties_and_averaging_iterations(case):
             assert H.bit_equal(e.cpu().numpy(), eo), f"iteration {t}: server error"
             assert H.bit_equal(x.cpu().numpy(), xo), f"iteration {t}: models"
         assert ctx.info().nonfinite == 0
+
+
+@pytest.mark.parametrize("case", range(40))
+def test_random_chains_with_drift_ties_and_averaging_iterations(case):
+    _random_chain(case, degenerate=False)
+
+
+@pytest.mark.parametrize("case", range(100_000, 100_040))
+def test_random_chains_on_degenerate_gradients(case):
+    _random_chain(case, degenerate=True)
 
 
 @pytest.mark.parametrize("wc,sc", [("topk", "topk"), ("topk", "sign")])
