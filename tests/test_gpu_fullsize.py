@@ -18,9 +18,9 @@ pytestmark = GPU_MARKS
 
 
 # ---- full-size configurations, in the launch configuration the bench times -------------------
-def _full_size_steps(name, steps, seed=0):
+def _full_size_steps(name, steps, seed=0, mantissa_bits=23, expect_slow_rows=None):
     w = WL[name]
-    say(f"case full size {name} N={w.N} d={w.d} steps={steps}")
+    say(f"case full size {name} N={w.N} d={w.d} steps={steps} mantissa bits={mantissa_bits}")
     src = workloads.GradientSource(w, seed=seed, device=DEV)
     x = torch.zeros((w.N, w.d), dtype=torch.float32, device=DEV)
     e = torch.zeros(w.d, dtype=torch.float32, device=DEV)
@@ -30,6 +30,8 @@ def _full_size_steps(name, steps, seed=0):
         ctx.set_random(seed + 1000, 0)
         for t in range(steps):
             g = src.grads(t)
+            if mantissa_bits < 23:                   # gradients as a low-precision backward pass leaves them
+                g = (g.view(torch.int32) & -(1 << (23 - mantissa_bits))).view(torch.float32).contiguous()
             ctx.step(g, x, e)
             gh = g.cpu().numpy()
             del g
@@ -37,6 +39,8 @@ def _full_size_steps(name, steps, seed=0):
                                                        w.worker_k, w.server_k, rng=(seed + 1000, t))
             say(f"  oracle step {t} done")
             check_descriptors(ctx, w, wdesc, sdesc, gh, v, f"{name} step {t}")
+            if expect_slow_rows is not None:
+                assert ctx.info().slow_rows == expect_slow_rows, f"{name} step {t}: rows in the general search"
             del P, gh
             eg = e.cpu().numpy()
             assert H.rel_err(eg, eo) <= (H.TOL_STEP if t == 0 else H.TOL_CHAIN)
@@ -65,3 +69,9 @@ def test_full_size_c5_vgg16_sign():
 
 def test_full_size_c4_resnet50_randk():
     _full_size_steps("c4_resnet50_randk", steps=2)
+
+
+def test_full_size_c4_resnet50_topk_on_bf16_like_gradients():
+    """7 mantissa bits: tens of thousands of entries of a row share the threshold; no row may need the
+    general search."""
+    _full_size_steps("c4_resnet50_topk", steps=2, mantissa_bits=7, expect_slow_rows=0)
