@@ -789,10 +789,12 @@ __device__ bool slow_multi(SlowLds& s, const float* __restrict__ g, uint32_t d, 
             uint32_t n = need - below;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const uint32_t cu = (uint32_t)(__popcll(kb[u][0]) + __popcll(kb[u][1]) + __popcll(kb[u][2]) + __popcll(kb[u][3]));
+                const uint32_t cu =
+                    (uint32_t)(__popcll(kb[u][0]) + __popcll(kb[u][1]) + __popcll(kb[u][2]) + __popcll(kb[u][3]));
                 if (n != 0 && n <= cu) {
                     const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
-                    const uint32_t lb = lanes_below(kb[u][0]) + lanes_below(kb[u][1]) + lanes_below(kb[u][2]) + lanes_below(kb[u][3]);
+                    const uint32_t lb = lanes_below(kb[u][0]) + lanes_below(kb[u][1]) + lanes_below(kb[u][2]) +
+                                        lanes_below(kb[u][3]);
                     uint32_t r = n > lb ? n - lb : 0u;           // 1-based rank among my own ties, 0: before me
                     uint32_t own = 0;
 #pragma unroll

@@ -248,7 +248,8 @@ void launch_select(Launcher& L, const float* src, size_t row_stride, uint32_t ro
     // random-k with a thin band: clear the kept bitmap, then walk the priorities above the band
     // few, long-lived blocks (every wave ends with a list flush): one per 32768 words to invert
     const uint64_t inv_words = 2ull * (0x80000000ull - rk.fix_lo);
-    const dim3 inv_grid((uint32_t)std::min<uint64_t>(std::max<uint64_t>(inv_words / 32768, 128), 1024), rows), zero_grid(std::min<uint32_t>((c->nwt * 32 + kBlock - 1) / kBlock, 4096u), rows);
+    const dim3 inv_grid((uint32_t)std::min<uint64_t>(std::max<uint64_t>(inv_words / 32768, 128), 1024), rows);
+    const dim3 zero_grid(std::min<uint32_t>((c->nwt * 32 + kBlock - 1) / kBlock, 4096u), rows);
     L.begin(slot0 + 0);
     if (RK && rk_inverse) {
         k_rk_zero<<<zero_grid, kBlock, 0, st>>>(c->nwt, row0, c->desc, kWarm, c->bits);
