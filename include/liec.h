@@ -86,7 +86,7 @@ typedef struct {
  *   lr          learning rate eta, finite
  * Allocates the context's device scratch: 4d bytes for v; N * d / 8 for sign or
  * random-k bitmaps; with top-k or random-k on either side also (N + 1) * (d / 2 +
- * 32 KiB) for the candidate lists, N * d / 32 for the group bitmap and about
+ * 32 KiB) for the candidate lists, N * d / 32 (or / 128) for the group bitmap and about
  * 120 KiB per row of histograms (liec_scratch_bytes reports the total).  The
  * context belongs to the HIP device that is current at this call: every later call
  * on it makes that device current for its own duration and puts the caller's back.

@@ -9,10 +9,13 @@ namespace liec {
 // among its ties are found without sorting:
 //   1. k_filter streams the row once against a band [lo, hi) of keys expected to hold tau:
 //      keys >= hi are only counted, keys inside the band are appended to a candidate list
-//      (key, index), and a group bitmap is written for the aggregation kernel: 4 words of 64 bits
-//      per wave tile, bit l of word u set when any of the 4 columns 1024t + 256u + 4l .. + 3 has
-//      key >= lo (a quarter of the bytes a per-column bitmap would take; writes are what a
-//      read stream pays most for).
+//      (key, index), and a group bitmap is written for the aggregation kernel, in one of two
+//      forms the host picks from k / d.  Fine: 4 words of 64 bits per wave tile, bit l of word u
+//      set when any of the 4 columns 1024t + 256u + 4l .. + 3 has key >= lo.  Coarse: one word
+//      per wave tile, bit 16u + m set when any of the 16 columns 1024t + 256u + 16m .. + 15 (one
+//      64-byte line, the unit a gather fetches anyway) has one -- 8 bytes written per 4 KiB read
+//      (writes are what a read stream pays most for); it pays when candidates are dense enough
+//      that most waves have a flagged lane in every chunk anyway.
 //      The band is predicted from the previous step's tau (kWarm).  It is usable when the list
 //      did not overflow and rank k falls inside it (band_ok); when there is no prediction, or it is not
 //      usable, the band becomes the first-radix-digit bin holding rank k, found by k_hist0 +
@@ -26,6 +29,18 @@ namespace liec {
 // k_slow_select) change a row's mode.  The host always enqueues the same kernels.
 // `row0` is added to blockIdx.y to address per-row state (the server's vector uses row N).
 // ---------------------------------------------------------------------------------------------
+// Bit m of the result: some lane of 4m .. 4m + 3 has its bit set in the ballot (those four lanes own one
+// 64-byte line of the row).
+__device__ __forceinline__ uint64_t any_of_four_lanes(uint64_t b) {
+    b |= b >> 1;
+    b |= b >> 2;
+    b &= 0x1111111111111111ull;                                 // bit 4m: any lane of the m-th four
+    b = (b | (b >> 3)) & 0x0303030303030303ull;                 // then squeeze the 16 bits together
+    b = (b | (b >> 6)) & 0x000f000f000f000full;
+    b = (b | (b >> 12)) & 0x000000ff000000ffull;
+    return (b | (b >> 24)) & 0xffffull;
+}
+
 // One chunk (256 columns, 4 per lane) of the filter: updates the per-lane count of keys >= hi and the
 // running maximum key, returns the ballot of "any of my 4 columns has key >= lo" and, per component,
 // the ballots of the candidates lo <= key < hi.  FULL: every column of the chunk is below d.
@@ -60,7 +75,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
                                                     uint32_t nwt, uint32_t row0, RowDesc* __restrict__ desc,
                                                     uint32_t expect_mode, uint64_t* __restrict__ gbits,
                                                     uint16_t* __restrict__ kbits, uint2* __restrict__ list, uint32_t cap,
-                                                    RkDraw rk) {
+                                                    RkDraw rk, bool coarse) {
     __shared__ uint2 stage[4][kStage];
     __shared__ uint32_t wsure[4];
     const uint32_t row = row0 + blockIdx.y;
@@ -85,7 +100,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
             for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
         }
         const bool full = (t + 1) * (uint32_t)kWaveTile <= d;  // wave-uniform
-        uint64_t word = 0;                                      // lane u (< 4) ends up holding group word u
+        uint64_t word = 0;                                      // fine: lane u (< 4) ends up holding group word u;
+                                                                // coarse: the tile's one group word (wave-uniform)
         uint32_t sure16 = 0;                                    // RK: bit 4u + q: my column q of chunk u has key >= hi
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -104,7 +120,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
             uint32_t cand4, hi4;
             const uint64_t any_lo = full ? filter_chunk<true>(keys, j, d, lo, hi, cand4, any_cand, n_hi, kmax, hi4)
                                          : filter_chunk<false>(keys, j, d, lo, hi, cand4, any_cand, n_hi, kmax, hi4);
-            word = lane == (uint32_t)u ? any_lo : word;
+            if (coarse) word |= any_of_four_lanes(any_lo) << (16 * u);
+            else word = lane == (uint32_t)u ? any_lo : word;
             sure16 |= hi4 << (4 * u);
             if (any_cand) {                                     // wave-uniform
                 uint64_t bc[4];
@@ -133,7 +150,11 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
         if (RK) {
             kbits[((size_t)row * nwt + t) * 64 + lane] = (uint16_t)sure16;
         } else {
-            if (gbits && lane < 4) gbits[((size_t)blockIdx.y * nwt + t) * 4 + lane] = word;
+            if (gbits && coarse) {
+                if (lane == 0) gbits[(size_t)blockIdx.y * nwt + t] = word;
+            } else if (gbits && lane < 4) {
+                gbits[((size_t)blockIdx.y * nwt + t) * 4 + lane] = word;
+            }
         }
     }
     // keys at or above 0x7f800000 are Inf / NaN (magnitude keys only: priorities use the whole range)

@@ -41,8 +41,9 @@ __device__ __forceinline__ float message_of(float g, uint32_t j, float scale, ui
 // |v| (fp64) for the server's scaled-sign operator.  grid = blocks; waves stride over wave tiles.
 //   WC == kSign / kBlockSign  read the packed sign bits instead of the gradients (blockwise: the scale
 //                   comes from the column's block);
-//   WC == kTopk     reads each row's group bitmap and fetches only the flagged groups of 4
-//                   gradients, testing them against (tau, cut-off); per-lane sums live in LDS;
+//   WC == kTopk     reads each row's group bitmap (one bit per 4 columns, or `coarse`: per 64-byte line) and
+//                   fetches only the flagged groups, testing their gradients against (tau, cut-off); per-lane
+//                   sums live in LDS;
 //   WC == kRandk    reads each row's kept bitmap and fetches only the groups of 4 gradients that hold a
 //                   kept column;
 //   WC == kIdentity reads the gradients.
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
                                                        int N, uint32_t d, uint32_t nwt, float inv_n,
                                                        const RowDesc* __restrict__ desc, const float* __restrict__ e_in,
                                                        float* __restrict__ v_out, double* __restrict__ srv_partial,
-                                                       BlockTable bt) {
+                                                       BlockTable bt, bool coarse) {
     __shared__ double lds_w[4];
     __shared__ float accs[(WC == kTopk || WC == kRandk) ? 16 * kBlock : 1];
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -112,13 +113,19 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
             float* my = accs + threadIdx.x;                    // slot b of this lane: my[b * kBlock]
 #pragma unroll
             for (int b = 0; b < 16; ++b) my[b * kBlock] = 0.f;
-            const uint64_t* __restrict__ gw = gbits + (size_t)t * 4;   // the tile's 4 group words of row 0
-            const size_t grow = (size_t)nwt * 4;
+            // the tile's group word(s) of row 0: one (coarse: a bit per 64-byte line) or four (a bit per lane)
+            const uint64_t* __restrict__ gw = gbits + (coarse ? (size_t)t : (size_t)t * 4);
+            const size_t grow = coarse ? (size_t)nwt : (size_t)nwt * 4;
+            const uint32_t four = lane >> 2;                   // my 64-byte line inside a chunk
             for (int i = 0; i < N; ++i) {
                 const float* __restrict__ gi = grads + (size_t)i * d;
                 const uint32_t tau = desc[i].tau, cut = desc[i].cutoff;
-                uint32_t mask = 0xfu;                          // bit u: this lane's group of chunk u is flagged
-                if (!desc[i].dense) {
+                uint32_t mask = 0xfu;                          // bit u: my line of chunk u holds a candidate
+                if (!desc[i].dense && coarse) {
+                    const uint64_t w = gw[(size_t)i * grow] >> four;
+                    mask = (uint32_t)(w & 1) | (uint32_t)((w >> 16) & 1) << 1 | (uint32_t)((w >> 32) & 1) << 2 |
+                           (uint32_t)((w >> 48) & 1) << 3;
+                } else if (!desc[i].dense) {
                     const uint64_t* __restrict__ w = gw + (size_t)i * grow;
                     mask = (uint32_t)((w[0] >> lane) & 1) | (uint32_t)((w[1] >> lane) & 1) << 1 |
                            (uint32_t)((w[2] >> lane) & 1) << 2 | (uint32_t)((w[3] >> lane) & 1) << 3;

@@ -98,30 +98,41 @@ __global__ __launch_bounds__(kBlock) void k_topk_count(const float* __restrict__
     }
 }
 
-// One block of 1024 threads: exclusive scan of n counts in place; *total receives the sum.
+// One block of 1024 threads: exclusive scan of n counts in place; *total receives the sum.  The block walks
+// the array 4096 counts at a time (4 consecutive ones per thread, so the accesses coalesce).
 __global__ __launch_bounds__(1024) void k_scan_u32(uint32_t* __restrict__ v, uint32_t n, uint32_t* __restrict__ total) {
-    __shared__ uint32_t part[1024];
-    const uint32_t per = (n + 1023) / 1024, lo = threadIdx.x * per, hi = min(lo + per, n);
-    uint32_t sum = 0;
-    for (uint32_t q = lo; q < hi; ++q) sum += v[q];
-    part[threadIdx.x] = sum;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (int q = 0; q < 1024; ++q) {
-            const uint32_t c = part[q];
-            part[q] = run;
-            run += c;
+    __shared__ uint32_t wsum[16];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t carry = 0;
+    for (uint32_t base = 0; base < n; base += 4096) {          // uniform trip count
+        const uint32_t i = base + tid * 4;
+        uint32_t a[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) a[q] = i + q < n ? v[i + q] : 0u;
+        const uint32_t s = a[0] + a[1] + a[2] + a[3];
+        uint32_t incl = s;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t up = __shfl_up(incl, o, 64);
+            if ((int)lane >= o) incl += up;
         }
-        *total = run;
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        uint32_t before = carry, all = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < (int)wave) before += wsum[w];
+            all += wsum[w];
+        }
+        uint32_t run = before + incl - s;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (i + q < n) v[i + q] = run;
+            run += a[q];
+        }
+        carry += all;
+        __syncthreads();
     }
-    __syncthreads();
-    uint32_t run = part[threadIdx.x];
-    for (uint32_t q = lo; q < hi; ++q) {
-        const uint32_t c = v[q];
-        v[q] = run;
-        run += c;
-    }
+    if (tid == 0) *total = carry;
 }
 
 template <bool VEC>
