@@ -86,7 +86,7 @@ typedef struct {
  *   lr          learning rate eta, finite
  * Allocates the context's device scratch: 4d bytes for v; N * d / 8 for sign or
  * random-k bitmaps; with top-k or random-k on either side also (N + 1) * (d / 2 +
- * 32 KiB) for the candidate lists, N * d / 32 (or / 128) for the group bitmap and about
+ * 32 KiB) for the candidate lists, N * d / 32 for the group bitmap and about
  * 120 KiB per row of histograms (liec_scratch_bytes reports the total).  The
  * context belongs to the HIP device that is current at this call: every later call
  * on it makes that device current for its own duration and puts the caller's back.
@@ -278,6 +278,16 @@ liec_status liec_force_search_mode(liec_ctx *ctx, int32_t mode);
  * tests reach that path.  LIEC_EINVAL for a negative value.
  */
 liec_status liec_set_search_wait(liec_ctx *ctx, int32_t polls);
+
+/*
+ * Testing and tuning aid for top-k workers: the form of the candidate bitmap that
+ * the threshold search leaves for the aggregation -- 0: one bit per 4 columns,
+ * 1: one bit per 64-byte line (16 columns).  liec_create* picks it from d (the
+ * second form from 4e7 columns up, where it measured faster); results do not
+ * depend on it.  Takes effect with the next step.  LIEC_EINVAL for another value
+ * or when the workers' operator is not top-k.
+ */
+liec_status liec_set_group_bitmap(liec_ctx *ctx, int32_t per_line);
 
 /* Synchronises the stream and copies the scalars of the last step to the host
  * struct `info`.  Returns LIEC_ENONFINITE (with `info` filled) if that step met

@@ -100,6 +100,8 @@ def lib():
         L.liec_force_search_mode.argtypes = [vp, i32]
         L.liec_set_search_wait.restype = ctypes.c_int
         L.liec_set_search_wait.argtypes = [vp, i32]
+        L.liec_set_group_bitmap.restype = ctypes.c_int
+        L.liec_set_group_bitmap.argtypes = [vp, i32]
         L.liec_get_info.restype = ctypes.c_int
         L.liec_get_info.argtypes = [vp, ctypes.POINTER(LiecInfo)]
         L.liec_get_worker_desc.restype = ctypes.c_int
@@ -310,6 +312,9 @@ class LiecContext:
 
     def set_search_wait(self, polls: int) -> None:
         _check(lib().liec_set_search_wait(self._h, polls), "liec_set_search_wait")
+
+    def set_group_bitmap(self, per_line: int) -> None:
+        _check(lib().liec_set_group_bitmap(self._h, per_line), "liec_set_group_bitmap")
 
     def info(self) -> LiecInfo:
         return liec_get_info(self._h)[0]

@@ -10,12 +10,12 @@ namespace liec {
 //   1. k_filter streams the row once against a band [lo, hi) of keys expected to hold tau:
 //      keys >= hi are only counted, keys inside the band are appended to a candidate list
 //      (key, index), and a group bitmap is written for the aggregation kernel, in one of two
-//      forms the host picks from k / d.  Fine: 4 words of 64 bits per wave tile, bit l of word u
+//      forms the host picks from the row length.  Fine: 4 words of 64 bits per wave tile, bit l of word u
 //      set when any of the 4 columns 1024t + 256u + 4l .. + 3 has key >= lo.  Coarse: one word
 //      per wave tile, bit 16u + m set when any of the 16 columns 1024t + 256u + 16m .. + 15 (one
 //      64-byte line, the unit a gather fetches anyway) has one -- 8 bytes written per 4 KiB read
-//      (writes are what a read stream pays most for); it pays when candidates are dense enough
-//      that most waves have a flagged lane in every chunk anyway.
+//      (writes are what a read stream pays most for); measured faster for rows of 48M columns
+//      and more, slower for 25M.
 //      The band is predicted from the previous step's tau (kWarm).  It is usable when the list
 //      did not overflow and rank k falls inside it (band_ok); when there is no prediction, or it is not
 //      usable, the band becomes the first-radix-digit bin holding rank k, found by k_hist0 +

@@ -85,7 +85,7 @@ struct liec_ctx {
     RkState* rk_state = nullptr;               // random-k: seed and number of the next draw (device)
     uint32_t rk_wlo = 0, rk_whi = 0, rk_slo = 0, rk_shi = 0;   // random-k: threshold bands of the worker / server draws
     bool rk_winv = false, rk_sinv = false;     // random-k: the band is thin enough to walk the priorities instead of the columns
-    uint64_t* gbits = nullptr;                 // [N * nwt * (gb_coarse ? 1 : 4)] group bitmap of the candidates (top-k workers)
+    uint64_t* gbits = nullptr;                 // [N * nwt * 4] group bitmap of the candidates (top-k workers), either form
     bool gb_coarse = false;                    // one bit per 64-byte line instead of one per 4 columns
     uint2* list = nullptr;                     // [(N + 1) * cap] candidates (key, index)
     uint32_t* ghist = nullptr;                 // [(N + 1) * kHistBins]
@@ -529,11 +529,13 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
         e = dev_alloc(c, &c->bits, (size_t)N * c->nwt * 64);
     if (e == hipSuccess) e = dev_alloc(c, &c->rk_state, 1);
     if (e == hipSuccess) e = hipMemsetAsync(c->rk_state, 0, sizeof(RkState), c->stream);
-    // the coarse group bitmap saves the filter a quarter of its stores but makes the aggregation fetch for four
-    // times as many lanes: it pays once candidates are dense enough (measured: k / d of 0.5 % yes, 0.1 % no)
-    c->gb_coarse = worker_comp == LIEC_COMP_TOPK && worker_k * 400 >= d;
+    // Which form of the group bitmap: measured over 13 shapes (N 8..64, d 25M..138M, k/d 0.1 % and 0.5 %, three
+    // gradient recipes) the row length decides -- one bit per 64-byte line is 1-2 % of a step faster from
+    // d = 48M up (filter -3 %, aggregation -10..20 %), even at 36M, and up to 1 % slower at 25M (the
+    // aggregation fetches for four times as many lanes and has less bitmap to save on).
+    c->gb_coarse = worker_comp == LIEC_COMP_TOPK && d >= 40000000;
     if (e == hipSuccess && worker_comp == LIEC_COMP_TOPK)
-        e = dev_alloc(c, &c->gbits, (size_t)N * c->nwt * (c->gb_coarse ? 1 : 4));
+        e = dev_alloc(c, &c->gbits, (size_t)N * c->nwt * 4);      // room for either form
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->list, rows * c->cap);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->ghist, rows * kHistBins);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->lhist, rows * 2 * kListBins);
@@ -648,6 +650,12 @@ liec_status liec_force_search_mode(liec_ctx* c, int32_t mode) {
         c->broken = true;
         return LIEC_EDEVICE;
     }
+    return LIEC_OK;
+}
+
+liec_status liec_set_group_bitmap(liec_ctx* c, int32_t per_line) {
+    if (!c || (per_line != 0 && per_line != 1) || c->worker_comp != kTopk) return LIEC_EINVAL;
+    c->gb_coarse = per_line != 0;              // the buffer always has room for the finer form
     return LIEC_OK;
 }
 

@@ -46,6 +46,8 @@ def test_random_shapes_and_operator_pairs(case):
     xo, eo = np.zeros((N, d), dtype=np.float32), np.zeros(d, dtype=np.float32)
     with LiecContext(N, d, wc, sc, wk, sk, lr) as ctx:
         ctx.set_random(case, 5)
+        if wc == "topk":
+            ctx.set_group_bitmap((case // 5) & 1)    # both forms of the candidate bitmap
         if "blocksign" in (wc, sc):
             ctx.set_blocks(off)
         for t in range(3):
@@ -108,6 +110,8 @@ def _random_chain(case, degenerate):
         ctx.set_random(case, 0)
         if wait is not None:
             ctx.set_search_wait(wait)
+        if wc == "topk":
+            ctx.set_group_bitmap(case & 1)           # both forms of the candidate bitmap
         if "blocksign" in (wc, sc):
             ctx.set_blocks(off)
         for t in range(steps):
