@@ -25,8 +25,9 @@ namespace liec {
 //      4096 of them through a buffer, more by a radix select over the listed indices).
 //   3. Rows whose band the list cannot hold (constant or near-constant rows) take k_slow_select.
 // All decisions are taken on the device per row, each kernel re-deriving from the row's counters
-// whether it has work; only the one-block-per-row kernels (k_pick_band, k_list_finish,
-// k_slow_select) change a row's mode.  The host always enqueues the same kernels.
+// whether it has work; a row's mode is changed only where one thread speaks for the row (k_pick_band,
+// k_list_finish, the block of k_slow_select that finds the cut-off).  The host always enqueues the same
+// kernels.
 // `row0` is added to blockIdx.y to address per-row state (the server's vector uses row N).
 // ---------------------------------------------------------------------------------------------
 // Bit m of the result: some lane of 4m .. 4m + 3 has its bit set in the ballot (those four lanes own one
