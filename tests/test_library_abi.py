@@ -67,6 +67,8 @@ def test_null_handles_are_rejected_or_ignored(lib):
     assert lib.liec_set_lr(None, 0.1) == 1
     assert lib.liec_set_random(None, 1, 2) == 1
     assert lib.liec_force_search_mode(None, 0) == 1
+    assert lib.liec_set_search_wait(None, 0) == 1
+    assert lib.liec_set_group_bitmap(None, 0) == 1
     assert lib.liec_l2_norm(None, None, 1, None) == 1
     assert lib.liec_iteration(None, 0, 4, None, None, None) == 1
     assert lib.liec_iteration(None, 0, 1, None, None, None) == 1      # a period of 1 would never compress
