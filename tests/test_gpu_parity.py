@@ -181,7 +181,14 @@ def test_step_rejects_bad_buffers_and_reports_nonfinite_input():
         ctx.step(g, x, e)
         info, st = ctx.info_status()
         assert st == 4 and info.nonfinite == 1
+        with pytest.raises(LiecError):
+            ctx.set_group_bitmap(1)                  # the workers' operator is not top-k
+        with pytest.raises(LiecError):
+            ctx.set_search_wait(-1)
     with LiecContext(N, d, "topk", "sign", 10, 0, 0.1) as ctx:
+        with pytest.raises(LiecError):
+            ctx.set_group_bitmap(2)
+        ctx.set_group_bitmap(1)
         x.zero_(), e.zero_()
         g[1, 17] = float("nan")
         ctx.step(g, x, e)
