@@ -85,8 +85,8 @@ typedef struct {
  *   k           kept entries for LIEC_COMP_TOPK / LIEC_COMP_RANDK, 1 <= k <= d; ignored otherwise
  *   lr          learning rate eta, finite
  * Allocates the context's device scratch: 4d bytes for v; N * d / 8 for sign or
- * random-k bitmaps; with top-k or random-k on either side also (N + 1) * (d / 2 +
- * 32 KiB) for the candidate lists, N * d / 32 for the group bitmap and about
+ * random-k bitmaps; with top-k or random-k on either side also (N + 1) * 8 *
+ * (min(d / 16, 8 k) + 4096) for the candidate lists, N * d / 32 for the group bitmap and about
  * 120 KiB per row of histograms (liec_scratch_bytes reports the total).  The
  * context belongs to the HIP device that is current at this call: every later call
  * on it makes that device current for its own duration and puts the caller's back.
@@ -197,8 +197,10 @@ liec_status liec_pack_sign_bits(liec_ctx *ctx, int32_t worker, uint8_t *out);
  * Decompression of such a message into the dense vector p (DEVICE, [d]):
  * p_j = -s or +s, with s = scales[0] (blockwise == 0) or the scale of the block
  * holding j (blockwise != 0; scales has nblocks entries, the context's block
- * table applies).  bits: DEVICE, ceil(d/8) bytes.  scales: HOST.  Enqueued on
- * the context's stream after a synchronous copy of the scales.
+ * table applies).  bits: DEVICE, ceil(d/8) bytes.  scales: HOST, read before
+ * the call returns.  Enqueued on the context's stream; with blockwise == 0 the
+ * call neither copies nor synchronises (the scale travels with the launch), with
+ * blockwise != 0 the scales are first copied to the device synchronously.
  */
 liec_status liec_unpack_sign_message(liec_ctx *ctx, const uint8_t *bits, const float *scales,
                                      int32_t blockwise, float *p_out);
@@ -259,36 +261,6 @@ liec_status liec_set_lr(liec_ctx *ctx, float lr);
 liec_status liec_set_random(liec_ctx *ctx, uint64_t seed, uint64_t draw);
 liec_status liec_get_random(liec_ctx *ctx, uint64_t *seed, uint64_t *draw);
 
-/*
- * Testing aid for the threshold search behind top-k (Definition 2) and random-k
- * (Definition 3): makes every such row start the next liec_step's search in the
- * given mode -- 0: filter the band predicted by the previous step, 1: no
- * prediction (first radix digit over the whole row, then filter), 4: the general
- * search over the whole row.  The modes differ in cost only; the kept set is the
- * same in each.  Synchronises the stream.  LIEC_EINVAL for any other mode.
- */
-liec_status liec_force_search_mode(liec_ctx *ctx, int32_t mode);
-
-/*
- * Testing aid for the general search (mode 4 above, also what constant or
- * mostly-zero rows fall to): several thread blocks share a row and wait for one
- * another between its phases; `polls` bounds each wait (default 65536, about 0.2 s).
- * A wait that runs out is not an error: one block then repeats the search on its
- * own, with the same result.  0 makes every wait run out at once, which is how the
- * tests reach that path.  LIEC_EINVAL for a negative value.
- */
-liec_status liec_set_search_wait(liec_ctx *ctx, int32_t polls);
-
-/*
- * Testing and tuning aid for top-k workers: the form of the candidate bitmap that
- * the threshold search leaves for the aggregation -- 0: one bit per 4 columns,
- * 1: one bit per 64-byte line (16 columns).  liec_create* picks it from d (the
- * second form from 4e7 columns up, where it measured faster); results do not
- * depend on it.  Takes effect with the next step.  LIEC_EINVAL for another value
- * or when the workers' operator is not top-k.
- */
-liec_status liec_set_group_bitmap(liec_ctx *ctx, int32_t per_line);
-
 /* Synchronises the stream and copies the scalars of the last step to the host
  * struct `info`.  Returns LIEC_ENONFINITE (with `info` filled) if that step met
  * a NaN or Inf. */
@@ -306,21 +278,6 @@ liec_status liec_get_info(liec_ctx *ctx, liec_info *info);
 liec_status liec_get_worker_desc(liec_ctx *ctx, float *scales, double *l1, uint32_t *tau,
                                  int64_t *cutoff);
 
-/*
- * Per-kernel timing with HIP events on the context's stream, for measurement.
- * liec_profile_begin(ctx, max_steps, update_only) makes every following
- * liec_step record an event before and after each kernel it launches, or, with
- * update_only != 0, around the update kernel alone (the kernel that moves most
- * of the bytes; two events per step disturb the step least).  At most
- * max_steps steps are recorded, later ones run unrecorded.  liec_profile_end
- * synchronises, stops recording and fills HOST arrays: names[s] (static
- * strings), total_ms[s] and launches[s] for s < *n_slots (in: capacity of the
- * arrays, out: slots used).
- */
-liec_status liec_profile_begin(liec_ctx *ctx, int32_t max_steps, int32_t update_only);
-liec_status liec_profile_end(liec_ctx *ctx, int32_t *n_slots, const char **names, double *total_ms,
-                             int64_t *launches);
-
 /* Releases the scratch memory and the context.  NULL is accepted. */
 void liec_destroy(liec_ctx *ctx);
 
@@ -329,15 +286,6 @@ const char *liec_status_string(liec_status s);
 
 /* Bytes of device scratch the context holds. */
 int64_t liec_scratch_bytes(const liec_ctx *ctx);
-
-/*
- * Measurement aid, not part of the method: a plain 128-bit device-to-device
- * copy kernel enqueued on `hip_stream` (hipStream_t as void*, NULL = null
- * stream).  dst and src are DEVICE pointers, 16-byte aligned, non-overlapping;
- * bytes must be a multiple of 16.  It gives the achievable streaming bandwidth
- * to quote next to the step's kernels and calibrates hardware byte counters.
- */
-liec_status liec_device_copy(void *dst, const void *src, int64_t bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,76 @@
+/*
+ * liec_testing.h -- testing, tuning and measurement aids of the LIEC-SGD library
+ * declared in liec.h.  Nothing here is part of the method (Algorithm 1 and
+ * Definitions 2-5 of the paper): these calls let the tests reach every path of
+ * the threshold search behind top-k and random-k, and let the measurement
+ * script time single kernels and calibrate hardware byte counters.  They are
+ * exported by the same shared library and follow the same rules: plain
+ * pointers, status codes, no exceptions.
+ */
+#ifndef LIEC_TESTING_H
+#define LIEC_TESTING_H
+
+#include "liec.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Testing aid for the threshold search behind top-k (Definition 2) and random-k
+ * (Definition 3): makes every such row start the next liec_step's search in the
+ * given mode -- 0: filter the band predicted by the previous step, 1: no
+ * prediction (first radix digit over the whole row, then filter), 4: the general
+ * search over the whole row.  The modes differ in cost only; the kept set is the
+ * same in each.  Synchronises the stream.  LIEC_EINVAL for any other mode.
+ */
+liec_status liec_force_search_mode(liec_ctx *ctx, int32_t mode);
+
+/*
+ * Testing aid for the general search (mode 4 above, also what constant or
+ * mostly-zero rows fall to): several thread blocks share a row and wait for one
+ * another between its phases; `polls` bounds each wait (default 65536, about 0.2 s).
+ * A wait that runs out is not an error: one block then repeats the search on its
+ * own, with the same result.  0 makes every wait run out at once, which is how the
+ * tests reach that path.  LIEC_EINVAL for a negative value.
+ */
+liec_status liec_set_search_wait(liec_ctx *ctx, int32_t polls);
+
+/*
+ * Testing and tuning aid for top-k workers: the form of the candidate bitmap that
+ * the threshold search leaves for the aggregation -- 0: one bit per 4 columns,
+ * 1: one bit per 64-byte line (16 columns).  liec_create* picks it from d (the
+ * second form from 4e7 columns up, where it measured faster); results do not
+ * depend on it.  Takes effect with the next step.  LIEC_EINVAL for another value
+ * or when the workers' operator is not top-k.
+ */
+liec_status liec_set_group_bitmap(liec_ctx *ctx, int32_t per_line);
+
+/*
+ * Per-kernel timing with HIP events on the context's stream, for measurement.
+ * liec_profile_begin(ctx, max_steps, update_only) makes every following
+ * liec_step record an event before and after each kernel it launches, or, with
+ * update_only != 0, around the update kernel alone (the kernel that moves most
+ * of the bytes; two events per step disturb the step least).  At most
+ * max_steps steps are recorded, later ones run unrecorded.  liec_profile_end
+ * synchronises, stops recording and fills HOST arrays: names[s] (static
+ * strings), total_ms[s] and launches[s] for s < *n_slots (in: capacity of the
+ * arrays, out: slots used).
+ */
+liec_status liec_profile_begin(liec_ctx *ctx, int32_t max_steps, int32_t update_only);
+liec_status liec_profile_end(liec_ctx *ctx, int32_t *n_slots, const char **names, double *total_ms,
+                             int64_t *launches);
+
+/*
+ * Measurement aid, not part of the method: a plain 128-bit device-to-device
+ * copy kernel enqueued on `hip_stream` (hipStream_t as void*, NULL = null
+ * stream).  dst and src are DEVICE pointers, 16-byte aligned, non-overlapping;
+ * bytes must be a multiple of 16.  It gives the achievable streaming bandwidth
+ * to quote next to the step's kernels and calibrates hardware byte counters.
+ */
+liec_status liec_device_copy(void *dst, const void *src, int64_t bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIEC_TESTING_H */

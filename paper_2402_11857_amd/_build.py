@@ -9,7 +9,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "libliec.so")
 SOURCES = [os.path.join(_HERE, "csrc", "liec_api.hip")]
-HEADERS = [os.path.join(_HERE, "csrc", "liec_kernels.hpp"), os.path.join(_ROOT, "include", "liec.h")] + \
+HEADERS = [os.path.join(_HERE, "csrc", "liec_kernels.hpp"), os.path.join(_ROOT, "include", "liec.h"),
+           os.path.join(_ROOT, "include", "liec_testing.h")] + \
           [os.path.join(_HERE, "csrc", "kernels", n)
            for n in ("common.hpp", "select.hpp", "sign.hpp", "step.hpp", "sync.hpp", "telemetry.hpp", "wire.hpp")]
 

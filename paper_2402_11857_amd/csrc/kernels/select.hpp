@@ -563,6 +563,8 @@ __global__ __launch_bounds__(kFinishBlock) void k_list_finish(uint32_t row0, Row
 // global memory.  The poll is bounded: when a wait runs out (blocks that could not all be resident
 // at once, a GPU shared with other work) the row is flagged, every block leaves, and block 0
 // repeats the search on its own with LDS histograms -- the B = 1 path.  Results are identical.
+// Block 0 is the only writer of the row's result on either path, so a row cannot leave the kernel
+// still in kSlow mode whatever the order in which waits run out.
 // The host chooses B so that B * rows blocks fit the chip at one block per compute unit.
 // ---------------------------------------------------------------------------------------------
 constexpr int kSlowMaxBlocks = 64;
@@ -711,7 +713,18 @@ __device__ __forceinline__ bool slow_meet(SlowLds& s, uint32_t* __restrict__ syn
     return s.ok != 0;
 }
 
-// The B blocks of a row together.  Returns false when a wait ran out (the descriptor is untouched then).
+// Arrival without a wait: my stores are out, then the counter says so.  Every thread calls it.
+__device__ __forceinline__ void slow_arrive(uint32_t* __restrict__ sync) {
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) atomicAdd(&sync[0], 1u);
+}
+
+// The B blocks of a row together.  Only block 0 ever writes the row's descriptor, and only its return
+// value matters: false when one of its waits ran out (the descriptor is untouched then, and the caller
+// repeats the search on block 0 alone), true when it has written the result.  A block other than 0 whose
+// wait runs out just leaves (block 0 then fails its next wait, because the give-up flag is set or the
+// arrivals never add up).
 template <bool VEC, bool RK>
 __device__ bool slow_multi(SlowLds& s, const float* __restrict__ g, uint32_t d, uint32_t nwt, uint32_t row,
                            RowDesc* __restrict__ desc, uint32_t k, RkDraw rk, uint32_t k0, uint32_t k1,
@@ -762,7 +775,7 @@ __device__ bool slow_multi(SlowLds& s, const float* __restrict__ g, uint32_t d, 
         ties = p.count;
         off += nbins;
     }
-    // ties inside my range, then the block whose range holds the rank-th tie walks it in index order
+    // ties inside my range; block 0 then walks the range that holds the rank-th tie in index order
     uint32_t mine = 0;
     for (uint32_t t = t0 + wave; t < t1; t += 16) {
 #pragma unroll
@@ -776,16 +789,32 @@ __device__ bool slow_multi(SlowLds& s, const float* __restrict__ g, uint32_t d, 
     }
     const uint32_t total = block_sum_u32(mine, s.wtot);         // valid on thread 0
     if (tid == 0) gcnt[b] = total;
-    if (!slow_meet(s, sync, B * ++meetings, spin_limit)) return false;
-    uint32_t before = 0;
-    for (uint32_t q = 0; q < b; ++q) before += gcnt[q];
-    const uint32_t here = gcnt[b];
-    if (!(before < rank && rank <= before + here)) return true;  // uniform for the block
+    // Last meeting.  From here on block 0 alone speaks for the row: the other blocks publish their count,
+    // arrive and leave without waiting, so no block can pass this meeting while the one that would have
+    // written the result gives up.  Block 0 either sees every count and walks the range that holds the
+    // rank-th tie itself (1/B of the row), or its wait runs out and the caller repeats the search alone.
+    ++meetings;
+    if (b != 0) {
+        slow_arrive(sync);
+        return true;
+    }
+    if (!slow_meet(s, sync, B * meetings, spin_limit)) return false;
+    uint32_t before = 0, owner = B;
+    for (uint32_t q = 0; q < B; ++q) {                          // uniform for the block
+        const uint32_t here = gcnt[q];
+        if (before < rank && rank <= before + here) {
+            owner = q;
+            break;
+        }
+        before += here;
+    }
+    if (owner == B) return false;                               // counts that do not add up to the histogram: search alone
     const uint32_t need = rank - before;
+    const uint32_t w0 = min(owner * tpb, nwt), w1 = min(w0 + tpb, nwt);   // the owner's range of wave tiles
     if (tid == 0) s.cut = 0xffffffffu;
     __syncthreads();
     uint32_t seen = 0;
-    for (uint32_t tb = t0; tb < t1; tb += 16) {                 // uniform trip count and exit
+    for (uint32_t tb = w0; tb < w1; tb += 16) {                 // uniform trip count and exit
         const uint32_t t = tb + wave;
         uint64_t kb[4][4];
         uint32_t cnt = 0;
@@ -793,10 +822,10 @@ __device__ bool slow_multi(SlowLds& s, const float* __restrict__ g, uint32_t d, 
         for (int u = 0; u < 4; ++u) {
             const uint32_t j = t * kWaveTile + u * kChunk + lane * 4;
             uint32_t key[4] = {0, 0, 0, 0};
-            if (t < t1) slow_keys_at<VEC, RK>(g, d, k0, k1, j, key);
+            if (t < w1) slow_keys_at<VEC, RK>(g, d, k0, k1, j, key);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                kb[u][q] = __ballot(t < t1 && j + q < d && key[q] == prefix);
+                kb[u][q] = __ballot(t < w1 && j + q < d && key[q] == prefix);
                 cnt += (uint32_t)__popcll(kb[u][q]);
             }
         }

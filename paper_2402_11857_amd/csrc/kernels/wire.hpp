@@ -22,8 +22,8 @@ __global__ __launch_bounds__(kBlock) void k_pack_sign(const uint16_t* __restrict
 
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_unpack_sign(const uint8_t* __restrict__ bytes, uint32_t d,
-                                                         const float* __restrict__ scales, BlockTable bt,
-                                                         float* __restrict__ p) {
+                                                         const float* __restrict__ scales, float scale0,
+                                                         BlockTable bt, float* __restrict__ p) {
     const uint32_t nq = (d + 3) / 4;                            // groups of 4 columns = half a wire byte
     for (uint32_t q = blockIdx.x * kBlock + threadIdx.x; q < nq; q += gridDim.x * kBlock) {
         const uint32_t j0 = q * 4;
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kBlock) void k_unpack_sign(const uint8_t* __restric
                 v[c] = ((m >> c) & 1u) ? -s : s;
             }
         } else {
-            const float s = scales[0];
+            const float s = scale0;                             // Definition 4: one scale, passed by value
 #pragma unroll
             for (int c = 0; c < 4; ++c) v[c] = ((m >> c) & 1u) ? -s : s;
         }

@@ -1,6 +1,7 @@
-// Host side of the C ABI declared in include/liec.h: argument checks, scratch ownership and
+// Host side of the C ABI declared in include/liec.h and include/liec_testing.h: argument checks, scratch ownership and
 // the launch sequence of one compressed LIEC-SGD iteration (Algorithm 1) on a HIP stream.
 #include "liec.h"
+#include "liec_testing.h"
 
 #include <hip/hip_runtime.h>
 
@@ -514,7 +515,12 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     c->agg_blocks = balanced(gathers ? 16384u : 65536u);
     c->cold_row_blocks = clampu(2048u / un, 1u, blk_iters);
     c->cold_srv_blocks = clampu(2048u, 1u, blk_iters);
-    c->cap = (uint32_t)((d / 16 + 4096 < d) ? d / 16 + 4096 : d);
+    // Candidate list capacity per row: the warm band lists a few per cent of k entries and the first-digit
+    // bin that holds rank k about k / 2 for bell-shaped rows, so 8 k (at most d / 16) leaves a wide margin;
+    // a band that needs more falls to the first-digit histogram or the general search, as any overflow does.
+    const int64_t kmax = std::max(c->worker_k, c->server_k);
+    const int64_t want = std::min<int64_t>(d / 16, 8 * kmax) + 4096;
+    c->cap = (uint32_t)std::min<int64_t>(want, d);
     c->list_blocks = clampu((c->cap + 2047u) / 2048u, 1u, 64u);
 
     const size_t rows = (size_t)N + 1;
@@ -858,30 +864,36 @@ liec_status liec_unpack_sign_message(liec_ctx* c, const uint8_t* bits, const flo
     DeviceScope on(c);
     if (!on.ok) return LIEC_EDEVICE;
     if (blockwise && c->B == 0) return LIEC_EINVAL;
-    const uint32_t n = blockwise ? c->B : 1u;
-    hipError_t e = hipSuccess;
-    if (c->wire_scales_len < n) {
-        e = hipStreamSynchronize(c->stream);
-        (void)hipFree(c->wire_scales);
-        c->wire_scales = nullptr;
-        c->wire_scales_len = 0;
-        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->wire_scales), (size_t)n * sizeof(float));
-        if (e == hipSuccess) c->wire_scales_len = n;
-    }
-    if (e == hipSuccess) e = hipMemcpyAsync(c->wire_scales, scales, (size_t)n * sizeof(float), hipMemcpyHostToDevice, c->stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);        // the host array may be reused on return
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        return e == hipErrorOutOfMemory ? LIEC_ENOMEM : LIEC_EDEVICE;
+    // Definition 4 has one scale: it travels as a kernel argument, and nothing is copied or waited for.
+    // Definition 5's table of scales is copied to the device first.
+    const float scale0 = scales[0];
+    if (blockwise) {
+        const uint32_t n = c->B;
+        hipError_t e = hipSuccess;
+        if (c->wire_scales_len < n) {
+            e = hipStreamSynchronize(c->stream);
+            (void)hipFree(c->wire_scales);
+            c->wire_scales = nullptr;
+            c->wire_scales_len = 0;
+            if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->wire_scales), (size_t)n * sizeof(float));
+            if (e == hipSuccess) c->wire_scales_len = n;
+        }
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(c->wire_scales, scales, (size_t)n * sizeof(float), hipMemcpyHostToDevice, c->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(c->stream);    // the host array may be reused on return
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return e == hipErrorOutOfMemory ? LIEC_ENOMEM : LIEC_EDEVICE;
+        }
     }
     BlockTable bt = block_table(c);
     if (!blockwise) bt.B = 0;
     const uint32_t d = (uint32_t)c->d;
     const uint32_t nq = (d + 3) / 4, grid = std::min<uint32_t>((nq + kBlock - 1) / kBlock, 16384u);
     if (d % 4 == 0 && ((uintptr_t)p_out & 15u) == 0)
-        k_unpack_sign<true><<<grid, kBlock, 0, c->stream>>>(bits, d, c->wire_scales, bt, p_out);
+        k_unpack_sign<true><<<grid, kBlock, 0, c->stream>>>(bits, d, c->wire_scales, scale0, bt, p_out);
     else
-        k_unpack_sign<false><<<grid, kBlock, 0, c->stream>>>(bits, d, c->wire_scales, bt, p_out);
+        k_unpack_sign<false><<<grid, kBlock, 0, c->stream>>>(bits, d, c->wire_scales, scale0, bt, p_out);
     if (hipGetLastError() != hipSuccess) {
         c->broken = true;
         return LIEC_EDEVICE;

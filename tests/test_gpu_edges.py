@@ -192,11 +192,12 @@ def test_quantised_gradients_with_thousands_of_ties_at_the_threshold(wc, sc):
 
 
 @pytest.mark.parametrize("kind", ["constant", "mostly_zero", "four_levels", "one_level_rest_noise"])
-@pytest.mark.parametrize("wait", [None, 0])
+@pytest.mark.parametrize("wait", [None, 0, 1, 2, 8])
 def test_degenerate_rows_at_a_size_where_thread_blocks_share_a_row(kind, wait):
     """Rows whose threshold is shared by more entries than the candidate list holds take the general search,
     in which several thread blocks split a row (wait=None) or, when their bounded wait for one another runs
-    out (wait=0 forces that), one block does it alone.  Either way the result is the oracle's."""
+    out (wait=0 forces that for every block; 1, 2 and 8 polls let some blocks pass a meeting that others
+    give up at), one block does it alone.  Either way the result is the oracle's and every kernel ends."""
     import oracle
     from paper_2402_11857_amd import LiecContext
 

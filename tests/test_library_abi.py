@@ -1,5 +1,6 @@
-"""The C-ABI library loads and exports every symbol include/liec.h declares; argument checks
-that need no GPU return the documented status codes."""
+"""The C-ABI library loads and exports every symbol include/*.h declares (liec.h: the method's calls,
+liec_testing.h: testing and measurement aids); argument checks that need no GPU return the documented
+status codes."""
 import ctypes
 import os
 import re
@@ -7,13 +8,19 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "liec.h")
+HEADERS = [os.path.join(ROOT, "include", n) for n in ("liec.h", "liec_testing.h")]
+AIDS = ("liec_force_search_mode", "liec_set_search_wait", "liec_set_group_bitmap", "liec_profile_begin",
+        "liec_profile_end", "liec_device_copy")
+
+
+def _declared_in(header):
+    text = open(header).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(liec_[a-z0-9_]+)\s*\(", text)))
 
 
 def _declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(liec_[a-z_]+)\s*\(", text)))
+    return sorted(set(n for h in HEADERS for n in _declared_in(h)))
 
 
 @pytest.fixture(scope="module")
@@ -35,7 +42,15 @@ def test_header_declares_the_north_star_calls():
 
 def test_every_declared_symbol_is_exported(lib):
     for name in _declared_functions():
-        assert hasattr(lib, name), f"{name} is declared in liec.h but not exported"
+        assert hasattr(lib, name), f"{name} is declared in include/ but not exported"
+
+
+def test_the_method_header_holds_no_testing_aids():
+    """liec.h declares the method's calls; the aids the tests and the measurement script use live in
+    liec_testing.h."""
+    method, aids = _declared_in(HEADERS[0]), _declared_in(HEADERS[1])
+    for name in AIDS:
+        assert name in aids and name not in method
 
 
 def test_status_strings(lib):
@@ -102,7 +117,7 @@ def test_header_is_plain_c(tmp_path):
     import subprocess
 
     src = tmp_path / "use_header.c"
-    src.write_text('#include "liec.h"\n'
+    src.write_text('#include "liec.h"\n#include "liec_testing.h"\n'
                    "int main(void) {\n"
                    "    liec_ctx *c = 0;\n"
                    "    liec_info info;\n"
