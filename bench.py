@@ -27,14 +27,36 @@ CACHE_RESIDENT = {"c1_tiny_sign": "1 MiB of gradients: cache-resident, bound by 
                   "c2_topk_mid": "32 MiB of gradients: cache-resident, bound by the gaps between 20 dependent kernels"}
 N_GRAD_BUFFERS = 4          # distinct gradient batches rotated through the timed steps
 REPEATS = 5                 # timed regions per workload; the median one is reported
-# HBM bytes one launch of the update kernel moves, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this script, each counter scaled by what it reads for the 1 GiB copy probe (profiles/liec_step_<workload>.md)
-UPDATE_TRAFFIC_BYTES = {"c5_vgg16_mixed": 28.406e9, "c5_vgg16_sign": 28.401e9, "c3_resnet18_sign": 2.394e9,
-                        "c4_resnet50_topk": 10.237e9, "c4_resnet50_randk": 10.349e9}
-# the same counters summed over every kernel of one steady-state step (same profiles): what the whole
-# step moves, to be read next to its algorithmic bytes
-STEP_TRAFFIC_BYTES = {"c5_vgg16_mixed": 40.06e9, "c5_vgg16_sign": 39.02e9, "c3_resnet18_sign": 3.291e9,
-                      "c4_resnet50_topk": 14.10e9, "c4_resnet50_randk": 10.90e9}
+# kernels that make up a steady-state step (the rest of a profile summary -- cold and general search,
+# averaging iteration, wire forms, copy probe -- is not part of it)
+STEADY_STATE_KERNELS = ("k_update", "k_filter", "k_aggregate", "k_l1_bits", "k_l1_final", "k_l1_items", "k_list_",
+                        "k_rk_zero", "k_rk_filter_inverse", "k_rk_mark", "k_rk_advance")
+
+
+def profile_traffic(workload: str):
+    """HBM bytes per launch of the update kernel and per steady-state step, read from the rocprofv3 counter
+    summary of this script's own run on that workload (profiles/liec_step_<workload>.md: FETCH_SIZE and
+    WRITE_SIZE, each scaled by what it reads for the 1 GiB copy probe).  (None, None) without a summary."""
+    path = os.path.join(ROOT, "profiles", f"liec_step_{workload}.md")
+    if not os.path.exists(path):
+        return None, None
+    update = step = None
+    in_table = False
+    for line in open(path):
+        if line.startswith("## HBM traffic counters"):
+            in_table = True
+            continue
+        if not in_table or not line.startswith("| liec::"):
+            continue
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        name, read_gb, write_gb = cells[0].replace("liec::", ""), float(cells[2]), float(cells[4])
+        if not name.startswith(STEADY_STATE_KERNELS):
+            continue
+        total = (read_gb + write_gb) * 1e9
+        step = (step or 0.0) + total
+        if name.startswith("k_update"):
+            update = total
+    return update, step
 
 
 def log(msg: str) -> None:
@@ -95,6 +117,7 @@ def run_workload(w, steps: int, warmup: int, seed: int = 0):
             ctx.step_sync(grads[t % nbuf], x, e)
         sync_ms = ctx.profile_end()["sync"][0] / ns
         wire = time_wire_forms(ctx, w, grads[0], x, e)
+        worst = time_worst_case_steps(ctx, w, grads, x, e)
         scratch = ctx.scratch_bytes()
     ms_per_step = 1e3 * elapsed / steps
     out = {
@@ -106,6 +129,7 @@ def run_workload(w, steps: int, warmup: int, seed: int = 0):
         "region_ms_per_step": [round(1e3 * r[0] / steps, 4) for r in regions],
         "sync_ms": sync_ms,
         "wire": wire,
+        "worst": worst,
         "sync_gbps": dominant_kernel_bytes(w) / (sync_ms * 1e-3) / 1e9,   # same bytes: g, x in, x out, e in/out
     }
     out["update_avg_ms"] = upd_ms / upd_n
@@ -113,6 +137,50 @@ def run_workload(w, steps: int, warmup: int, seed: int = 0):
     del grads, x, e
     torch.cuda.empty_cache()
     return out
+
+
+def time_worst_case_steps(ctx, w, grads, x, e, reps: int = 3):
+    """Single steps outside the steady state, each timed by events on the step's stream (median of `reps`):
+    `cold` -- no threshold prediction at all (what the first step of a context pays): every top-k row takes
+    the first-digit histogram and a second filter pass; `failed_prediction` -- the gradients' scale jumps
+    by 30 between two steps, so the band predicted from the last thresholds misses and the same two extra
+    passes run after the wasted one.  Operators without a threshold search have no such cases."""
+    import torch
+
+    if "topk" not in (w.worker_comp, w.server_comp):
+        return None
+    alg = w.alg_bytes_per_step
+
+    def timed_step(g):
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        ctx.step(g, x, e)
+        stop.record()
+        torch.cuda.synchronize()
+        return start.elapsed_time(stop)
+
+    def entry(ms_list):
+        ms = sorted(ms_list)[len(ms_list) // 2]
+        return {"ms": round(ms, 4), "hbm_frac": round(alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "all_ms": [round(m, 4) for m in ms_list]}
+
+    cold = []
+    for r in range(reps):
+        ctx.step(grads[r % len(grads)], x, e)
+        ctx.force_search_mode(1)                  # no prediction: as in the first step of a context
+        cold.append(timed_step(grads[(r + 1) % len(grads)]))
+    big = grads[0] * 30.0
+    failed = []
+    for r in range(reps):
+        for q in range(3):                         # settle the prediction on the unscaled gradients
+            ctx.step(grads[q % len(grads)], x, e)
+        failed.append(timed_step(big))
+    slow_rows = ctx.info().slow_rows
+    del big
+    return {"cold_step": entry(cold), "failed_prediction_step": entry(failed),
+            "rows_in_general_search_after": slow_rows,
+            "note": "single steps timed by events; value and roofline are the steady state, in which every row's "
+                    "predicted band holds"}
 
 
 def time_wire_forms(ctx, w, g, x, e, reps: int = 5):
@@ -173,50 +241,46 @@ def copy_ceiling_gbps(nbytes: int = 1 << 30, reps: int = 10) -> float:
 
 
 def cpu_baseline(w, seed: int = 0):
-    """The CPU oracle as it stands, one thread, on a column slice of the same workload."""
+    """The CPU oracle as it stands.  `value`: one host thread, one step at the benched configuration's full
+    row length with N cut to one worker (the oracle's top-k is a full sort, so elements per second depend on
+    d; they do not depend on N).  Beside it, labelled: a 2^21-column slice at full N on one thread, and the
+    same slice through the -fopenmp build of the same source (workers of a step on all host threads)."""
     import numpy as np
 
     import oracle
     import workloads
 
     oracle.build()
-    d_s = min(w.d, 1 << 21)
-    ws = workloads.scaled(w, d=d_s)
-    g = workloads.GradientSource(ws, seed=seed, device="cpu").grads(0).numpy()
-    x = np.zeros((ws.N, ws.d), dtype=np.float32)
-    e = np.zeros(ws.d, dtype=np.float32)
-    steps, t0 = 0, time.perf_counter()
-    while True:
-        oracle.step(g, x, e, ws.worker_comp, ws.server_comp, ws.lr, ws.worker_k, ws.server_k)
-        steps += 1
-        el = time.perf_counter() - t0
-        if el > 10.0 or steps >= 50:
-            break
-    out = {"value": ws.N * ws.d * steps / el, "unit": "elems/s", "cores": 1, "kind": "oracle",
-           "sample": f"{steps} step(s) of the same recipe cut to N={ws.N}, d={ws.d} columns "
-                     f"(k scaled with d), {el:.1f} s of one host thread"}
-    # the same oracle functions with the per-worker phases of the step on one host thread per worker
-    from concurrent.futures import ThreadPoolExecutor
 
-    threads = min(ws.N, os.cpu_count() or 1, 16)
-    x[:] = 0
-    e[:] = 0
-    with ThreadPoolExecutor(max_workers=threads) as pool:
-        steps, t0 = 0, time.perf_counter()
+    def run(ws, step_fn, budget_s, max_steps):
+        g = workloads.GradientSource(ws, seed=seed, device="cpu").grads(0).numpy()
+        x = np.zeros((ws.N, ws.d), dtype=np.float32)
+        e = np.zeros(ws.d, dtype=np.float32)
+        steps, threads, t0 = 0, 1, time.perf_counter()
         while True:
-            res = list(pool.map(lambda i: oracle.compress(ws.worker_comp, g[i], ws.worker_k), range(ws.N)))
-            P = np.stack([r[0] for r in res])
-            v = oracle.server_average(P, e)
-            p, _ = oracle.compress(ws.server_comp, v, ws.server_k)
-            e[:] = oracle.error_update(v, p)
-            list(pool.map(lambda i: oracle.worker_update(g[i], P[i], p, ws.lr, x[i]), range(ws.N)))
+            r = step_fn(g, x, e, ws.worker_comp, ws.server_comp, ws.lr, ws.worker_k, ws.server_k)
+            threads = r if isinstance(r, int) else 1
             steps += 1
             el = time.perf_counter() - t0
-            if el > 5.0 or steps >= 50:
-                break
-    out["workers_in_parallel"] = {"value": ws.N * ws.d * steps / el, "unit": "elems/s", "threads": threads,
-                                  "note": "same oracle functions, the per-worker phases of a step on one thread "
-                                          "per worker; the server phases stay on one thread"}
+            if el > budget_s or steps >= max_steps:
+                return ws.N * ws.d * steps / el, steps, el, threads
+
+    full = workloads.scaled(w, N=1, worker_k=w.worker_k, server_k=w.server_k)
+    v, steps, el, _ = run(full, oracle.step, 0.0, 1)
+    out = {"value": v, "unit": "elems/s", "cores": 1, "kind": "oracle",
+           "sample": f"{steps} step of the benched recipe at its full row length d={full.d} with N cut to 1 worker "
+                     f"(k unchanged), {el:.1f} s of one host thread"}
+    ws = workloads.scaled(w, d=min(w.d, 1 << 21))
+    v, steps, el, _ = run(ws, oracle.step, 8.0, 50)
+    out["column_slice"] = {"value": v, "unit": "elems/s", "cores": 1,
+                           "sample": f"SLICE, not the benched size: {steps} step(s) at N={ws.N}, d={ws.d} columns "
+                                     f"(k scaled with d), {el:.1f} s of one host thread"}
+    v, steps, el, threads = run(ws, oracle.step_all_cores, 5.0, 50)
+    out["all_host_cores"] = {"value": v, "unit": "elems/s", "threads": threads,
+                             "sample": f"SLICE: the same {ws.N} x {ws.d} slice, {steps} step(s) in {el:.1f} s through the "
+                                       "-fopenmp build of the same source (the workers of a step on separate threads, "
+                                       "the server on one); its output is checked bit for bit against the one-thread "
+                                       "build by tests/test_oracle_step.py"}
     return out
 
 
@@ -260,6 +324,7 @@ def main() -> int:
                           "update_gbps": round(r["update_gbps"], 1),
                           "averaging_iteration_ms": round(r["sync_ms"], 4),
                           "wire_worker0": r["wire"],
+                          "outside_steady_state": r["worst"],
                           "kernels_ms_per_step": {k: round(v, 4) for k, v in r["kernels_ms_per_step"].items()}}
             if name in CACHE_RESIDENT:
                 also[name]["note"] = CACHE_RESIDENT[name]
@@ -289,15 +354,17 @@ def main() -> int:
         "step_alg_bytes": w.alg_bytes_per_step,
         "step_alg_gbps": main_res["alg_gbps"],
         "step_hbm_frac": main_res["alg_gbps"] / HBM_PEAK_GBPS,
-        "step_traffic_bytes": STEP_TRAFFIC_BYTES.get(w.name),
+        "step_traffic_bytes": profile_traffic(w.name)[1],
+        "traffic_source": f"profiles/liec_step_{w.name}.md",
         "copy_kernel_gbps": copy_gbps,
         "roofline": {"bound": "hbm", "kernel": "update", "achieved": main_res["update_gbps"],
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": main_res["update_gbps"] / HBM_PEAK_GBPS,
-                     "traffic": UPDATE_TRAFFIC_BYTES.get(w.name), "alg_bytes_per_launch": dominant_kernel_bytes(w),
+                     "traffic": profile_traffic(w.name)[0], "alg_bytes_per_launch": dominant_kernel_bytes(w),
                      "avg_launch_ms": main_res["update_avg_ms"]},
         "kernels_ms_per_step_untimed_pass": {k: round(v, 4) for k, v in main_res["kernels_ms_per_step"].items()},
         "scratch_bytes": main_res["scratch_bytes"],
         "wire_worker0": main_res["wire"],
+        "outside_steady_state": main_res["worst"],
         "averaging_iteration": {"ms": round(main_res["sync_ms"], 4), "alg_gbps": round(main_res["sync_gbps"], 1),
                                 "note": "Algorithm 1's uncompressed iteration, one in every `period` steps; not part of value"},
         # Algorithm 1 as a whole with the averaging periods of the paper's experiments, from the two measured times

@@ -11,6 +11,8 @@ from .liec_oracle import (  # noqa: F401
     RANDK,
     Desc,
     build,
+    build_all_cores,
+    step_all_cores,
     compress,
     compress_blocksign,
     error_update,

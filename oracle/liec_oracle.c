@@ -1,7 +1,8 @@
 /*
  * liec_oracle.c -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
  *
- * A plain, slow, single-threaded CPU statement of one compressed iteration of
+ * A plain, slow CPU statement (single-threaded unless built with -fopenmp, which only spreads
+ * the independent workers of a step over threads) of one compressed iteration of
  * LIEC-SGD (Algorithm 1, the ELSE branches), of its averaging iteration (the IF
  * branches) and of the compression operators it uses (Definition 2 top-k,
  * Definition 4 scaled sign, Definition 5 blockwise scaled sign, and the identity
@@ -340,12 +341,31 @@ int liec_oracle_step_rng(int32_t N, int64_t d, int worker_comp, int64_t worker_k
     float *p = p_out ? p_out : (float *)malloc((size_t)d * sizeof(float));
     int rc = (!P || !v || !p) ? 2 : 0;
 
-    /* worker i: p^i = C(g_i) */
-    for (int32_t i = 0; rc == 0 && i < N; ++i)
-        rc = liec_oracle_compress_rng(worker_comp, g + (size_t)i * (size_t)d, d, worker_k, off, B,
-                                      seed, draw, (uint32_t)i, P + (size_t)i * (size_t)d,
-                                      wdesc ? &wdesc[i] : NULL,
-                                      wscales ? wscales + (size_t)i * (size_t)B : NULL);
+    /* worker i: p^i = C(g_i).  The workers are independent of one another: a build with -fopenmp
+     * (the "all host cores" timing of the bench) runs them on several threads, each worker's
+     * arithmetic unchanged and single-threaded; the plain build runs them in order. */
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (int32_t i = 0; i < N; ++i) {
+        int failed;
+#ifdef _OPENMP
+#pragma omp atomic read
+#endif
+        failed = rc;
+        if (failed != 0)
+            continue;
+        int r = liec_oracle_compress_rng(worker_comp, g + (size_t)i * (size_t)d, d, worker_k, off, B,
+                                         seed, draw, (uint32_t)i, P + (size_t)i * (size_t)d,
+                                         wdesc ? &wdesc[i] : NULL,
+                                         wscales ? wscales + (size_t)i * (size_t)B : NULL);
+        if (r != 0) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            rc = r;
+        }
+    }
     if (rc == 0) {
         /* server: v = e + mean_i p^i ; p = C(v) ; e <- v - p */
         liec_oracle_server_average(P, N, d, e, v);
@@ -355,6 +375,9 @@ int liec_oracle_step_rng(int32_t N, int64_t d, int worker_comp, int64_t worker_k
     if (rc == 0) {
         liec_oracle_error_update(v, p, d, e);
         /* worker i: x^i <- x^i - eta (p - p^i + g_i) */
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
         for (int32_t i = 0; i < N; ++i)
             liec_oracle_worker_update(g + (size_t)i * (size_t)d, P + (size_t)i * (size_t)d, p, d,
                                       lr, x + (size_t)i * (size_t)d);
@@ -490,3 +513,14 @@ void liec_oracle_unpack_topk(const uint32_t *idx, const float *val, int64_t k, i
 }
 
 int liec_oracle_desc_size(void) { return (int)sizeof(oracle_desc); }
+
+/* Threads a step's per-worker loops may use: 1 in the plain build. */
+int liec_oracle_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -55,6 +55,45 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+_LIB_OMP = os.path.join(_HERE, "libliec_oracle_omp.so")
+
+
+def build_all_cores(force: bool = False) -> str:
+    """The same source with -fopenmp: the independent workers of a step run on several host threads.
+    Used only for the bench's labelled "all host cores" timing and by the test that checks its output
+    bit for bit against the plain build."""
+    if force or not os.path.exists(_LIB_OMP) or os.path.getmtime(_LIB_OMP) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _LIB_OMP, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB_OMP
+
+
+def step_all_cores(g: np.ndarray, x: np.ndarray, e: np.ndarray, worker_comp, server_comp, lr: float,
+                   worker_k: int = 0, server_k: int = 0, rng: Tuple[int, int] = (0, 0)) -> int:
+    """`step` through the -fopenmp build; returns the number of threads it may use."""
+    global _lib_omp
+    if _lib_omp is None:
+        build_all_cores()
+        _lib_omp = ctypes.CDLL(_LIB_OMP)
+        _lib_omp.liec_oracle_threads.restype = ctypes.c_int
+    g, x, e = _f32(g), _f32(x, True), _f32(e, True)
+    N, d = g.shape
+    assert x.shape == (N, d) and e.shape == (d,)
+    fn = _lib_omp.liec_oracle_step_rng
+    fn.restype = ctypes.c_int
+    rc = fn(ctypes.c_int32(N), ctypes.c_int64(d), ctypes.c_int(_comp(worker_comp)), ctypes.c_int64(int(worker_k)),
+            ctypes.c_int(_comp(server_comp)), ctypes.c_int64(int(server_k)), ctypes.c_float(lr), _ptr(g), _ptr(x),
+            _ptr(e), None, ctypes.c_int32(0), ctypes.c_uint64(int(rng[0])), ctypes.c_uint64(int(rng[1])),
+            None, None, None, None, None, None, None)
+    if rc != 0:
+        raise ValueError(f"liec_oracle_step_rng (all cores) failed with code {rc}")
+    return int(_lib_omp.liec_oracle_threads())
+
+
+_lib_omp = None
+
+
 def _load():
     global _lib
     if _lib is None:

@@ -227,7 +227,7 @@ def test_out_of_memory_is_reported_and_leaves_the_library_usable():
     from paper_2402_11857_amd import LiecContext, LiecError
 
     with pytest.raises(LiecError) as err:          # the candidate lists alone would take about 1 TB
-        LiecContext(1000, 2_000_000_000, "topk", "topk", 1000, 1000, 0.1)
+        LiecContext(1000, 2_000_000_000, "topk", "topk", 100_000_000, 100_000_000, 0.1)
     assert err.value.status == 2
     w = workloads.scaled(WL["c1_tiny_sign"], N=2, d=5000)
     assert run_chain(w, steps=2, seed=1)

@@ -243,3 +243,22 @@ def test_worker_update_is_one_fused_multiply_add(oracle):
     zero = np.zeros(1, dtype=np.float32)
     oracle.worker_update(zero, zero, np.array([3.0], dtype=np.float32), float(lr), x)
     assert x[0] == np.float32(2.0 ** -27)
+
+
+@pytest.mark.parametrize("wc,sc", [("sign", "sign"), ("topk", "topk"), ("topk", "sign"), ("randk", "randk"),
+                                   ("identity", "identity")])
+def test_the_all_cores_build_of_the_oracle_gives_the_same_bits(oracle, wc, sc):
+    """The -fopenmp build (workers of a step on several threads; timed by the bench as the "all host cores"
+    figure) must leave exactly the state the plain build leaves."""
+    rng = np.random.default_rng(17)
+    N, d, k = 7, 5003, 211
+    x1 = rng.standard_normal((N, d)).astype(np.float32)
+    e1 = (rng.standard_normal(d) * 0.1).astype(np.float32)
+    x2, e2 = x1.copy(), e1.copy()
+    for t in range(3):
+        g = rng.standard_normal((N, d)).astype(np.float32)
+        oracle.step(g, x1, e1, wc, sc, 0.05, k, k, rng=(9, t))
+        threads = oracle.step_all_cores(g, x2, e2, wc, sc, 0.05, k, k, rng=(9, t))
+        assert threads >= 1
+        assert np.array_equal(x1.view(np.uint32), x2.view(np.uint32))
+        assert np.array_equal(e1.view(np.uint32), e2.view(np.uint32))
