@@ -236,6 +236,28 @@ liec_status liec_unpack_topk_message(liec_ctx *ctx, const uint32_t *idx, const f
  */
 liec_status liec_l2_norm(liec_ctx *ctx, const float *vec, int64_t n, double *norm_out);
 
+/*
+ * liec_l2_norm_static: liec_l2_norm for callers that cannot allocate device
+ * memory or wait for the device -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  It needs no context, allocates
+ * nothing, copies nothing to the host and does not synchronise: two kernels are
+ * enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = null stream) of
+ * the current device, and the norm is written to the DEVICE double *norm_out
+ * (8-byte aligned) when they have run.
+ *   vec   DEVICE, n fp32 values, 4-byte aligned, read only
+ *   n     1 .. LIEC_L2_STATIC_MAX_N; anything else is LIEC_EINVAL
+ * The block partials live in a 32 KiB array that is part of the library's image
+ * on every GPU it runs on (held until the process ends); its address on a device
+ * is looked up at the first call on that device, which therefore should be made
+ * outside a capture.  All calls on one GPU share that array: calls that may
+ * overlap there (two streams, two threads) race and must be serialised by the
+ * caller.  The sum of squares is carried in fp64 in a fixed order; the result
+ * can differ from liec_l2_norm's in the last bits (the number of partials
+ * differs), not more.
+ */
+#define LIEC_L2_STATIC_MAX_N ((int64_t)1 << 32)
+liec_status liec_l2_norm_static(const float *vec, int64_t n, double *norm_out, void *hip_stream);
+
 /* Learning-rate schedules (the paper decays eta during training): takes effect
  * from the next liec_step. */
 liec_status liec_set_lr(liec_ctx *ctx, float lr);

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     liec_destroy,
     liec_get_info,
     liec_get_worker_desc,
+    liec_l2_norm_static,
     liec_set_lr,
     liec_set_random,
     liec_get_random,

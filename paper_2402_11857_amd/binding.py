@@ -96,6 +96,8 @@ def lib():
         L.liec_get_random.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
         L.liec_l2_norm.restype = ctypes.c_int
         L.liec_l2_norm.argtypes = [vp, vp, i64, ctypes.POINTER(ctypes.c_double)]
+        L.liec_l2_norm_static.restype = ctypes.c_int
+        L.liec_l2_norm_static.argtypes = [vp, i64, vp, vp]
         L.liec_force_search_mode.restype = ctypes.c_int
         L.liec_force_search_mode.argtypes = [vp, i32]
         L.liec_set_search_wait.restype = ctypes.c_int
@@ -223,6 +225,17 @@ def liec_get_worker_desc(ctx: int, N: int) -> Dict[str, list]:
 def liec_destroy(ctx: Optional[int]) -> None:
     if ctx:
         lib().liec_destroy(ctx)
+
+
+def liec_l2_norm_static(vec: torch.Tensor, out: torch.Tensor, n: Optional[int] = None, stream: Optional[int] = None) -> None:
+    """l2 norm of the first n values (default: all) of a contiguous fp32 device tensor into out[0] (a float64
+    device tensor), enqueued on `stream` (default: the null stream); nothing is allocated or waited for."""
+    if not (vec.is_cuda and vec.dtype == torch.float32 and vec.is_contiguous()):
+        raise TypeError("liec_l2_norm_static needs a contiguous fp32 device tensor")
+    if not (out.is_cuda and out.dtype == torch.float64 and out.numel() >= 1):
+        raise TypeError("liec_l2_norm_static writes to a float64 device tensor")
+    count = vec.numel() if n is None else int(n)
+    _check(lib().liec_l2_norm_static(vec.data_ptr(), count, out.data_ptr(), stream), "liec_l2_norm_static")
 
 
 def device_copy(dst: torch.Tensor, src: torch.Tensor, stream: Optional[int] = None) -> None:

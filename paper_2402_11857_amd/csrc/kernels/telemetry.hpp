@@ -20,13 +20,14 @@ __global__ __launch_bounds__(kBlock) void k_sumsq(const float* __restrict__ v, u
     if (threadIdx.x == 0) partial[blockIdx.x] = s;
 }
 
+// take_root: write the norm itself (the correctly rounded square root of the sum) instead of the sum.
 __global__ __launch_bounds__(kBlock) void k_sumsq_final(const double* __restrict__ partial, uint32_t nparts,
-                                                         double* __restrict__ out) {
+                                                         double* __restrict__ out, bool take_root) {
     __shared__ double lds_w[4];
     double acc = 0.0;
     for (uint32_t q = threadIdx.x; q < nparts; q += kBlock) acc += partial[q];
     const double s = block_sum_f64(acc, lds_w);
-    if (threadIdx.x == 0) *out = s;
+    if (threadIdx.x == 0) *out = take_root ? __dsqrt_rn(s) : s;
 }
 
 // Plain device copy (128 bits per thread, streaming hints), used to measure the achievable

@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -54,6 +55,38 @@ struct ProfEvent {
     hipEvent_t start, stop;
     int slot;
 };
+
+}  // namespace
+
+// Block partials of liec_l2_norm_static: device memory the library never allocates or frees.  Every GPU
+// the library runs on holds its own copy (32 KiB) at its own address until the process ends; in host code
+// the name below only stands for the symbol, the address on a device comes from static_scratch().
+constexpr int kL2StaticBlocks = 4096;
+static __device__ __align__(256) double scratch[kL2StaticBlocks];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on the current device, looked up once per device with that device current.
+hipError_t static_scratch(double** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<double*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 }  // namespace
 
@@ -958,7 +991,7 @@ liec_status liec_l2_norm(liec_ctx* c, const float* vec, int64_t n, double* norm_
     // s_partial holds agg_blocks doubles; one more double behind the worker partials receives the sum
     const uint32_t blocks = (uint32_t)std::min<int64_t>((n + kBlock - 1) / kBlock, (int64_t)std::min<uint32_t>(c->agg_blocks, 4096u));
     k_sumsq<<<blocks, kBlock, 0, c->stream>>>(vec, (uint64_t)n, c->s_partial);
-    k_sumsq_final<<<1, kBlock, 0, c->stream>>>(c->s_partial, blocks, c->w_partial);
+    k_sumsq_final<<<1, kBlock, 0, c->stream>>>(c->s_partial, blocks, c->w_partial, false);
     double sum = 0.0;
     if (hipGetLastError() != hipSuccess ||
         hipMemcpyAsync(&sum, c->w_partial, sizeof sum, hipMemcpyDeviceToHost, c->stream) != hipSuccess ||
@@ -968,6 +1001,22 @@ liec_status liec_l2_norm(liec_ctx* c, const float* vec, int64_t n, double* norm_
     }
     *norm_out = std::sqrt(sum);
     return LIEC_OK;
+}
+
+liec_status liec_l2_norm_static(const float* vec, int64_t n, double* norm_out, void* hip_stream) {
+    if (!vec || !norm_out || n < 1 || n > LIEC_L2_STATIC_MAX_N) return LIEC_EINVAL;
+    if (((uintptr_t)vec & 3u) || ((uintptr_t)norm_out & 7u)) return LIEC_EINVAL;
+    double* partial = nullptr;                                  // this device's copy of `scratch`
+    if (static_scratch(&partial) != hipSuccess) {
+        (void)hipGetLastError();
+        return LIEC_EDEVICE;
+    }
+    hipStream_t st = (hipStream_t)hip_stream;
+    // every partial the second kernel reads is written by the first: nothing of an earlier call survives
+    const uint32_t blocks = (uint32_t)std::min<int64_t>((n + kBlock - 1) / kBlock, (int64_t)kL2StaticBlocks);
+    k_sumsq<<<blocks, kBlock, 0, st>>>(vec, (uint64_t)n, partial);
+    k_sumsq_final<<<1, kBlock, 0, st>>>(partial, blocks, norm_out, true);
+    return hipGetLastError() == hipSuccess ? LIEC_OK : LIEC_EDEVICE;
 }
 
 liec_status liec_set_lr(liec_ctx* c, float lr) {
