@@ -103,6 +103,7 @@ def run_workload(w, steps: int, warmup: int, seed: int = 0):
         elapsed, (upd_ms, upd_n) = regions[len(regions) // 2]
         info, status = ctx.info_status()
         assert status == 0, "non-finite values met during the bench"
+        band_misses = int(info.band_misses)      # row-steps of warm-up + timed regions whose predicted band failed
         # diagnostic breakdown, outside the timed region: every kernel bracketed by events
         nb = min(steps, 10)
         ctx.profile_begin(nb)
@@ -130,6 +131,7 @@ def run_workload(w, steps: int, warmup: int, seed: int = 0):
         "sync_ms": sync_ms,
         "wire": wire,
         "worst": worst,
+        "band_misses": band_misses,
         "sync_gbps": dominant_kernel_bytes(w) / (sync_ms * 1e-3) / 1e9,   # same bytes: g, x in, x out, e in/out
     }
     out["update_avg_ms"] = upd_ms / upd_n
@@ -325,6 +327,7 @@ def main() -> int:
                           "averaging_iteration_ms": round(r["sync_ms"], 4),
                           "wire_worker0": r["wire"],
                           "outside_steady_state": r["worst"],
+                          "band_misses_in_warmup_and_timed_regions": r["band_misses"],
                           "kernels_ms_per_step": {k: round(v, 4) for k, v in r["kernels_ms_per_step"].items()}}
             if name in CACHE_RESIDENT:
                 also[name]["note"] = CACHE_RESIDENT[name]
@@ -365,6 +368,7 @@ def main() -> int:
         "scratch_bytes": main_res["scratch_bytes"],
         "wire_worker0": main_res["wire"],
         "outside_steady_state": main_res["worst"],
+        "band_misses_in_warmup_and_timed_regions": main_res["band_misses"],
         "averaging_iteration": {"ms": round(main_res["sync_ms"], 4), "alg_gbps": round(main_res["sync_gbps"], 1),
                                 "note": "Algorithm 1's uncompressed iteration, one in every `period` steps; not part of value"},
         # Algorithm 1 as a whole with the averaging periods of the paper's experiments, from the two measured times

@@ -74,6 +74,11 @@ typedef struct {
                                  threshold search fell to the general single-block
                                  search -- constant or near-constant rows; results are
                                  exact either way, such rows only take much longer   */
+    int64_t band_misses;      /* top-k: row-steps, since the context was created, whose
+                                 threshold fell outside the band predicted from the
+                                 previous steps, so that the row needed two more passes
+                                 (steps without a prediction, such as the first, do not
+                                 count); results are exact either way               */
 } liec_info;
 
 /*

@@ -27,6 +27,20 @@ extern "C" {
 liec_status liec_force_search_mode(liec_ctx *ctx, int32_t mode);
 
 /*
+ * Testing and tuning aid: the state the threshold search of row `row` (0 .. N - 1:
+ * worker rows, N: the server's vector) is in after the last step, copied to the
+ * HOST array `out` of 8 words: out[0] mode the next step starts in (0, 1 or 4 as
+ * above), out[1] / out[2] lower / upper end of the band of keys predicted for the
+ * next step, out[3] candidates the last step listed, out[4] steps so far whose
+ * predicted band failed, out[5] the predictor's current swing (an eighth of the
+ * band's half width unless a floor or the last change of the threshold decides),
+ * out[6] 1 if the last step took the general search, out[7] reserved (0).
+ * Synchronises the stream.  LIEC_EINVAL for a row out of range or one whose
+ * operator has no threshold search.
+ */
+liec_status liec_get_search_state(liec_ctx *ctx, int32_t row, uint32_t *out);
+
+/*
  * Testing aid for the general search (mode 4 above, also what constant or
  * mostly-zero rows fall to): several thread blocks share a row and wait for one
  * another between its phases; `polls` bounds each wait (default 65536, about 0.2 s).

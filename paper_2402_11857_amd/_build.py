@@ -22,14 +22,15 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found: the HIP library cannot be built")
 
 
-def build_library(verbose: bool = False) -> str:
+def build_library(verbose: bool = False, defines=(), out: str = LIB_PATH) -> str:
     """Always recompiles.  -ffp-contract=off keeps every fp32 expression a single IEEE operation;
-    packed fp32 instructions are disabled for the device pass."""
+    packed fp32 instructions are disabled for the device pass.  `defines` (NAME=value strings) and `out`
+    let a tuning run build a variant of the library beside the product's."""
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-ffp-contract=off", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-command-line-argument",
+           "-Wall", "-Wno-unused-command-line-argument"] + [f"-D{d}" for d in defines] + [
            "-I", os.path.join(_ROOT, "include"), "-I", os.path.join(_HERE, "csrc"),
-           "-o", LIB_PATH] + SOURCES
+           "-o", out] + SOURCES
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -37,7 +38,7 @@ def build_library(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
     if verbose and res.stderr.strip():
         print(res.stderr)
-    return LIB_PATH
+    return out
 
 
 if __name__ == "__main__":

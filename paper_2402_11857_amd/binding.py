@@ -44,6 +44,7 @@ class LiecInfo(ctypes.Structure):
         ("server_cutoff", ctypes.c_int64),
         ("nonfinite", ctypes.c_int32),
         ("slow_rows", ctypes.c_int32),
+        ("band_misses", ctypes.c_int64),
     ]
 
 
@@ -102,6 +103,8 @@ def lib():
         L.liec_force_search_mode.argtypes = [vp, i32]
         L.liec_set_search_wait.restype = ctypes.c_int
         L.liec_set_search_wait.argtypes = [vp, i32]
+        L.liec_get_search_state.restype = ctypes.c_int
+        L.liec_get_search_state.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_uint32)]
         L.liec_set_group_bitmap.restype = ctypes.c_int
         L.liec_set_group_bitmap.argtypes = [vp, i32]
         L.liec_get_info.restype = ctypes.c_int
@@ -325,6 +328,12 @@ class LiecContext:
 
     def set_search_wait(self, polls: int) -> None:
         _check(lib().liec_set_search_wait(self._h, polls), "liec_set_search_wait")
+
+    def search_state(self, row: int) -> Dict[str, int]:
+        out = (ctypes.c_uint32 * 8)()
+        _check(lib().liec_get_search_state(self._h, row, out), "liec_get_search_state")
+        return {"mode": out[0], "lo": out[1], "hi": out[2], "listed": out[3], "misses": out[4], "swing": out[5],
+                "general_search": out[6]}
 
     def set_group_bitmap(self, per_line: int) -> None:
         _check(lib().liec_set_group_bitmap(self._h, per_line), "liec_set_group_bitmap")

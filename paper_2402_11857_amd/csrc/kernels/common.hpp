@@ -24,18 +24,22 @@ constexpr int kSureStripes = 16;        // counters per row for the keys above t
 constexpr int kListBits = 13;           // widest radix digit of the list select (two digits cover a band of 2^26 keys)
 constexpr int kListBins = 1 << kListBits;
 constexpr int kStage = 512;             // per-wave LDS staging slots of the candidate filter
+constexpr int kDirectList = 16384;      // candidate lists up to this length are selected by one block on its own
+constexpr int kShortCap = 4096;         // entries of the first list digit's bin that are handed to the list select on their own
 constexpr int kTieCap = 4096;           // ties at the threshold the fast path resolves
-constexpr uint32_t kBandMargin = 1u << 18;   // least half width, in key units, of the predicted band (about 2 % in value)
+constexpr uint32_t kBandStart = 1u << 17;    // swing (an eighth of the band's half width) after a step without a prediction
+constexpr uint32_t kBandFloor = 1u << 15;    // least half width, in key units, of the predicted band (about 0.27 % in value)
 constexpr uint32_t kUpdatePanel = 4096; // column tiles per panel of the update kernel
 
 enum Comp : int { kIdentity = 0, kSign = 1, kTopk = 2, kBlockSign = 3, kRandk = 4 };
 
-// Progress of a row's top-k threshold search within one step.
+// How a row's top-k threshold search starts its step.  A row's mode changes only where one block speaks
+// for the row (the list select, the general search); in between, every kernel re-derives what the row
+// needs from the mode and the row's counters.
 enum SelMode : uint32_t {
     kWarm = 0,      // a band [lo, hi) predicted from the previous step is filtered
-    kCold = 1,      // no usable prediction: the first radix digit of the whole row is needed
-    kColdBand = 2,  // band = the first-digit bin holding rank k; filtered by the second filter pass
-    kSlow = 4       // needs the general (single block, multi pass) search over the row
+    kCold = 1,      // no prediction: the band is the first-radix-digit bin holding rank k
+    kSlow = 4       // needs the general (multi pass) search over the row
 };
 
 // One per worker row, plus one (index N) for the server's vector v.
@@ -50,17 +54,21 @@ struct RowDesc {
     uint32_t nonfinite_acc;
     uint32_t lo, hi;       // candidate band: keys in [lo, hi) are listed, keys >= hi are surely kept
     uint32_t mode;         // SelMode
-    uint32_t n_cand;       // candidates appended so far (may exceed the capacity: overflow)
-    uint32_t n_sure[kSureStripes];   // keys at or above the band seen by the filter pass; block b of the filter adds
+    uint32_t n_cand;       // candidates the pass over the predicted band appended (may exceed the capacity: overflow)
+    uint32_t n_sure[kSureStripes];   // keys at or above that band seen by the pass; block b of the filter adds
                            // to stripe b % kSureStripes (one address would serialise the blocks' atomics)
-    uint32_t n_ties;       // ties collected
+    uint32_t n_cand2;      // the same two counts for the pass over the first-digit band, which runs when there is
+    uint32_t n_sure2[kSureStripes];  // no prediction or the predicted band failed (its own set, so that every
+                           // kernel can still tell from the first set that the row needed this pass)
+    uint32_t n_short;      // entries of the first list digit's bin collected into the row's short list
     uint32_t n_list;       // candidates that were listed when the search finished (random-k marks the kept ones)
     uint32_t dense;        // the row's candidate bitmap is not valid: test every column
-    uint32_t sel_bin;      // list select: first digit of (tau - lo)
-    uint32_t sel_rank;     // list select: rank of tau inside that digit's bin
     uint32_t prev_tau;     // tau of the step before (valid when have_prev)
     uint32_t have_prev;
-    uint32_t was_cold;     // this step's band came from the first-digit histogram, not from a prediction
+    uint32_t misses;       // steps in which the predicted band was not usable (since the context was created)
+    uint32_t centre;       // where the last prediction expected tau
+    uint32_t swing;        // decaying maximum of the distances between tau and that centre
+    uint32_t was_cold;     // the last band came from the first-digit histogram, not from a prediction
 };
 
 __host__ __device__ __forceinline__ uint32_t sure_count(const RowDesc& r) {
@@ -69,9 +77,19 @@ __host__ __device__ __forceinline__ uint32_t sure_count(const RowDesc& r) {
     for (int q = 0; q < kSureStripes; ++q) n += r.n_sure[q];
     return n;
 }
-__host__ __device__ __forceinline__ void clear_sure(RowDesc& r) {
+__host__ __device__ __forceinline__ uint32_t sure_count2(const RowDesc& r) {
+    uint32_t n = 0;
 #pragma unroll
-    for (int q = 0; q < kSureStripes; ++q) r.n_sure[q] = 0;
+    for (int q = 0; q < kSureStripes; ++q) n += r.n_sure2[q];
+    return n;
+}
+// Both passes' counters back to zero (whoever finishes a row's search calls it).
+__host__ __device__ __forceinline__ void clear_counts(RowDesc& r) {
+    r.n_cand = 0;
+    r.n_cand2 = 0;
+    r.n_short = 0;
+#pragma unroll
+    for (int q = 0; q < kSureStripes; ++q) r.n_sure[q] = r.n_sure2[q] = 0;
 }
 
 // After a filter pass: the band is usable when its list did not overflow and rank k falls inside it.
@@ -80,13 +98,10 @@ __device__ __forceinline__ bool band_ok(const RowDesc& r, uint32_t cap, uint32_t
     return r.n_cand <= cap && n_sure < k && (uint64_t)k <= (uint64_t)n_sure + r.n_cand &&
            r.hi - r.lo <= (1u << (2 * kListBits));       // the list select's two digits must span the band
 }
-// Rows that need the first-digit histogram: no prediction, or the predicted band failed.
+// Rows that need the first-digit histogram: no prediction, or the predicted band failed.  Stable from the
+// end of the pass over the predicted band until the row's search is finished.
 __device__ __forceinline__ bool wants_cold(const RowDesc& r, uint32_t cap, uint32_t k) {
     return r.mode == kCold || (r.mode == kWarm && !band_ok(r, cap, k));
-}
-// Rows whose candidate list holds rank k (evaluated after both filter passes).
-__device__ __forceinline__ bool listable(const RowDesc& r, uint32_t cap, uint32_t k) {
-    return (r.mode == kWarm || r.mode == kColdBand) && band_ok(r, cap, k);
 }
 
 // Radix digits of the 31-bit magnitude key, most significant first.

@@ -6,28 +6,30 @@ namespace liec {
 
 // ---------------------------------------------------------------------------------------------
 // Top-k (Definition 2).  The k-th largest magnitude key tau of a row and the index cut-off
-// among its ties are found without sorting:
-//   1. k_filter streams the row once against a band [lo, hi) of keys expected to hold tau:
-//      keys >= hi are only counted, keys inside the band are appended to a candidate list
-//      (key, index), and a group bitmap is written for the aggregation kernel, in one of two
-//      forms the host picks from the row length.  Fine: 4 words of 64 bits per wave tile, bit l of word u
-//      set when any of the 4 columns 1024t + 256u + 4l .. + 3 has key >= lo.  Coarse: one word
-//      per wave tile, bit 16u + m set when any of the 16 columns 1024t + 256u + 16m .. + 15 (one
-//      64-byte line, the unit a gather fetches anyway) has one -- 8 bytes written per 4 KiB read
-//      (writes are what a read stream pays most for); measured faster for rows of 48M columns
-//      and more, slower for 25M.
-//      The band is predicted from the previous step's tau (kWarm).  It is usable when the list
-//      did not overflow and rank k falls inside it (band_ok); when there is no prediction, or it is not
-//      usable, the band becomes the first-radix-digit bin holding rank k, found by k_hist0 +
-//      k_pick_band over the whole row (-> kColdBand), and the row is filtered again.
-//   2. k_list_hist<0>, k_list_hist<1>, k_list_ties and k_list_finish run a 2-digit radix select on
-//      the listed keys, taken relative to the band's lower end, and order the ties by index (up to
-//      4096 of them through a buffer, more by a radix select over the listed indices).
-//   3. Rows whose band the list cannot hold (constant or near-constant rows) take k_slow_select.
-// All decisions are taken on the device per row, each kernel re-deriving from the row's counters
-// whether it has work; a row's mode is changed only where one thread speaks for the row (k_pick_band,
-// k_list_finish, the block of k_slow_select that finds the cut-off).  The host always enqueues the same
-// kernels.
+// among its ties are found without sorting, by five kernels the host enqueues every step:
+//   1. k_filter (pass over the predicted band) streams the row once against a band [lo, hi) of keys
+//      expected to hold tau, predicted from the previous steps' tau (rows in kWarm mode): keys >= hi are
+//      only counted, keys inside the band are appended to a candidate list (key, index), and a group
+//      bitmap is written for the aggregation kernel, in one of two forms the host picks from the row
+//      length.  Fine: 4 words of 64 bits per wave tile, bit l of word u set when any of the 4 columns
+//      1024t + 256u + 4l .. + 3 has key >= lo.  Coarse: one word per wave tile, bit 16u + m set when any
+//      of the 16 columns 1024t + 256u + 16m .. + 15 (one 64-byte line, the unit a gather fetches anyway)
+//      has one -- 8 bytes written per 4 KiB read (writes are what a read stream pays most for); measured
+//      faster for rows of 48M columns and more, slower for 25M.  The band is usable when the list did
+//      not overflow and rank k falls inside it (band_ok).
+//   2. k_hist0, for rows without a prediction (kCold) or whose predicted band was not usable: the
+//      histogram of the first radix digit (12 bits) of the whole row.
+//   3. k_filter (pass over the first-digit band), for the same rows: every block picks the bin holding
+//      rank k from that histogram, and the row is filtered again with that bin as its band, counting
+//      into a second set of counters.
+//   4. k_list_select, one block per row: a 2-digit radix select on the listed keys, taken relative to
+//      the band's lower end, then the ties in index order (up to 4096 of them through LDS, more by a
+//      radix select over the listed indices); writes (tau, cut-off), predicts the next band.  Rows
+//      whose band the list cannot hold (constant or near-constant rows) are put into kSlow mode.
+//   5. k_slow_select takes the kSlow rows.
+// All decisions are taken on the device per row, each kernel re-deriving from the row's mode and
+// counters whether it has work; kernels 2, 3 and 5 return at once in the steady state.  A row's mode
+// and its result are written only by k_list_select and k_slow_select.
 // `row0` is added to blockIdx.y to address per-row state (the server's vector uses row N).
 // ---------------------------------------------------------------------------------------------
 // Bit m of the result: some lane of 4m .. 4m + 3 has its bit set in the ballot (those four lanes own one
@@ -68,20 +70,130 @@ __device__ __forceinline__ uint64_t filter_chunk(const uint32_t (&keys)[4], uint
     return __ballot(lo4 != 0);
 }
 
+// List select: the keys of a band are taken relative to its lower end and need b <= 26 bits.  The first
+// digit is their top kFirstBits bits when many blocks build its histogram in global memory (256 bins: the
+// blocks' LDS histograms then merge with few global atomics, which are slow across the chip's dies), or up
+// to kListBits bits when one block builds it in LDS; the following digits take up to kListBits bits each.
+constexpr int kFirstBits = 8;
+__device__ __forceinline__ int band_bits(uint32_t width) {            // width: 1 .. 2^26
+    return width > 1 ? 32 - __clz((int)(width - 1)) : 1;
+}
+__device__ __forceinline__ int first_shift(uint32_t width, int first_bits) {   // bits below the first digit
+    const int b = band_bits(width);
+    return b > first_bits ? b - first_bits : 0;
+}
+
+// Blocks that share a pass over a list of n entries: one per 2048 entries.
+__device__ __forceinline__ uint32_t list_blocks_for(uint32_t n, uint32_t grid) {
+    const uint32_t want = (n + 2047u) / 2048u;
+    return want < 1u ? 1u : (want > grid ? grid : want);
+}
+
+// The two passes over a row's candidate list that are shared by many blocks.  They ride in the two kernels
+// that otherwise only work for rows without a usable prediction (k_hist0 and the second k_filter pass), for the
+// rows whose predicted band holds rank k:
+//   list_first_digit  adds the first digit of every listed key to the row's global histogram;
+//   list_collect      picks the bin holding rank k from that histogram (every block redoes the pick) and, when
+//                     that bin has at most kShortCap entries, appends them to the row's short list.
+// k_list_select then finishes on the short list alone.  Lists of at most kDirectList entries skip both: one block
+// walks those as fast as the shared passes' fixed costs.  Every thread of the block calls them.
+__device__ __forceinline__ void list_first_digit(const RowDesc* __restrict__ desc, uint32_t row,
+                                                 const uint2* __restrict__ in, uint32_t* __restrict__ hrow,
+                                                 uint32_t* lds_h /* 256 words */) {
+    const uint32_t n = desc[row].n_cand, nb = list_blocks_for(n, gridDim.x);
+    if (n <= (uint32_t)kDirectList || blockIdx.x >= nb) return;
+    const uint32_t lo = desc[row].lo, lane = threadIdx.x & 63;
+    const int shift = first_shift(desc[row].hi - lo, kFirstBits);
+    for (uint32_t b = threadIdx.x; b < 256; b += blockDim.x) lds_h[b] = 0;
+    __syncthreads();
+    for (uint32_t base = blockIdx.x * blockDim.x; base < n; base += nb * blockDim.x) {    // uniform for the block
+        const uint32_t e = base + threadIdx.x;
+        const bool valid = e < n;
+        const uint32_t key = valid ? in[e].x : lo;
+        wave_count(lds_h, valid, (key - lo) >> shift, lane);
+    }
+    __syncthreads();
+    for (uint32_t b = threadIdx.x; b < 256; b += blockDim.x) {
+        const uint32_t c = lds_h[b];
+        if (c) atomicAdd(&hrow[b], c);
+    }
+}
+
+__device__ __forceinline__ void list_collect(RowDesc* __restrict__ desc, uint32_t row, const uint2* __restrict__ in,
+                                             const uint32_t* __restrict__ hrow, uint2* __restrict__ out, uint32_t k,
+                                             uint32_t* part, uint32_t* res) {
+    const uint32_t n = desc[row].n_cand, nb = list_blocks_for(n, gridDim.x);
+    if (n <= (uint32_t)kDirectList || blockIdx.x >= nb) return;
+    const uint32_t lo = desc[row].lo, lane = threadIdx.x & 63;
+    const int shift = first_shift(desc[row].hi - lo, kFirstBits);
+    const Pick p = block_pick(hrow, 1 << kFirstBits, k - sure_count(desc[row]), part, res);
+    if (p.count > (uint32_t)kShortCap) return;                  // too many for the short list: k_list_select walks the list
+    for (uint32_t base = blockIdx.x * blockDim.x; base < n; base += nb * blockDim.x) {    // uniform for the block
+        const uint32_t e = base + threadIdx.x;
+        const uint2 kv = e < n ? in[e] : make_uint2(0u, 0u);
+        const bool hit = e < n && ((kv.x - lo) >> shift) == p.bin;
+        const uint64_t m = __ballot(hit);
+        if (m) {                                                // wave-uniform
+            uint32_t at = 0;
+            if (lane == 0) at = atomicAdd(&desc[row].n_short, (uint32_t)__popcll(m));
+            at = __builtin_amdgcn_readfirstlane(at);
+            if (hit) out[at + lanes_below(m)] = kv;             // the bin's count bounds the total: at most kShortCap
+        }
+    }
+}
+
+// The band a row is filtered against and the counters the pass adds to.  cold_pass false: rows in kWarm
+// mode, their predicted band, the first counter set.  cold_pass true: rows for which wants_cold holds,
+// the first-digit bin that holds rank k (every block redoes that pick from the row's finished histogram;
+// needs 256 threads and 259 words of LDS), the second counter set.  False when the block has no work.
+struct FilterBand {
+    uint32_t lo, hi;
+    uint32_t* n_cand;
+    uint32_t* n_sure;
+};
+__device__ __forceinline__ bool filter_band(RowDesc* __restrict__ desc, uint32_t row, bool cold_pass,
+                                            const uint32_t* __restrict__ ghist, uint32_t cap, uint32_t k,
+                                            uint32_t* part, uint32_t* res, FilterBand& fb) {
+    if (!cold_pass) {
+        if (desc[row].mode != kWarm) return false;
+        fb.lo = desc[row].lo;
+        fb.hi = desc[row].hi;
+        fb.n_cand = &desc[row].n_cand;
+        fb.n_sure = desc[row].n_sure;
+        return true;
+    }
+    if (!wants_cold(desc[row], cap, k)) return false;
+    const Pick p = block_pick(ghist + (size_t)row * kHistBins, kHistBins, k, part, res);
+    if (p.count > cap) return false;             // the list cannot hold the bin: the row takes the general search
+    fb.lo = p.bin << 19;
+    fb.hi = (p.bin + 1) << 19;                   // 0x80000000 for the top bin: no key reaches it
+    fb.n_cand = &desc[row].n_cand2;
+    fb.n_sure = desc[row].n_sure2;
+    return true;
+}
+
 // RK: the keys are the priorities of a random-k draw (nothing is read from src), and instead of the
 // group bitmap the kernel writes, per column, whether its key is at or above the band (lane-major
 // half-words like the sign bits, at row `row` of kbits); k_rk_mark later adds the kept candidates.
 template <bool VEC, bool RK>
 __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src, size_t row_stride, uint32_t d,
                                                     uint32_t nwt, uint32_t row0, RowDesc* __restrict__ desc,
-                                                    uint32_t expect_mode, uint64_t* __restrict__ gbits,
+                                                    bool cold_pass, const uint32_t* __restrict__ ghist, uint32_t k,
+                                                    uint64_t* __restrict__ gbits,
                                                     uint16_t* __restrict__ kbits, uint2* __restrict__ list, uint32_t cap,
-                                                    RkDraw rk, bool coarse) {
+                                                    uint2* __restrict__ shortl, RkDraw rk, bool coarse, uint32_t run) {
     __shared__ uint2 stage[4][kStage];
     __shared__ uint32_t wsure[4];
+    __shared__ uint32_t part[256], res[3];
     const uint32_t row = row0 + blockIdx.y;
-    if (desc[row].mode != expect_mode) return;                 // uniform for the block
-    const uint32_t lo = desc[row].lo, hi = desc[row].hi;
+    if (cold_pass && desc[row].mode == kWarm && !wants_cold(desc[row], cap, k)) {   // uniform for the block
+        list_collect(desc, row, list + (size_t)row * cap, ghist + (size_t)row * kHistBins,
+                     shortl + (size_t)row * kShortCap, k, part, res);
+        return;
+    }
+    FilterBand fb;
+    if (!filter_band(desc, row, cold_pass, ghist, cap, k, part, res, fb)) return;   // uniform for the block
+    const uint32_t lo = fb.lo, hi = fb.hi;
     const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
     uint2* __restrict__ out = list + (size_t)row * cap;
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -94,7 +206,10 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
     uint2* st = stage[wave];
     uint32_t cnt = 0;                                           // staged candidates (wave-uniform)
     uint32_t n_hi = 0, kmax = 0;                                // per lane: keys >= hi seen, largest key seen
-    for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
+    // a wave takes `run` consecutive wave tiles at a time and a block 4 * run (long rows: 4, so that the
+    // group words one block writes fill whole lines of the bitmap; short rows: 1, more blocks in flight)
+    for (uint32_t tb = (blockIdx.x * 4 + wave) * run; tb < nwt; tb += gridDim.x * 4 * run)
+    for (uint32_t t = tb; t < min(tb + run, nwt); ++t) {
         float4 a[4];
         if (!RK) {
 #pragma unroll
@@ -132,7 +247,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
                 if (cnt + m > kStage) {                         // flush the staged candidates
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     uint32_t base = 0;
-                    if (lane == 0) base = atomicAdd(&desc[row].n_cand, cnt);
+                    if (lane == 0) base = atomicAdd(fb.n_cand, cnt);
                     base = __builtin_amdgcn_readfirstlane(base);
                     for (uint32_t s = lane; s < cnt; s += 64)
                         if (base + s < cap) out[base + s] = st[s];
@@ -163,7 +278,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
     if (cnt) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         uint32_t base = 0;
-        if (lane == 0) base = atomicAdd(&desc[row].n_cand, cnt);
+        if (lane == 0) base = atomicAdd(fb.n_cand, cnt);
         base = __builtin_amdgcn_readfirstlane(base);
         for (uint32_t s = lane; s < cnt; s += 64)
             if (base + s < cap) out[base + s] = st[s];
@@ -174,7 +289,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
     __syncthreads();
     if (threadIdx.x == 0) {
         const uint32_t n = wsure[0] + wsure[1] + wsure[2] + wsure[3];
-        if (n) atomicAdd(&desc[row].n_sure[blockIdx.x % kSureStripes], n);
+        if (n) atomicAdd(&fb.n_sure[blockIdx.x % kSureStripes], n);
     }
 }
 
@@ -185,23 +300,32 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
 // keys above the band, the candidate list, and the bits of the columns above the band -- set with
 // atomic ORs into a bitmap that k_rk_zero cleared.  grid = (blocks, rows).
 __global__ __launch_bounds__(kBlock) void k_rk_zero(uint32_t nwt, uint32_t row0, const RowDesc* __restrict__ desc,
-                                                     uint32_t expect_mode, uint16_t* __restrict__ kbits) {
+                                                     bool cold_pass, uint32_t cap, uint32_t k,
+                                                     uint16_t* __restrict__ kbits) {
     const uint32_t row = row0 + blockIdx.y;
-    if (desc[row].mode != expect_mode) return;
+    if (cold_pass ? !wants_cold(desc[row], cap, k) : desc[row].mode != kWarm) return;
     uint32_t* __restrict__ words = reinterpret_cast<uint32_t*>(kbits + (size_t)row * nwt * 64);
     const uint32_t n = nwt * 32;
     for (uint32_t q = blockIdx.x * kBlock + threadIdx.x; q < n; q += gridDim.x * kBlock) words[q] = 0u;
 }
 
 __global__ __launch_bounds__(kBlock) void k_rk_filter_inverse(uint32_t d, uint32_t nwt, uint32_t row0,
-                                                               RowDesc* __restrict__ desc, uint32_t expect_mode,
+                                                               RowDesc* __restrict__ desc, bool cold_pass,
+                                                               const uint32_t* __restrict__ ghist, uint32_t k,
                                                                uint16_t* __restrict__ kbits, uint2* __restrict__ list,
-                                                               uint32_t cap, RkDraw rk) {
+                                                               uint32_t cap, uint2* __restrict__ shortl, RkDraw rk) {
     __shared__ uint2 stage[4][kStage];
     __shared__ uint32_t wsure[4];
+    __shared__ uint32_t part[256], res[3];
     const uint32_t row = row0 + blockIdx.y;
-    if (desc[row].mode != expect_mode) return;                 // uniform for the block
-    const uint32_t lo = desc[row].lo, hi = desc[row].hi;
+    if (cold_pass && desc[row].mode == kWarm && !wants_cold(desc[row], cap, k)) {   // uniform for the block
+        list_collect(desc, row, list + (size_t)row * cap, ghist + (size_t)row * kHistBins,
+                     shortl + (size_t)row * kShortCap, k, part, res);
+        return;
+    }
+    FilterBand fb;
+    if (!filter_band(desc, row, cold_pass, ghist, cap, k, part, res, fb)) return;   // uniform for the block
+    const uint32_t lo = fb.lo, hi = fb.hi;
     uint2* __restrict__ out = list + (size_t)row * cap;
     uint32_t* __restrict__ words = reinterpret_cast<uint32_t*>(kbits + (size_t)row * nwt * 64);
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -228,7 +352,7 @@ __global__ __launch_bounds__(kBlock) void k_rk_filter_inverse(uint32_t d, uint32
             if (cnt + m > kStage) {
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 uint32_t at = 0;
-                if (lane == 0) at = atomicAdd(&desc[row].n_cand, cnt);
+                if (lane == 0) at = atomicAdd(fb.n_cand, cnt);
                 at = __builtin_amdgcn_readfirstlane(at);
                 for (uint32_t s = lane; s < cnt; s += 64)
                     if (at + s < cap) out[at + s] = st[s];
@@ -242,7 +366,7 @@ __global__ __launch_bounds__(kBlock) void k_rk_filter_inverse(uint32_t d, uint32
     if (cnt) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         uint32_t at = 0;
-        if (lane == 0) at = atomicAdd(&desc[row].n_cand, cnt);
+        if (lane == 0) at = atomicAdd(fb.n_cand, cnt);
         at = __builtin_amdgcn_readfirstlane(at);
         for (uint32_t s = lane; s < cnt; s += 64)
             if (at + s < cap) out[at + s] = st[s];
@@ -253,18 +377,24 @@ __global__ __launch_bounds__(kBlock) void k_rk_filter_inverse(uint32_t d, uint32
     __syncthreads();
     if (threadIdx.x == 0) {
         const uint32_t n = wsure[0] + wsure[1] + wsure[2] + wsure[3];
-        if (n) atomicAdd(&desc[row].n_sure[blockIdx.x % kSureStripes], n);
+        if (n) atomicAdd(&fb.n_sure[blockIdx.x % kSureStripes], n);
     }
 }
 
-// First radix digit (12 bits) of every key of the rows that have no usable band.  grid = (blocks, rows).
+// First radix digit (12 bits) of every key of the rows that have no usable band; for the rows whose
+// predicted band holds rank k, the first digit of the listed keys instead (list_first_digit).  Either
+// histogram goes to the row's kHistBins words of `hist`.  grid = (blocks, rows).
 template <bool VEC, bool RK>
 __global__ __launch_bounds__(kBlock) void k_hist0(const float* __restrict__ src, size_t row_stride, uint32_t d,
                                                    uint32_t nwt, uint32_t row0, const RowDesc* __restrict__ desc,
-                                                   uint32_t* __restrict__ hist, uint32_t cap, uint32_t k, RkDraw rk) {
+                                                   uint32_t* __restrict__ hist, const uint2* __restrict__ list, uint32_t cap,
+                                                   uint32_t k, RkDraw rk) {
     __shared__ uint32_t h[kHistBins];
     const uint32_t row = row0 + blockIdx.y;
-    if (!wants_cold(desc[row], cap, k)) return;
+    if (!wants_cold(desc[row], cap, k)) {                       // uniform for the block
+        if (desc[row].mode == kWarm) list_first_digit(desc, row, list + (size_t)row * cap, hist + (size_t)row * kHistBins, h);
+        return;
+    }
     const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
     for (int b = threadIdx.x; b < kHistBins; b += kBlock) h[b] = 0;
     __syncthreads();
@@ -306,130 +436,13 @@ __global__ __launch_bounds__(kBlock) void k_hist0(const float* __restrict__ src,
     }
 }
 
-// grid = rows.  For the rows k_hist0 worked on: the band becomes the first-digit bin that holds rank k.
-__global__ __launch_bounds__(kBlock) void k_pick_band(uint32_t row0, RowDesc* __restrict__ desc,
-                                                       uint32_t* __restrict__ hist, uint32_t cap, uint32_t k) {
-    __shared__ uint32_t part[256], res[3];
-    const uint32_t row = row0 + blockIdx.x;
-    if (!wants_cold(desc[row], cap, k)) return;
-    uint32_t* __restrict__ h = hist + (size_t)row * kHistBins;
-    const Pick p = block_pick(h, kHistBins, k, part, res);
-    for (int b = threadIdx.x; b < kHistBins; b += kBlock) h[b] = 0;
-    if (threadIdx.x == 0) {
-        RowDesc r = desc[row];
-        r.lo = p.bin << 19;
-        r.hi = (p.bin + 1) << 19;            // 0x80000000 for the top bin: no key reaches it
-        r.n_cand = 0;
-        clear_sure(r);
-        r.was_cold = 1;
-        r.mode = p.count <= cap ? kColdBand : kSlow;
-        desc[row] = r;
-    }
-}
-
-// Blocks of a list kernel that take part for a list of n entries: one per 2048 entries, so that a short
-// list does not pay every block's fixed cost (histogram pick, LDS clear, flush).
-__device__ __forceinline__ uint32_t list_blocks_for(uint32_t n, uint32_t grid) {
-    const uint32_t want = (n + 2047u) / 2048u;
-    return want < 1u ? 1u : (want > grid ? grid : want);
-}
-
-// List select: the keys of a band are taken relative to its lower end; the b bits that the band's width
-// needs (b <= 26) are split into a low digit of ceil(b/2) bits and a high digit of the rest, so a narrow
-// band (the usual 2^19 keys) gets two short histograms and a wide one still fits kListBins bins each.
-struct ListDigits {
-    int low_bits;
-    uint32_t low_bins, high_bins;    // histogram sizes, at least 256 (what block_pick walks)
-};
-__device__ __forceinline__ ListDigits list_digits(const RowDesc& r) {
-    const uint32_t width = r.hi - r.lo;                     // 1 .. 2^26 for a listable row
-    const int b = width > 1 ? 32 - __clz((int)(width - 1)) : 1;
-    ListDigits g;
-    g.low_bits = (b + 1) / 2;
-    g.low_bins = max(256u, 1u << g.low_bits);
-    g.high_bins = max(256u, 1u << (b - g.low_bits));
-    return g;
-}
-
-// P = 0: histogram of the high digit of every listed key.  P = 1: each block first redoes the pick of
-// the high digit from its finished histogram, then counts the low digits of the keys in that bin.
-// grid = (blocks, rows); lhist: [row][P][kListBins].
-template <int P>
-__global__ __launch_bounds__(kBlock) void k_list_hist(uint32_t row0, RowDesc* __restrict__ desc,
-                                                       const uint2* __restrict__ list, uint32_t cap, uint32_t k,
-                                                       uint32_t* __restrict__ lhist) {
-    __shared__ uint32_t h[kListBins];
-    __shared__ uint32_t part[256], res[3];
-    const uint32_t row = row0 + blockIdx.y;
-    if (!listable(desc[row], cap, k)) return;
-    const uint32_t n = desc[row].n_cand;                       // <= cap for a listable row
-    const uint32_t nb = list_blocks_for(n, gridDim.x);
-    if (blockIdx.x >= nb) return;
-    uint32_t* __restrict__ hrow = lhist + (size_t)row * 2 * kListBins;
-    const uint32_t lo = desc[row].lo;
-    const ListDigits dg = list_digits(desc[row]);
-    const int nbins = (int)(P == 0 ? dg.high_bins : dg.low_bins);
-    uint32_t bin0 = 0;
-    if constexpr (P == 1) {
-        const Pick p = block_pick(hrow, (int)dg.high_bins, k - sure_count(desc[row]), part, res);
-        bin0 = p.bin;
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            desc[row].sel_bin = p.bin;
-            desc[row].sel_rank = p.rank_in;
-        }
-    }
-    for (int b = threadIdx.x; b < nbins; b += kBlock) h[b] = 0;
-    __syncthreads();
-    const uint2* __restrict__ in = list + (size_t)row * cap;
-    const uint32_t low_mask = (1u << dg.low_bits) - 1u;
-    for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < n; e += nb * kBlock) {
-        const uint32_t rel = in[e].x - lo;
-        if (P == 0) atomicAdd(&h[rel >> dg.low_bits], 1u);
-        else if ((rel >> dg.low_bits) == bin0) atomicAdd(&h[rel & low_mask], 1u);
-    }
-    __syncthreads();
-    uint32_t* __restrict__ out = hrow + P * kListBins;
-    for (int b = threadIdx.x; b < nbins; b += kBlock) {
-        const uint32_t c = h[b];
-        if (c) atomicAdd(&out[b], c);
-    }
-}
-
-// Picks the low digit (-> tau, how many of its ties are kept, how many there are) and collects the
-// indices of the listed entries whose key equals tau when the tie buffer can hold them.  grid = (blocks, rows).
-__global__ __launch_bounds__(kBlock) void k_list_ties(uint32_t row0, RowDesc* __restrict__ desc,
-                                                       const uint2* __restrict__ list, uint32_t cap, uint32_t k,
-                                                       const uint32_t* __restrict__ lhist,
-                                                       uint32_t* __restrict__ tiebuf) {
-    __shared__ uint32_t part[256], res[3];
-    const uint32_t row = row0 + blockIdx.y;
-    if (!listable(desc[row], cap, k)) return;
-    const uint32_t n = desc[row].n_cand;
-    const uint32_t nb = list_blocks_for(n, gridDim.x);
-    if (blockIdx.x >= nb) return;
-    const uint32_t* __restrict__ hrow = lhist + (size_t)row * 2 * kListBins;
-    const ListDigits dg = list_digits(desc[row]);
-    const Pick p = block_pick(hrow + kListBins, (int)dg.low_bins, desc[row].sel_rank, part, res);
-    const uint32_t tau = desc[row].lo + ((desc[row].sel_bin << dg.low_bits) | p.bin);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        desc[row].tau = tau;
-        desc[row].rank = p.rank_in;
-        desc[row].ties = p.count;
-    }
-    if (p.count > (uint32_t)kTieCap) return;                    // too many for the buffer: k_list_finish selects by index
-    const uint2* __restrict__ in = list + (size_t)row * cap;
-    uint32_t* __restrict__ tb = tiebuf + (size_t)row * kTieCap;
-    for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < n; e += nb * kBlock) {
-        const uint2 kv = in[e];
-        if (kv.x == tau) {
-            const uint32_t pos = atomicAdd(&desc[row].n_ties, 1u);
-            if (pos < kTieCap) tb[pos] = kv.y;
-        }
-    }
-}
-
-// Band for the next step: centred on tau extrapolated by its last change, at least kBandMargin wide
-// on either side, wider when tau is moving or when the last prediction failed.
+// Band for the next step: centred on tau extrapolated by its last change.  Its half width follows how
+// far the thresholds actually fell from their predicted centres: eight times `swing`, a maximum of those
+// misses that decays by an eighth per step -- by a half while the last miss was under 1/512 of the band's
+// half width, so that very quiet rows narrow quickly -- never less than twice the last change of tau, between
+// kBandFloor and 2^25 key units.  After a step without a usable prediction the band starts 2^20 keys wide
+// on either side.  A band that misses costs two more passes over the row; one that is wider than needed
+// only lengthens the candidate list, hence the wide safety factor.
 __device__ __forceinline__ void predict_band(RowDesc& r, uint32_t fix_lo, uint32_t fix_hi) {
     if (fix_hi) {                                   // random-k: the band does not depend on the data
         r.lo = fix_lo;
@@ -441,9 +454,18 @@ __device__ __forceinline__ void predict_band(RowDesc& r, uint32_t fix_lo, uint32
     }
     const int64_t tau = (int64_t)r.tau;
     const int64_t delta = r.have_prev ? tau - (int64_t)r.prev_tau : 0;
-    int64_t margin = 2 * (delta < 0 ? -delta : delta);
-    if (margin < (int64_t)kBandMargin) margin = kBandMargin;
-    if (r.was_cold && margin < 4 * (int64_t)kBandMargin) margin = 4 * (int64_t)kBandMargin;
+    int64_t swing = kBandStart;
+    if (r.have_prev && !r.was_cold) {
+        int64_t miss = tau - (int64_t)r.centre;
+        if (miss < 0) miss = -miss;
+        const int64_t last = (int64_t)r.swing;
+        swing = 64 * miss < last ? last / 2 : last - last / 8;
+        if (swing < miss) swing = miss;
+    }
+    if (swing > (int64_t)1 << 22) swing = (int64_t)1 << 22;
+    int64_t margin = 8 * swing;
+    if (margin < 2 * (delta < 0 ? -delta : delta)) margin = 2 * (delta < 0 ? -delta : delta);
+    if (margin < (int64_t)kBandFloor) margin = kBandFloor;
     if (margin > (int64_t)1 << 25) margin = (int64_t)1 << 25;   // two list digits cover a band of 2^26 keys
     int64_t centre = tau + delta;
     if (centre < 0) centre = 0;
@@ -451,86 +473,172 @@ __device__ __forceinline__ void predict_band(RowDesc& r, uint32_t fix_lo, uint32
     const int64_t lo = centre - margin, hi = centre + margin;
     r.lo = lo < 0 ? 0u : (uint32_t)lo;
     r.hi = hi > 0x80000000ll ? 0x80000000u : (uint32_t)hi;
+    r.centre = (uint32_t)centre;
+    r.swing = (uint32_t)swing;
     r.prev_tau = r.tau;
     r.have_prev = 1;
     r.was_cold = 0;
 }
 
-// grid = rows, 1024 threads.  Orders the collected ties by index, sets the cut-off, clears the list state
-// and predicts the next step's band.  When more entries share the threshold than the tie buffer holds
-// (quantised gradients: thousands of equal magnitudes), the cut-off -- the `rank`-th smallest index
-// among the listed entries whose key is tau -- comes from a three-digit radix select over those
-// indices, read from the candidate list itself.  Rows whose band failed twice go to the slow search.
-constexpr int kFinishBlock = 1024;
-__global__ __launch_bounds__(kFinishBlock) void k_list_finish(uint32_t row0, RowDesc* __restrict__ desc,
-                                                               uint32_t* __restrict__ lhist,
-                                                               const uint32_t* __restrict__ tiebuf,
-                                                               const uint2* __restrict__ list, uint32_t cap, uint32_t k,
+// One pass of the block over the n listed entries, two entries per 128-bit load and eight loads in flight
+// per thread (a row's list starts 16-byte aligned): fn(entry, valid) is called in wave-uniform control
+// flow (valid false beyond n), so it may use wave_count.
+constexpr int kSelectBlock = 1024;
+template <typename F>
+__device__ __forceinline__ void for_each_listed(const uint2* __restrict__ in, uint32_t n, F fn) {
+    const uint32_t tid = threadIdx.x;
+    const uint4* __restrict__ in2 = reinterpret_cast<const uint4*>(in);
+    const uint32_t npairs = (n + 1) / 2;                    // the slot after an odd n is inside the row's capacity
+    for (uint32_t base = 0; base < npairs; base += 8 * kSelectBlock) {     // uniform trip count
+        uint4 a[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t e = base + q * kSelectBlock + tid;
+            a[q] = e < npairs ? in2[e] : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t e = 2 * (base + q * kSelectBlock + tid);
+            fn(make_uint2(a[q].x, a[q].y), e < n);
+            fn(make_uint2(a[q].z, a[q].w), e + 1 < n);
+        }
+    }
+}
+
+// grid = rows, 1024 threads: finishes the list select of a row.  Which band the row's list was filtered
+// against -- the predicted one, or the first-digit bin picked (again, here) from the row's histogram --
+// follows from the row's mode and first counter set, as in the filter passes.  Two radix digits over the
+// listed keys give tau.  For a row on its predicted band the first digit's histogram is ready (k_hist0) and,
+// when the bin holding rank k was small enough, so is the short list of that bin's entries (second k_filter
+// pass): the rest of the select then reads those few entries only.  Otherwise the block walks the list
+// itself.  The cut-off is the `rank`-th smallest index among the entries whose key is tau: through an LDS
+// buffer when at most kTieCap entries share tau, else (quantised gradients: thousands of equal magnitudes)
+// by a three-digit radix select over those indices.  Then the row's counters and histogram are cleared, the
+// next step's band is predicted and the row is back in kWarm mode.  Rows whose list does not hold rank k
+// (overflow, a bin larger than the list, rank outside the band) are put into kSlow mode.
+__global__ __launch_bounds__(kSelectBlock) void k_list_select(uint32_t row0, RowDesc* __restrict__ desc,
+                                                               uint32_t* __restrict__ ghist,
+                                                               const uint2* __restrict__ list, uint32_t cap,
+                                                               const uint2* __restrict__ shortl, uint32_t k,
                                                                uint32_t fix_lo, uint32_t fix_hi,
                                                                uint32_t* __restrict__ slow_sync) {
-    __shared__ uint32_t t_idx[kTieCap];                        // tie indices, or the digit histogram
+    __shared__ uint32_t h[kListBins];                          // digit histograms, then the tie indices
     __shared__ uint32_t part[256], res[3];
-    __shared__ uint32_t s_cut;
-    const uint32_t row = row0 + blockIdx.x, tid = threadIdx.x;
+    __shared__ uint32_t s_cut, s_nties;
+    static_assert(kTieCap <= kListBins, "the tie indices reuse the histogram");
+    const uint32_t row = row0 + blockIdx.x, tid = threadIdx.x, lane = tid & 63;
     // the meeting counter and give-up flag of the general search that may follow start every step at zero
     if (slow_sync && tid < 2) slow_sync[(size_t)blockIdx.x * 2 + tid] = 0;
     if (desc[row].mode == kSlow) return;
-    if (!listable(desc[row], cap, k)) {                        // uniform for the block
+    const bool cold = wants_cold(desc[row], cap, k);           // uniform for the block
+    const uint32_t missed = (cold && desc[row].mode == kWarm) ? 1u : 0u;    // there was a prediction and it failed
+    uint32_t* __restrict__ hrow = ghist + (size_t)row * kHistBins;
+    const uint2* __restrict__ in = list + (size_t)row * cap;
+    uint32_t lo, hi, n, n_sure;
+    bool ok = true;
+    Pick ph;                                                    // first digit: bin holding rank k, rank inside it
+    int shift;                                                  // key bits below the digits found so far
+    bool direct = cold;                                         // this block builds the first digit's histogram itself
+    if (cold) {
+        const Pick p = block_pick(hrow, kHistBins, k, part, res);
+        lo = p.bin << 19;
+        hi = (p.bin + 1) << 19;
+        n = desc[row].n_cand2;
+        n_sure = sure_count2(desc[row]);
+        ok = p.count <= cap && n <= cap && n_sure < k && (uint64_t)k <= (uint64_t)n_sure + n;
+        shift = first_shift(hi - lo, kListBits);
+    } else {                                                    // kWarm and band_ok
+        lo = desc[row].lo;
+        hi = desc[row].hi;
+        n = desc[row].n_cand;
+        n_sure = sure_count(desc[row]);
+        direct = n <= (uint32_t)kDirectList;
+        shift = first_shift(hi - lo, direct ? kListBits : kFirstBits);
+        if (!direct) ph = block_pick(hrow, 1 << kFirstBits, k - n_sure, part, res);
+    }
+    if (cold || !direct)
+        for (int b = tid; b < kHistBins; b += kSelectBlock) hrow[b] = 0;    // the row's histogram is ready for the next step
+    if (!ok) {
         if (tid == 0) {
             RowDesc r = desc[row];
-            r.n_cand = 0;
-            clear_sure(r);
-            r.n_ties = 0;
+            clear_counts(r);
             r.n_list = 0;
+            r.misses += missed;
             r.mode = kSlow;
             desc[row] = r;
         }
         return;
     }
-    uint32_t* __restrict__ hrow = lhist + (size_t)row * 2 * kListBins;
-    for (int b = tid; b < 2 * kListBins; b += kFinishBlock) hrow[b] = 0;
-    const uint32_t ties = desc[row].ties, want = desc[row].rank;
-    if (ties <= (uint32_t)kTieCap) {
-        const uint32_t* __restrict__ tb = tiebuf + (size_t)row * kTieCap;
-        for (uint32_t q = tid; q < ties; q += kFinishBlock) t_idx[q] = tb[q];
-        if (tid == 0) s_cut = 0xffffffffu;
+    const uint32_t n_all = n;
+    if (direct) {
+        // first digit of every listed key, in LDS
+        const uint32_t nbins = max(256u, 1u << (band_bits(hi - lo) - shift));
+        for (uint32_t b = tid; b < nbins; b += kSelectBlock) h[b] = 0;
         __syncthreads();
-        for (uint32_t q = tid; q < ties; q += kFinishBlock) {
-            const uint32_t mine = t_idx[q];
+        for_each_listed(in, n, [&](uint2 kv, bool valid) { wave_count(h, valid, (kv.x - lo) >> shift, lane); });
+        __syncthreads();
+        ph = block_pick(h, (int)nbins, k - n_sure, part, res);
+    } else if (ph.count <= (uint32_t)kShortCap && desc[row].n_short == ph.count) {
+        in = shortl + (size_t)row * kShortCap;                  // the bin's entries, collected by the second filter pass
+        n = ph.count;
+    }
+    // the following digits, over the entries that carry the digits found so far
+    uint32_t prefix = ph.bin, want = ph.rank_in, ties = ph.count;
+#pragma unroll 1
+    while (shift > 0) {
+        const int bits = shift < kListBits ? shift : kListBits, below = shift - bits;
+        const uint32_t nbins = max(256u, 1u << bits), mask = (1u << bits) - 1u;
+        for (uint32_t b = tid; b < nbins; b += kSelectBlock) h[b] = 0;
+        __syncthreads();
+        for_each_listed(in, n, [&](uint2 kv, bool valid) {
+            const uint32_t rel = kv.x - lo;
+            wave_count(h, valid && (rel >> shift) == prefix, (rel >> below) & mask, lane);
+        });
+        __syncthreads();
+        const Pick p = block_pick(h, (int)nbins, want, part, res);
+        prefix = (prefix << bits) | p.bin;
+        want = p.rank_in;
+        ties = p.count;
+        shift = below;
+    }
+    const uint32_t tau = lo + prefix;
+    if (ties <= (uint32_t)kTieCap) {
+        if (tid == 0) {
+            s_nties = 0;
+            s_cut = 0xffffffffu;
+        }
+        __syncthreads();
+        for_each_listed(in, n, [&](uint2 kv, bool valid) {
+            if (valid && kv.x == tau) {
+                const uint32_t pos = atomicAdd(&s_nties, 1u);
+                if (pos < (uint32_t)kTieCap) h[pos] = kv.y;
+            }
+        });
+        __syncthreads();
+        for (uint32_t q = tid; q < ties; q += kSelectBlock) {
+            const uint32_t mine = h[q];
             uint32_t below = 0;
-            for (uint32_t r = 0; r < ties; ++r) below += t_idx[r] < mine;
-            if (below + 1 == want) s_cut = mine;            // indices are distinct: one writer
+            for (uint32_t r = 0; r < ties; ++r) below += h[r] < mine;
+            if (below + 1 == want) s_cut = mine;                // indices are distinct: one writer
         }
         __syncthreads();
     } else {
         // Indices are below 2^31; taking 0x7fffffff - index as the key turns "want-th smallest index" into
         // "want-th largest key", which is what block_pick finds.  Digits of 11, 10 and 10 bits.
-        const uint2* __restrict__ in = list + (size_t)row * cap;
-        const uint32_t n = desc[row].n_cand, tau = desc[row].tau;
         uint32_t prefix = 0, rank = want;
 #pragma unroll 1
         for (int pass = 0; pass < 3; ++pass) {
             const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
             const int above = pass == 0 ? 31 : (pass == 1 ? 20 : 10);   // bits above this digit are the prefix
             const int nbins = pass == 0 ? 2048 : 1024;
-            for (int b = tid; b < nbins; b += kFinishBlock) t_idx[b] = 0;
+            for (int b = tid; b < nbins; b += kSelectBlock) h[b] = 0;
             __syncthreads();
-            auto count = [&](uint2 kv) {
+            for_each_listed(in, n, [&](uint2 kv, bool valid) {
                 const uint32_t inv = 0x7fffffffu - kv.y;
-                if (kv.x == tau && (inv >> above) == prefix) atomicAdd(&t_idx[(inv >> shift) & (uint32_t)(nbins - 1)], 1u);
-            };
-            uint32_t e = tid;
-            for (; e + 3 * kFinishBlock < n; e += 4 * kFinishBlock) {   // four independent loads in flight
-                const uint2 a0 = in[e], a1 = in[e + kFinishBlock], a2 = in[e + 2 * kFinishBlock],
-                            a3 = in[e + 3 * kFinishBlock];
-                count(a0);
-                count(a1);
-                count(a2);
-                count(a3);
-            }
-            for (; e < n; e += kFinishBlock) count(in[e]);
+                wave_count(h, valid && kv.x == tau && (inv >> above) == prefix, (inv >> shift) & (uint32_t)(nbins - 1), lane);
+            });
             __syncthreads();
-            const Pick p = block_pick(t_idx, nbins, rank, part, res);
+            const Pick p = block_pick(h, nbins, rank, part, res);
             prefix = (prefix << (pass == 0 ? 11 : 10)) | p.bin;
             rank = p.rank_in;
         }
@@ -539,14 +647,17 @@ __global__ __launch_bounds__(kFinishBlock) void k_list_finish(uint32_t row0, Row
     }
     if (tid == 0) {
         RowDesc r = desc[row];
-        r.n_list = r.n_cand;
-        r.n_cand = 0;
-        clear_sure(r);
-        r.n_ties = 0;
+        r.n_list = n_all;
+        clear_counts(r);
+        r.tau = tau;
+        r.rank = want;
+        r.ties = ties;
         r.cutoff = s_cut;
         r.dense = 0;
         r.nonfinite = r.nonfinite_acc;
         r.nonfinite_acc = 0;
+        r.was_cold = cold ? 1u : 0u;
+        r.misses += missed;
         predict_band(r, fix_lo, fix_hi);
         r.mode = kWarm;
         desc[row] = r;
@@ -604,9 +715,7 @@ __device__ __forceinline__ void slow_write_result(RowDesc* __restrict__ desc, ui
     r.dense = 1;
     r.nonfinite = bad | r.nonfinite_acc;
     r.nonfinite_acc = 0;
-    r.n_cand = 0;
-    clear_sure(r);
-    r.n_ties = 0;
+    clear_counts(r);
     r.n_list = 0;
     r.have_prev = 0;
     r.was_cold = 0;

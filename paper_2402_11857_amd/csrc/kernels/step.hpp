@@ -47,6 +47,8 @@ __device__ __forceinline__ float message_of(float g, uint32_t j, float scale, ui
 //   WC == kRandk    reads each row's kept bitmap and fetches only the groups of 4 gradients that hold a
 //                   kept column;
 //   WC == kIdentity reads the gradients.
+// With `vbits` the kernel also leaves the sign bits of v (lane-major half-words like the workers' sign
+// bits) for the update kernel of a scaled-sign server.
 // ---------------------------------------------------------------------------------------------
 template <int WC, bool SRV_L1, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ grads, const uint16_t* __restrict__ bits,
@@ -54,7 +56,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
                                                        int N, uint32_t d, uint32_t nwt, float inv_n,
                                                        const RowDesc* __restrict__ desc, const float* __restrict__ e_in,
                                                        float* __restrict__ v_out, double* __restrict__ srv_partial,
-                                                       BlockTable bt, bool coarse) {
+                                                       BlockTable bt, bool coarse, uint16_t* __restrict__ vbits) {
     __shared__ double lds_w[4];
     __shared__ float accs[(WC == kTopk || WC == kRandk) ? 16 * kBlock : 1];
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -134,7 +136,11 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
                     const int u = __builtin_ctz(mask);
                     mask &= mask - 1;
                     const uint32_t j = j0 + u * kChunk;
+#ifdef LIEC_AGG_NT_GATHER
+                    const float4 g = ld4<VEC, true>(gi, j, d);
+#else
                     const float4 g = ld4<VEC>(gi, j, d);
+#endif
                     const float gv[4] = {g.x, g.y, g.z, g.w};
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
@@ -192,6 +198,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
                 }
             }
         }
+        uint32_t vm = 0;                                        // sign bits of my 16 values of v
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const uint32_t j = j0 + u * kChunk;
@@ -201,6 +208,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
             v.y = __fmaf_rn(acc[u].y, inv_n, e.y);
             v.z = __fmaf_rn(acc[u].z, inv_n, e.z);
             v.w = __fmaf_rn(acc[u].w, inv_n, e.w);
+            vm |= ((v.x < 0.f ? 1u : 0u) | (v.y < 0.f ? 2u : 0u) | (v.z < 0.f ? 4u : 0u) | (v.w < 0.f ? 8u : 0u)) << (4 * u);
             // with the gathering operators a streaming store of v measured 10 % faster, with the others slower
             if (WC == kTopk || WC == kRandk) st4<VEC, true>(v_out, j, d, v);
             else st4<VEC>(v_out, j, d, v);
@@ -211,6 +219,8 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
                 if (j + 3 < d) l1 += (double)fabsf(v.w);
             }
         }
+        // a scaled-sign server's message is these bits and one scale: the update kernel reads them instead of v
+        if (vbits) vbits[(size_t)t * 64 + lane] = (uint16_t)vm;
     }
     if (SRV_L1) {
         const double s = block_sum_f64(l1, lds_w);
@@ -231,7 +241,8 @@ __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ gra
                                                     const float* __restrict__ v_in, float* __restrict__ e_out, int N,
                                                     uint32_t panel, uint32_t ncol_tiles, uint32_t d, float neg_lr,
                                                     const RowDesc* __restrict__ desc, BlockTable bt,
-                                                    const uint16_t* __restrict__ kbits) {
+                                                    const uint16_t* __restrict__ kbits, const uint16_t* __restrict__ vbits,
+                                                    const uint64_t* __restrict__ sgbits) {
     const uint32_t per_panel = panel * (uint32_t)N;
     const uint32_t pn = blockIdx.x / per_panel, r = blockIdx.x % per_panel;
     const uint32_t i = r / panel, tile = pn * panel + r % panel;
@@ -240,15 +251,30 @@ __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ gra
     if (j >= d) return;
     const float* __restrict__ gi = grads + (size_t)i * d;
     float* __restrict__ xi = x + (size_t)i * d;
+    const uint32_t lane = threadIdx.x & 63, chunk = threadIdx.x >> 6;   // this thread is lane `lane` of chunk `chunk` of wave tile `tile`
     uint32_t tb = 0;
     if (WC == kBlockSign || SC == kBlockSign) tb = bt.tile_blk[tile];   // issued ahead of the streams
-    // random-k: the 4 kept bits of this thread's columns (the thread is lane `threadIdx.x & 63` of chunk
-    // `threadIdx.x >> 6` of wave tile `tile`); row N of the bitmap is the server's draw
+    // random-k: the 4 kept bits of this thread's columns; row N of the bitmap is the server's draw
     uint32_t wkeep = 0, skeep = 0;
-    if (WC == kRandk)
-        wkeep = (kbits[((size_t)i * ncol_tiles + tile) * 64 + (threadIdx.x & 63)] >> (4 * (threadIdx.x >> 6))) & 0xfu;
-    if (SC == kRandk)
-        skeep = (kbits[((size_t)N * ncol_tiles + tile) * 64 + (threadIdx.x & 63)] >> (4 * (threadIdx.x >> 6))) & 0xfu;
+    if (WC == kRandk) wkeep = (kbits[((size_t)i * ncol_tiles + tile) * 64 + lane] >> (4 * chunk)) & 0xfu;
+    if (SC == kRandk) skeep = (kbits[((size_t)N * ncol_tiles + tile) * 64 + lane] >> (4 * chunk)) & 0xfu;
+    const RowDesc* __restrict__ sd = desc + N;
+    // What the server's message needs of v.  The row-0 block of a tile reads v in full (it writes e).  The other
+    // rows' blocks take what the server side left behind instead of re-reading 4 d bytes of v per row: the sign
+    // bits of v (scaled sign, either form), the candidate bit of these 4 columns (top-k: v is read only where
+    // a candidate sits, unless the row's bitmap is not valid), the kept bits (random-k).
+    uint32_t sbits = 0;
+    bool need_v = true;
+    if (i != 0) {
+        if (SC == kSign || SC == kBlockSign) {
+            sbits = ((uint32_t)vbits[(size_t)tile * 64 + lane] >> (4 * chunk)) & 0xfu;
+            need_v = false;
+        } else if (SC == kTopk) {
+            need_v = sd->dense || ((sgbits[(size_t)tile * 4 + chunk] >> lane) & 1u);
+        } else if (SC == kRandk) {
+            need_v = skeep != 0;
+        }
+    }
     const float4 g = ld4<VEC, true>(gi, j, d);
 #if defined(__HIP_DEVICE_COMPILE__)
     // One stream at a time per wave: waiting for the gradients before asking for the model measured
@@ -256,8 +282,8 @@ __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ gra
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #endif
     const float4 xv = ld4<VEC, true>(xi, j, d);
-    const float4 v = ld4<VEC>(v_in, j, d);
-    const RowDesc* __restrict__ sd = desc + N;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (need_v) v = ld4<VEC>(v_in, j, d);
     const uint32_t stau = sd->tau, scut = sd->cutoff;
     float sw[4], ss[4];                                    // worker / server scale of each of the 4 columns
     if (WC == kBlockSign || SC == kBlockSign) {
@@ -276,10 +302,17 @@ __global__ __launch_bounds__(kBlock) void k_update(const float* __restrict__ gra
         }
     }
     float4 p;
-    p.x = message_of<SC>(v.x, j, ss[0], stau, scut, skeep & 1u);
-    p.y = message_of<SC>(v.y, j + 1, ss[1], stau, scut, skeep & 2u);
-    p.z = message_of<SC>(v.z, j + 2, ss[2], stau, scut, skeep & 4u);
-    p.w = message_of<SC>(v.w, j + 3, ss[3], stau, scut, skeep & 8u);
+    if ((SC == kSign || SC == kBlockSign) && i != 0) {
+        p.x = (sbits & 1u) ? -ss[0] : ss[0];
+        p.y = (sbits & 2u) ? -ss[1] : ss[1];
+        p.z = (sbits & 4u) ? -ss[2] : ss[2];
+        p.w = (sbits & 8u) ? -ss[3] : ss[3];
+    } else {                                               // for columns whose v was not read p is +0, as v is
+        p.x = message_of<SC>(v.x, j, ss[0], stau, scut, skeep & 1u);
+        p.y = message_of<SC>(v.y, j + 1, ss[1], stau, scut, skeep & 2u);
+        p.z = message_of<SC>(v.z, j + 2, ss[2], stau, scut, skeep & 4u);
+        p.w = message_of<SC>(v.w, j + 3, ss[3], stau, scut, skeep & 8u);
+    }
     if (i == 0) {
         float4 en;
         en.x = __fsub_rn(v.x, p.x);

@@ -20,23 +20,21 @@ using namespace liec;
 namespace {
 
 // Kernel slots for per-kernel timing: worker side, aggregation, server side, update.
+constexpr int kSelSlots = 6;
 enum Slot : int {
     S_W_L1 = 0, S_W_L1_FINAL,
     S_W_SEL,                       // kSelSlots slots of the worker-side top-k / random-k search
-    S_AGGREGATE = S_W_SEL + 10,
+    S_AGGREGATE = S_W_SEL + kSelSlots,
     S_S_L1, S_S_L1_FINAL,
     S_S_SEL,                       // kSelSlots slots of the server-side top-k / random-k search
-    S_UPDATE = S_S_SEL + 10,
+    S_UPDATE = S_S_SEL + kSelSlots,
     S_SYNC,
     S_COUNT
 };
 
-constexpr int kSelSlots = 10;
-const char* const kWorkerSel[kSelSlots] = {"worker_filter_warm", "worker_hist0", "worker_pick_band", "worker_filter_cold",
-                                           "worker_list_hist0", "worker_list_hist1", "worker_list_ties", "worker_list_finish",
+const char* const kWorkerSel[kSelSlots] = {"worker_filter_warm", "worker_hist0", "worker_filter_cold", "worker_list_select",
                                            "worker_slow_select", "worker_randk_mark"};
-const char* const kServerSel[kSelSlots] = {"server_filter_warm", "server_hist0", "server_pick_band", "server_filter_cold",
-                                           "server_list_hist0", "server_list_hist1", "server_list_ties", "server_list_finish",
+const char* const kServerSel[kSelSlots] = {"server_filter_warm", "server_hist0", "server_filter_cold", "server_list_select",
                                            "server_slow_select", "server_randk_mark"};
 
 const char* slot_name(int s) {
@@ -105,9 +103,9 @@ struct liec_ctx {
     uint32_t ncol_tiles = 0;                   // column tiles of the update kernel
     uint32_t row_blocks = 0;                   // scaled-sign pass over grads: grid (row_blocks, N)
     uint32_t filter_row_blocks = 0, filter_srv_blocks = 0;   // top-k filter pass (fewer, longer-lived blocks)
+    uint32_t filter_run = 1;                   // consecutive wave tiles a wave of the filter takes at a time
     uint32_t agg_blocks = 0;                   // aggregation kernel
     uint32_t cold_row_blocks = 0, cold_srv_blocks = 0;   // first-digit histogram (rarely needed)
-    uint32_t list_blocks = 0;                  // kernels over the candidate lists
     uint32_t cap = 0;                          // candidate list capacity per row
 
     // device scratch
@@ -121,10 +119,11 @@ struct liec_ctx {
     bool rk_winv = false, rk_sinv = false;     // random-k: the band is thin enough to walk the priorities instead of the columns
     uint64_t* gbits = nullptr;                 // [N * nwt * 4] group bitmap of the candidates (top-k workers), either form
     bool gb_coarse = false;                    // one bit per 64-byte line instead of one per 4 columns
+    uint16_t* vbits = nullptr;                 // [nwt * 64] sign bits of v (scaled-sign server, either form)
+    uint64_t* sgbits = nullptr;                // [nwt * 4] group bitmap of the server's candidates in v (top-k server), fine form
     uint2* list = nullptr;                     // [(N + 1) * cap] candidates (key, index)
-    uint32_t* ghist = nullptr;                 // [(N + 1) * kHistBins]
-    uint32_t* lhist = nullptr;                 // [(N + 1) * 2 * kListBins]
-    uint32_t* tiebuf = nullptr;                // [(N + 1) * kTieCap]
+    uint32_t* ghist = nullptr;                 // [(N + 1) * kHistBins] first digit of a row (12 bits) or of its list (8 bits)
+    uint2* shortl = nullptr;                   // [(N + 1) * kShortCap] listed entries of the first list digit's bin
     // general (degenerate-row) search: B thread blocks share a row when B * rows fit the chip
     uint32_t slow_bw = 1, slow_bs = 1;         // blocks per worker row / for the server's vector
     uint32_t slow_spin = 1u << 16;             // bound, in polls, of the waits between those blocks
@@ -216,10 +215,11 @@ void free_scratch(liec_ctx* c) {
     (void)hipFree(c->bits);
     (void)hipFree(c->rk_state);
     (void)hipFree(c->gbits);
+    (void)hipFree(c->vbits);
+    (void)hipFree(c->sgbits);
     (void)hipFree(c->list);
     (void)hipFree(c->ghist);
-    (void)hipFree(c->lhist);
-    (void)hipFree(c->tiebuf);
+    (void)hipFree(c->shortl);
     (void)hipFree(c->slow_hist);
     (void)hipFree(c->slow_cnt);
     (void)hipFree(c->slow_sync);
@@ -269,56 +269,42 @@ struct Launcher {
 };
 
 // Top-k threshold search (Definition 2) of `rows` rows of `src`; per-row state lives at row0 + r.
-// The host enqueues the same nine kernels every step; each one acts only on the rows whose state
-// asks for it, so the warm path costs one pass over the data and the others return at once.
+// The host enqueues the same five kernels every step; each one acts only on the rows whose state
+// asks for it, so the steady state costs one pass over the data and one block per row of list select,
+// and the others return at once.
 // RK: the same search over the priorities of a random-k draw (Definition 3), which read nothing from
 // `src`, followed by the kernel that completes the kept bitmap.
 template <bool VEC, bool RK>
 void launch_select(Launcher& L, const float* src, size_t row_stride, uint32_t rows, uint32_t row0, uint32_t k,
-                   uint64_t* gbits, uint32_t blocks, uint32_t cold_blocks, int slot0, RkDraw rk, bool rk_inverse = false) {
+                   uint64_t* gbits, bool coarse, uint32_t blocks, uint32_t cold_blocks, int slot0, RkDraw rk,
+                   bool rk_inverse = false) {
     liec_ctx* c = L.c;
     const uint32_t d = (uint32_t)c->d;
     hipStream_t st = c->stream;
-    const dim3 grid(blocks, rows), cold_grid(cold_blocks, rows), list_grid(c->list_blocks, rows);
+    const dim3 grid(blocks, rows), cold_grid(cold_blocks, rows);
     // random-k with a thin band: clear the kept bitmap, then walk the priorities above the band
     // few, long-lived blocks (every wave ends with a list flush): one per 32768 words to invert
     const uint64_t inv_words = 2ull * (0x80000000ull - rk.fix_lo);
     const dim3 inv_grid((uint32_t)std::min<uint64_t>(std::max<uint64_t>(inv_words / 32768, 128), 1024), rows);
     const dim3 zero_grid(std::min<uint32_t>((c->nwt * 32 + kBlock - 1) / kBlock, 4096u), rows);
-    L.begin(slot0 + 0);
-    if (RK && rk_inverse) {
-        k_rk_zero<<<zero_grid, kBlock, 0, st>>>(c->nwt, row0, c->desc, kWarm, c->bits);
-        k_rk_filter_inverse<<<inv_grid, kBlock, 0, st>>>(d, c->nwt, row0, c->desc, kWarm, c->bits, c->list, c->cap, rk);
-    } else {
-        k_filter<VEC, RK><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kWarm, gbits, c->bits, c->list,
-                                                    c->cap, rk, c->gb_coarse);
+    for (int pass = 0; pass < 2; ++pass) {
+        const bool cold_pass = pass == 1;
+        if (cold_pass) {
+            L.begin(slot0 + 1);
+            k_hist0<VEC, RK><<<cold_grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, c->ghist, c->list, c->cap, k, rk);
+            L.end();
+        }
+        L.begin(slot0 + (cold_pass ? 2 : 0));
+        if (RK && rk_inverse) {
+            k_rk_zero<<<zero_grid, kBlock, 0, st>>>(c->nwt, row0, c->desc, cold_pass, c->cap, k, c->bits);
+            k_rk_filter_inverse<<<inv_grid, kBlock, 0, st>>>(d, c->nwt, row0, c->desc, cold_pass, c->ghist, k, c->bits,
+                                                             c->list, c->cap, c->shortl, rk);
+        } else {
+            k_filter<VEC, RK><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, cold_pass, c->ghist, k,
+                                                        gbits, c->bits, c->list, c->cap, c->shortl, rk, coarse, c->filter_run);
+        }
+        L.end();
     }
-    L.end();
-    L.begin(slot0 + 1);
-    k_hist0<VEC, RK><<<cold_grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, c->ghist, c->cap, k, rk);
-    L.end();
-    L.begin(slot0 + 2);
-    k_pick_band<<<rows, kBlock, 0, st>>>(row0, c->desc, c->ghist, c->cap, k);
-    L.end();
-    L.begin(slot0 + 3);
-    if (RK && rk_inverse) {
-        k_rk_zero<<<zero_grid, kBlock, 0, st>>>(c->nwt, row0, c->desc, kColdBand, c->bits);
-        k_rk_filter_inverse<<<inv_grid, kBlock, 0, st>>>(d, c->nwt, row0, c->desc, kColdBand, c->bits, c->list, c->cap, rk);
-    } else {
-        k_filter<VEC, RK><<<grid, kBlock, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, kColdBand, gbits, c->bits,
-                                                    c->list, c->cap, rk, c->gb_coarse);
-    }
-    L.end();
-    L.begin(slot0 + 4);
-    k_list_hist<0><<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, k, c->lhist);
-    L.end();
-    L.begin(slot0 + 5);
-    k_list_hist<1><<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, k, c->lhist);
-    L.end();
-    L.begin(slot0 + 6);
-    k_list_ties<<<list_grid, kBlock, 0, st>>>(row0, c->desc, c->list, c->cap, k, c->lhist, c->tiebuf);
-    L.end();
-    L.begin(slot0 + 7);
     // scratch of the general search: the worker rows' slots come first, then the server's
     const bool server_side = row0 != 0;
     const uint32_t slow_b = server_side ? c->slow_bs : c->slow_bw;
@@ -326,15 +312,16 @@ void launch_select(Launcher& L, const float* src, size_t row_stride, uint32_t ro
     uint32_t* const shist = slow_b > 1 ? c->slow_hist + slow_slot * kSlowHistWords : nullptr;
     uint32_t* const scnt = slow_b > 1 ? c->slow_cnt + slow_slot * kSlowMaxBlocks : nullptr;
     uint32_t* const ssync = slow_b > 1 ? c->slow_sync + slow_slot * 2 : nullptr;
-    k_list_finish<<<rows, kFinishBlock, 0, st>>>(row0, c->desc, c->lhist, c->tiebuf, c->list, c->cap, k, rk.fix_lo, rk.fix_hi,
+    L.begin(slot0 + 3);
+    k_list_select<<<rows, kSelectBlock, 0, st>>>(row0, c->desc, c->ghist, c->list, c->cap, c->shortl, k, rk.fix_lo, rk.fix_hi,
                                                  ssync);
     L.end();
-    L.begin(slot0 + 8);
+    L.begin(slot0 + 4);
     k_slow_select<VEC, RK><<<dim3(slow_b, rows), 1024, 0, st>>>(src, row_stride, d, c->nwt, row0, c->desc, k, rk, shist, scnt,
                                                                  ssync, c->slow_spin);
     L.end();
     if (RK) {
-        L.begin(slot0 + 9);
+        L.begin(slot0 + 5);
         k_rk_mark<<<dim3(cold_blocks, rows), kBlock, 0, st>>>(d, c->nwt, row0, c->desc, c->list, c->cap, c->bits, rk);
         L.end();
     }
@@ -365,11 +352,11 @@ void launch_aggregate(Launcher& L, const float* grads, const float* e, bool srv_
     if (srv_l1)
         k_aggregate<WC, true, VEC><<<c->agg_blocks, kBlock, 0, c->stream>>>(grads, c->bits, c->gbits, c->N, d, c->nwt, inv_n,
                                                                              c->desc, e, c->vbuf, c->s_partial,
-                                                                             block_table(c), c->gb_coarse);
+                                                                             block_table(c), c->gb_coarse, c->vbits);
     else
         k_aggregate<WC, false, VEC><<<c->agg_blocks, kBlock, 0, c->stream>>>(grads, c->bits, c->gbits, c->N, d, c->nwt, inv_n,
                                                                               c->desc, e, c->vbuf, c->s_partial,
-                                                                              block_table(c), c->gb_coarse);
+                                                                              block_table(c), c->gb_coarse, c->vbits);
     L.end();
 }
 
@@ -382,7 +369,7 @@ void launch_update(Launcher& L, const float* grads, float* x, float* e) {
     L.begin(S_UPDATE);
     k_update<WC, SC, VEC><<<(uint32_t)blocks, kBlock, 0, c->stream>>>(grads, x, c->vbuf, e, c->N, panel, c->ncol_tiles,
                                                                        (uint32_t)c->d, -c->lr, c->desc, block_table(c),
-                                                                       c->bits);
+                                                                       c->bits, c->vbits, c->sgbits);
     L.end();
 }
 
@@ -415,10 +402,10 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
     } else if (c->worker_comp == kBlockSign) {
         launch_block_l1<VEC>(L, grads, stride, (uint32_t)c->N, 0u, c->bits, S_W_L1);
     } else if (c->worker_comp == kTopk) {
-        launch_select<VEC, false>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, c->gbits,
+        launch_select<VEC, false>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, c->gbits, c->gb_coarse,
                                   c->filter_row_blocks, c->cold_row_blocks, S_W_SEL, RkDraw{nullptr, 0, 0});
     } else if (c->worker_comp == kRandk) {
-        launch_select<VEC, true>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, nullptr,
+        launch_select<VEC, true>(L, grads, stride, (uint32_t)c->N, 0u, (uint32_t)c->worker_k, nullptr, false,
                                  c->filter_row_blocks, c->cold_row_blocks, S_W_SEL,
                                  RkDraw{c->rk_state, c->rk_wlo, c->rk_whi}, c->rk_winv);
     }
@@ -440,10 +427,11 @@ void run_step(Launcher& L, const float* grads, float* x, float* e) {
         launch_block_l1<VEC>(L, c->vbuf, 0, 1u, (uint32_t)c->N, nullptr, S_S_L1);
     } else if (c->server_comp == kTopk) {
         // v is always 16-byte aligned scratch, but d % 4 decides whether 128-bit loads stay in bounds
-        launch_select<VEC, false>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, nullptr,
+        // the server's candidates get the fine group bitmap: the update kernel reads v only where a bit is set
+        launch_select<VEC, false>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, c->sgbits, false,
                                   c->filter_srv_blocks, c->cold_srv_blocks, S_S_SEL, RkDraw{nullptr, 0, 0});
     } else if (c->server_comp == kRandk) {
-        launch_select<VEC, true>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, nullptr,
+        launch_select<VEC, true>(L, c->vbuf, 0, 1u, (uint32_t)c->N, (uint32_t)c->server_k, nullptr, false,
                                  c->filter_srv_blocks, c->cold_srv_blocks, S_S_SEL,
                                  RkDraw{c->rk_state, c->rk_slo, c->rk_shi}, c->rk_sinv);
     }
@@ -541,8 +529,17 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     c->row_blocks = balanced(1u << 20);
     // the filter pays one list flush (a global atomic) per wave: about 1024 long-lived blocks per row
     // (more when there are too few rows to fill the chip)
-    c->filter_row_blocks = balanced(clampu(4096u / un, 1024u, 4096u));
-    c->filter_srv_blocks = balanced(8192u);
+    // A wave of the filter takes 4 consecutive wave tiles at a time on long rows (a block then covers 16, and the
+    // group words it writes fill whole 128-byte lines of the bitmap: measured 2 % faster than 1 on rows of 25M
+    // and 138M columns, 2 and 8 in between); short rows keep 1, so that enough blocks are in flight.
+    c->filter_run = c->nwt >= 8192u ? 4u : 1u;
+    auto balanced_filter = [&](uint32_t max_blocks) {
+        const uint32_t iters = (c->nwt + 4 * c->filter_run - 1) / (4 * c->filter_run);
+        const uint32_t per = (iters + max_blocks - 1) / max_blocks;
+        return (iters + per - 1) / per;
+    };
+    c->filter_row_blocks = balanced_filter(clampu(4096u / un, 1024u, 4096u));
+    c->filter_srv_blocks = balanced_filter(8192u);
     // the aggregation reads sign bits fastest with many short blocks, and gathers fastest with fewer
     const bool gathers = worker_comp == LIEC_COMP_TOPK || worker_comp == LIEC_COMP_RANDK;
     c->agg_blocks = balanced(gathers ? 16384u : 65536u);
@@ -554,7 +551,7 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     const int64_t kmax = std::max(c->worker_k, c->server_k);
     const int64_t want = std::min<int64_t>(d / 16, 8 * kmax) + 4096;
     c->cap = (uint32_t)std::min<int64_t>(want, d);
-    c->list_blocks = clampu((c->cap + 2047u) / 2048u, 1u, 64u);
+    c->cap += c->cap & 1u;                     // even: every row's list starts 16-byte aligned (read two entries at a time)
 
     const size_t rows = (size_t)N + 1;
     hipError_t e = dev_alloc(c, &c->desc, rows);
@@ -575,10 +572,12 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     c->gb_coarse = worker_comp == LIEC_COMP_TOPK && d >= 40000000;
     if (e == hipSuccess && worker_comp == LIEC_COMP_TOPK)
         e = dev_alloc(c, &c->gbits, (size_t)N * c->nwt * 4);      // room for either form
+    if (e == hipSuccess && (server_comp == LIEC_COMP_SIGN || server_comp == LIEC_COMP_BLOCKSIGN))
+        e = dev_alloc(c, &c->vbits, (size_t)c->nwt * 64);
+    if (e == hipSuccess && server_comp == LIEC_COMP_TOPK) e = dev_alloc(c, &c->sgbits, (size_t)c->nwt * 4);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->list, rows * c->cap);
     if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->ghist, rows * kHistBins);
-    if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->lhist, rows * 2 * kListBins);
-    if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->tiebuf, rows * kTieCap);
+    if (e == hipSuccess && any_topk) e = dev_alloc(c, &c->shortl, rows * kShortCap);
     if (e == hipSuccess && any_topk) {
         // blocks that share a row meet inside the kernel, so all of them must be resident at once:
         // at most one per compute unit
@@ -608,7 +607,6 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
         e = hipMemcpy(c->desc, init.data(), rows * sizeof(RowDesc), hipMemcpyHostToDevice);
     }
     if (e == hipSuccess && any_topk) e = hipMemsetAsync(c->ghist, 0, rows * kHistBins * sizeof(uint32_t), c->stream);
-    if (e == hipSuccess && any_topk) e = hipMemsetAsync(c->lhist, 0, rows * 2 * kListBins * sizeof(uint32_t), c->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -681,14 +679,35 @@ liec_status liec_force_search_mode(liec_ctx* c, int32_t mode) {
     for (size_t r = 0; r < h.size(); ++r) {
         if (!selects_k(r < (size_t)c->N ? c->worker_comp : c->server_comp)) continue;
         h[r].mode = (uint32_t)mode;
-        h[r].n_cand = 0;
-        clear_sure(h[r]);
-        h[r].n_ties = 0;
+        clear_counts(h[r]);
     }
     if (hipMemcpy(c->desc, h.data(), h.size() * sizeof(RowDesc), hipMemcpyHostToDevice) != hipSuccess) {
         c->broken = true;
         return LIEC_EDEVICE;
     }
+    return LIEC_OK;
+}
+
+liec_status liec_get_search_state(liec_ctx* c, int32_t row, uint32_t* out) {
+    if (!c || !out || row < 0 || row > c->N) return LIEC_EINVAL;
+    if (!selects_k(row < c->N ? c->worker_comp : c->server_comp)) return LIEC_EINVAL;
+    if (c->broken) return LIEC_EDEVICE;
+    DeviceScope on(c);
+    if (!on.ok) return LIEC_EDEVICE;
+    RowDesc r;
+    if (hipStreamSynchronize(c->stream) != hipSuccess ||
+        hipMemcpy(&r, c->desc + row, sizeof r, hipMemcpyDeviceToHost) != hipSuccess) {
+        c->broken = true;
+        return LIEC_EDEVICE;
+    }
+    out[0] = r.mode;
+    out[1] = r.lo;
+    out[2] = r.hi;
+    out[3] = r.n_list;
+    out[4] = r.misses;
+    out[5] = r.swing;
+    out[6] = r.dense;
+    out[7] = 0;
     return LIEC_OK;
 }
 
@@ -1053,8 +1072,11 @@ liec_status liec_get_info(liec_ctx* c, liec_info* info) {
         info->server_tau_key = s.tau;
         info->server_cutoff = (int64_t)s.cutoff;
     }
-    for (size_t r = 0; r < h.size(); ++r)
-        if (selects_k(r < (size_t)c->N ? c->worker_comp : c->server_comp) && h[r].dense) ++info->slow_rows;
+    for (size_t r = 0; r < h.size(); ++r) {
+        if (!selects_k(r < (size_t)c->N ? c->worker_comp : c->server_comp)) continue;
+        if (h[r].dense) ++info->slow_rows;
+        info->band_misses += (int64_t)h[r].misses;
+    }
     bool bad = (c->server_comp == kSign || c->server_comp == kTopk) && s.nonfinite;
     if (c->worker_comp == kSign || c->worker_comp == kTopk)
         for (int32_t i = 0; i < c->N; ++i) bad = bad || h[(size_t)i].nonfinite;

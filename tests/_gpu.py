@@ -51,9 +51,10 @@ def check_descriptors(ctx, w, wdesc, sdesc, g_host, v_host, label):
 
 
 def run_chain(w, steps, seed=0, teacher_forced=False, mutate=None, check_descs=True, tol_end=H.TOL_CHAIN,
-               rk_seed=0, force_mode=None):
+               rk_seed=0, force_mode=None, stats=None):
     """Runs `steps` chained steps on both sides and compares after every step.  rk_seed seeds the
-    random-k draws (draw t in step t); force_mode[t], when given, is the search mode forced before step t."""
+    random-k draws (draw t in step t); force_mode[t], when given, is the search mode forced before step t;
+    stats, when given, receives the context's band_misses count at the end of the chain."""
     src = workloads.GradientSource(w, seed=seed, device=DEV)
     x = torch.zeros((w.N, w.d), dtype=torch.float32, device=DEV)
     e = torch.zeros(w.d, dtype=torch.float32, device=DEV)
@@ -86,6 +87,8 @@ def run_chain(w, steps, seed=0, teacher_forced=False, mutate=None, check_descs=T
             if w.server_comp in ("topk", "randk"):
                 assert np.array_equal(eg == 0, eo == 0), f"{label}: server index set"
             exact = exact and H.bit_equal(xg, xo) and H.bit_equal(eg, eo)
+        if stats is not None:
+            stats["band_misses"] = ctx.info().band_misses
     return exact
 
 

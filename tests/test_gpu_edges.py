@@ -265,7 +265,10 @@ def test_threshold_prediction_survives_jumps_of_the_gradient_scale(wc, sc):
     def mutate(g, t):
         return g * scales[t]
 
-    assert run_chain(w, steps=len(scales), seed=17, mutate=mutate)
+    stats = {}
+    assert run_chain(w, steps=len(scales), seed=17, mutate=mutate, stats=stats)
+    # four jumps, three worker rows each: the context counts the predictions that failed
+    assert stats["band_misses"] >= 12, f"only {stats['band_misses']} failed predictions were counted"
 
 
 @pytest.mark.parametrize("wc,sc", [("sign", "sign"), ("topk", "topk"), ("identity", "identity")])
@@ -402,3 +405,43 @@ def test_error_norm_telemetry():
         ctx.step(src.grads(4), x, e)                      # the scratch it borrowed is the step's again
         H.oracle_step_rows(src.grads(4).cpu().numpy(), xo, eo, "topk", "topk", w.lr, w.worker_k, w.server_k)
         assert H.bit_equal(x.cpu().numpy(), xo) and H.bit_equal(e.cpu().numpy(), eo)
+
+
+def test_predicted_band_narrows_while_the_predictions_hold_and_reopens_after_a_miss():
+    """The band a row is filtered against follows how far its thresholds fell from the predicted centres:
+    on steady gradients it narrows step by step (fewer listed candidates, no failed prediction), a jump of
+    the gradient scale makes the prediction fail once (counted) and the band restart wide.  Results are
+    checked against the oracle all along."""
+    import oracle
+    from paper_2402_11857_amd import LiecContext
+
+    N, d, k = 2, 2_000_000, 40_000
+    say(f"case band width trajectory N={N} d={d} k={k}")
+    w = workloads.scaled(WL["c1_tiny_sign"], N=N, d=d, worker_comp="topk", server_comp="sign", worker_k=k, lr=0.1)
+    src = workloads.GradientSource(w, seed=5, device=DEV)
+    x = torch.zeros((N, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    xo, eo = np.zeros((N, d), dtype=np.float32), np.zeros(d, dtype=np.float32)
+    widths, listed = [], []
+    with LiecContext(N, d, "topk", "sign", k, 0, 0.1) as ctx:
+        with pytest.raises(Exception):
+            ctx.search_state(N)                         # the server's operator has no threshold search
+        for t in range(24):
+            g = src.grads(t)
+            if t >= 20:
+                g = g * 8.0
+            ctx.step(g, x, e)
+            oracle.step(g.cpu().numpy(), xo, eo, "topk", "sign", 0.1, k, 0)
+            st = ctx.search_state(0)
+            widths.append(st["hi"] - st["lo"])
+            listed.append(st["listed"])
+            assert st["mode"] == 0 and st["general_search"] == 0
+            if t == 19:
+                assert ctx.info().band_misses == 0, "steady gradients: no prediction may fail"
+        assert ctx.info().band_misses == N, "the jump of the scale makes each worker row's prediction fail once"
+        assert H.bit_equal(e.cpu().numpy(), eo) and H.bit_equal(x.cpu().numpy(), xo)
+    assert widths[0] == 2 << 20, "after the first step the band is 2^20 keys on either side"
+    assert widths[19] < widths[0] // 4, f"the band must narrow on steady gradients: {widths}"
+    assert min(widths) >= 2 << 15, "the band never gets narrower than its floor"
+    assert widths[20] == 2 << 20, "a failed prediction restarts the band wide"
+    assert listed[19] < listed[1], f"fewer candidates are listed once the band has narrowed: {listed}"

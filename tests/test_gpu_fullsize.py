@@ -71,7 +71,7 @@ def _chain(w, steps, label, seed=0, mantissa_bits=23, expect_slow_rows=None, pro
             for i in range(w.N):                 # row at a time keeps the host copies small
                 _assert_same(x[i].cpu().numpy(), xo[i], tol, f"{what}: model of worker {i}")
             if (t + 1) % progress_every == 0 or t + 1 == steps:
-                say(f"  step {t} compared")
+                say(f"  step {t} compared (row-steps whose predicted band failed so far: {info.band_misses})")
             g, gh = nxt
 
 
