@@ -55,7 +55,7 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
-_LIB_OMP = os.path.join(_HERE, "libliec_oracle_omp.so")
+_LIB_OMP = os.path.splitext(_LIB)[0] + "_omp.so"     # beside whichever build LIEC_ORACLE_LIB names
 
 
 def build_all_cores(force: bool = False) -> str:
