@@ -69,7 +69,7 @@ def dominant_kernel_bytes(w) -> int:
     return 12 * w.N * w.d + 8 * w.d
 
 
-def run_workload(w, steps: int, warmup: int, seed: int = 0):
+def run_workload(w, steps: int, warmup: int, seed: int = 0, steady_only: bool = False):
     import torch
 
     import workloads
@@ -110,15 +110,17 @@ def run_workload(w, steps: int, warmup: int, seed: int = 0):
         for t in range(nb):
             ctx.step(grads[t % nbuf], x, e)
         kernels = {k: (v[0] / nb, v[1]) for k, v in ctx.profile_end().items()}
-        # the averaging iteration of Algorithm 1 (one in every `period` steps), timed on its own
-        ns = 5
-        ctx.step_sync(grads[0], x, e)
-        ctx.profile_begin(ns)
-        for t in range(ns):
-            ctx.step_sync(grads[t % nbuf], x, e)
-        sync_ms = ctx.profile_end()["sync"][0] / ns
-        wire = time_wire_forms(ctx, w, grads[0], x, e)
-        worst = time_worst_case_steps(ctx, w, grads, x, e)
+        sync_ms, wire, worst = float("nan"), None, None
+        if not steady_only:
+            # the averaging iteration of Algorithm 1 (one in every `period` steps), timed on its own
+            ns = 5
+            ctx.step_sync(grads[0], x, e)
+            ctx.profile_begin(ns)
+            for t in range(ns):
+                ctx.step_sync(grads[t % nbuf], x, e)
+            sync_ms = ctx.profile_end()["sync"][0] / ns
+            wire = time_wire_forms(ctx, w, grads[0], x, e)
+            worst = time_worst_case_steps(ctx, w, grads, x, e)
         scratch = ctx.scratch_bytes()
     ms_per_step = 1e3 * elapsed / steps
     out = {
@@ -294,6 +296,9 @@ def main() -> int:
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-also", action="store_true", help="skip the secondary workloads")
+    ap.add_argument("--steady-only", action="store_true",
+                    help="skip the steps outside the steady state, the averaging iteration and the wire forms "
+                         "(for profiler runs: every launch after the first step is then a steady-state one)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the N workers are a batch axis on a single MI355X; "
@@ -313,7 +318,7 @@ def main() -> int:
     log(f"workload {w.name}: N={w.N} d={w.d} {w.worker_comp}/{w.server_comp}")
     copy_gbps = copy_ceiling_gbps()
     log(f"copy kernel ceiling {copy_gbps:.0f} GB/s")
-    main_res = run_workload(w, args.steps, args.warmup)
+    main_res = run_workload(w, args.steps, args.warmup, steady_only=args.steady_only)
     log(f"{w.name}: {main_res['ms_per_step']:.3f} ms/step, {main_res['alg_gbps']:.0f} GB/s algorithmic")
     also = {}
     if not args.no_also:
@@ -369,10 +374,12 @@ def main() -> int:
         "wire_worker0": main_res["wire"],
         "outside_steady_state": main_res["worst"],
         "band_misses_in_warmup_and_timed_regions": main_res["band_misses"],
-        "averaging_iteration": {"ms": round(main_res["sync_ms"], 4), "alg_gbps": round(main_res["sync_gbps"], 1),
+        "averaging_iteration": None if args.steady_only else
+                               {"ms": round(main_res["sync_ms"], 4), "alg_gbps": round(main_res["sync_gbps"], 1),
                                 "note": "Algorithm 1's uncompressed iteration, one in every `period` steps; not part of value"},
         # Algorithm 1 as a whole with the averaging periods of the paper's experiments, from the two measured times
-        "algorithm1_ms_per_iteration": {f"period_{h}": round(((h - 1) * main_res["ms_per_step"] + main_res["sync_ms"]) / h, 4)
+        "algorithm1_ms_per_iteration": None if args.steady_only else
+                                       {f"period_{h}": round(((h - 1) * main_res["ms_per_step"] + main_res["sync_ms"]) / h, 4)
                                         for h in (32, 100)},
         "also": also,
         "cpu_baseline": cpu,

@@ -453,7 +453,10 @@ __device__ __forceinline__ void predict_band(RowDesc& r, uint32_t fix_lo, uint32
         return;
     }
     const int64_t tau = (int64_t)r.tau;
-    const int64_t delta = r.have_prev ? tau - (int64_t)r.prev_tau : 0;
+    int64_t delta = r.have_prev ? tau - (int64_t)r.prev_tau : 0;
+    // a change of more than 2^22 keys (a factor of 1.4 in value) that the last prediction missed is a jump, not a
+    // trend: extrapolating it would put the next band as far off again
+    if (r.was_cold && (delta > ((int64_t)1 << 22) || delta < -((int64_t)1 << 22))) delta = 0;
     int64_t swing = kBandStart;
     if (r.have_prev && !r.was_cold) {
         int64_t miss = tau - (int64_t)r.centre;
