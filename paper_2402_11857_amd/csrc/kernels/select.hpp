@@ -18,17 +18,20 @@ namespace liec {
 //      faster for rows of 48M columns and more, slower for 25M.  The band is usable when the list did
 //      not overflow and rank k falls inside it (band_ok).
 //   2. k_hist0, for rows without a prediction (kCold) or whose predicted band was not usable: the
-//      histogram of the first radix digit (12 bits) of the whole row.
-//   3. k_filter (pass over the first-digit band), for the same rows: every block picks the bin holding
-//      rank k from that histogram, and the row is filtered again with that bin as its band, counting
-//      into a second set of counters.
-//   4. k_list_select, one block per row: a 2-digit radix select on the listed keys, taken relative to
-//      the band's lower end, then the ties in index order (up to 4096 of them through LDS, more by a
-//      radix select over the listed indices); writes (tau, cut-off), predicts the next band.  Rows
-//      whose band the list cannot hold (constant or near-constant rows) are put into kSlow mode.
+//      histogram of the first radix digit (12 bits) of the whole row.  For rows on their predicted band
+//      with a long list it counts the first digit of the listed keys instead (list_first_digit).
+//   3. k_filter (pass over the first-digit band), for the rows of the first kind: every block picks the
+//      bin holding rank k from that histogram, and the row is filtered again with that bin as its band,
+//      counting into a second set of counters.  For the rows of the second kind every block picks the
+//      first list digit's bin and the bin's entries are collected into a short list (list_collect).
+//   4. k_list_select, one block per row: radix digits over the listed keys, taken relative to the band's
+//      lower end (over the short list when there is one), then the ties in index order (up to 4096 of
+//      them through LDS, more by a radix select over the listed indices); writes (tau, cut-off), predicts
+//      the next band.  Rows whose band the list cannot hold (constant or near-constant rows) are put
+//      into kSlow mode.
 //   5. k_slow_select takes the kSlow rows.
 // All decisions are taken on the device per row, each kernel re-deriving from the row's mode and
-// counters whether it has work; kernels 2, 3 and 5 return at once in the steady state.  A row's mode
+// counters whether it has work; in the steady state kernels 2 and 3 only touch the lists and 5 returns at once.  A row's mode
 // and its result are written only by k_list_select and k_slow_select.
 // `row0` is added to blockIdx.y to address per-row state (the server's vector uses row N).
 // ---------------------------------------------------------------------------------------------

@@ -270,8 +270,9 @@ struct Launcher {
 
 // Top-k threshold search (Definition 2) of `rows` rows of `src`; per-row state lives at row0 + r.
 // The host enqueues the same five kernels every step; each one acts only on the rows whose state
-// asks for it, so the steady state costs one pass over the data and one block per row of list select,
-// and the others return at once.
+// asks for it, so the steady state costs one pass over the data, two short passes over the candidate
+// lists (in the launches that otherwise serve rows without a prediction) and one block per row of list
+// select; the general search returns at once.
 // RK: the same search over the priorities of a random-k draw (Definition 3), which read nothing from
 // `src`, followed by the kernel that completes the kept bitmap.
 template <bool VEC, bool RK>
