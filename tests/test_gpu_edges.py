@@ -445,3 +445,36 @@ def test_predicted_band_narrows_while_the_predictions_hold_and_reopens_after_a_m
     assert min(widths) >= 2 << 15, "the band never gets narrower than its floor"
     assert widths[20] == 2 << 20, "a failed prediction restarts the band wide"
     assert min(listed[2:20]) < listed[1] // 2, f"fewer candidates are listed once the band has narrowed: {listed}"
+
+
+@pytest.mark.parametrize("frac,sc", [(0.10, "topk"), (0.5, "sign"), (0.006, "topk")])
+def test_long_candidate_lists_take_the_shared_passes(frac, sc):
+    """Large k and the wide band of the first predicted steps give candidate lists far beyond what one block
+    selects on its own (16 384 entries): the first list digit is counted and its bin collected by many blocks,
+    or, when the bin itself is too large for the short list, the list is walked.  Gradients cut to 9 mantissa
+    bits add thousands of equal keys.  Every step is checked against the oracle."""
+    import oracle
+    from paper_2402_11857_amd import LiecContext
+
+    N, d = 2, 3_000_000
+    k = int(frac * d)
+    sk = k if sc == "topk" else 0
+    say(f"case long candidate lists N={N} d={d} k={k} server {sc}")
+    w = workloads.scaled(WL["c1_tiny_sign"], N=N, d=d, worker_comp="topk", server_comp=sc, worker_k=k, server_k=sk, lr=0.1)
+    src = workloads.GradientSource(w, seed=31, device=DEV)
+    x = torch.zeros((N, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    xo, eo = np.zeros((N, d), dtype=np.float32), np.zeros(d, dtype=np.float32)
+    longest = 0
+    with LiecContext(N, d, "topk", sc, k, sk, 0.1) as ctx:
+        for t in range(4):
+            g = src.grads(t)
+            if t >= 2:
+                g = (g.view(torch.int32) & -(1 << 14)).view(torch.float32).contiguous()
+            ctx.step(g, x, e)
+            oracle.step(g.cpu().numpy(), xo, eo, "topk", sc, 0.1, k, sk)
+            assert H.bit_equal(e.cpu().numpy(), eo), f"step {t}: server error"
+            assert H.bit_equal(x.cpu().numpy(), xo), f"step {t}: models"
+            longest = max(longest, ctx.search_state(0)["listed"])
+            assert ctx.info().slow_rows == 0
+    assert longest > 16_384, f"the case must list more candidates than one block takes on its own ({longest})"
