@@ -92,7 +92,8 @@ typedef struct {
  * Allocates the context's device scratch: 4d bytes for v; N * d / 8 for sign or
  * random-k bitmaps; with top-k or random-k on either side also (N + 1) * 8 *
  * (min(d / 16, 8 k) + 4096) for the candidate lists, N * d / 32 for the group bitmap and about
- * 120 KiB per row of histograms (liec_scratch_bytes reports the total).  The
+ * 50 KiB per row of histograms and short lists; d / 8 for the server's sign bits or d / 32 for its
+ * group bitmap (liec_scratch_bytes reports the total).  The
  * context belongs to the HIP device that is current at this call: every later call
  * on it makes that device current for its own duration and puts the caller's back.
  */
