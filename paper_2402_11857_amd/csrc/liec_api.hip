@@ -755,11 +755,17 @@ liec_status liec_step_sync(liec_ctx* c, const float* grads, float* x, float* ser
     if (c->profiling && c->prof_steps_left <= 0) c->profiling = false;
     if (c->profiling) --c->prof_steps_left;
     const float inv_n = 1.0f / (float)c->N;
+    const uint32_t panel = c->ncol_tiles < kUpdatePanel ? c->ncol_tiles : kUpdatePanel;
+    const uint32_t npanels = (c->ncol_tiles + panel - 1) / panel;
+    const uint32_t spread_blocks = (uint32_t)((uint64_t)npanels * panel * (uint64_t)c->N);
     L.begin(S_SYNC);
-    if (vec)
-        k_sync<true><<<c->ncol_tiles, kBlock, 0, c->stream>>>(grads, x, server_err, c->N, (uint32_t)c->d, inv_n, -c->lr);
-    else
-        k_sync<false><<<c->ncol_tiles, kBlock, 0, c->stream>>>(grads, x, server_err, c->N, (uint32_t)c->d, inv_n, -c->lr);
+    if (vec) {
+        k_sync_reduce<true><<<c->ncol_tiles, kBlock, 0, c->stream>>>(grads, x, server_err, c->N, (uint32_t)c->d, inv_n, -c->lr);
+        k_sync_spread<true><<<spread_blocks, kBlock, 0, c->stream>>>(x, server_err, c->N, panel, c->ncol_tiles, (uint32_t)c->d);
+    } else {
+        k_sync_reduce<false><<<c->ncol_tiles, kBlock, 0, c->stream>>>(grads, x, server_err, c->N, (uint32_t)c->d, inv_n, -c->lr);
+        k_sync_spread<false><<<spread_blocks, kBlock, 0, c->stream>>>(x, server_err, c->N, panel, c->ncol_tiles, (uint32_t)c->d);
+    }
     L.end();
     c->profiling = was_profiling;
     if (!L.ok) {
