@@ -20,10 +20,9 @@ constexpr int kChunk = 256;             // columns per wave and load instruction
 constexpr int kWaveTile = 1024;         // columns per wave iteration
 constexpr int kColTile = 1024;          // columns per block of the update kernel
 constexpr int kHistBins = 4096;         // first radix digit of a whole row (12 bits)
-constexpr int kSureStripes = 16;        // counters per row for the keys above the band
 constexpr int kListBits = 13;           // widest radix digit of the list select (two digits cover a band of 2^26 keys)
 constexpr int kListBins = 1 << kListBits;
-constexpr int kStage = 512;             // per-wave LDS staging slots of the candidate filter
+constexpr int kStage = 2048;            // LDS staging slots of a block of the candidate filter
 constexpr int kDirectList = 16384;      // candidate lists up to this length are selected by one block on its own
 constexpr int kShortCap = 4096;         // entries of the first list digit's bin that are handed to the list select on their own
 constexpr int kTieCap = 4096;           // ties at the threshold the fast path resolves
@@ -43,7 +42,8 @@ enum SelMode : uint32_t {
 };
 
 // One per worker row, plus one (index N) for the server's vector v.
-struct RowDesc {
+struct alignas(128) RowDesc {
+    // first 128-byte line: what the kernels read, written once a step by whoever finishes the row's search
     double l1;             // scaled sign: sum |v_j| (fp64)
     float scale;           // scaled sign: fp32(l1 / d)
     uint32_t tau;          // top-k: key of the k-th kept entry
@@ -51,16 +51,8 @@ struct RowDesc {
     uint32_t ties;         // top-k: how many entries have key == tau
     uint32_t cutoff;       // top-k: largest kept index among entries with key == tau
     uint32_t nonfinite;    // a NaN/Inf reached the L1 sum or a key (last step)
-    uint32_t nonfinite_acc;
     uint32_t lo, hi;       // candidate band: keys in [lo, hi) are listed, keys >= hi are surely kept
     uint32_t mode;         // SelMode
-    uint32_t n_cand;       // candidates the pass over the predicted band appended (may exceed the capacity: overflow)
-    uint32_t n_sure[kSureStripes];   // keys at or above that band seen by the pass; block b of the filter adds
-                           // to stripe b % kSureStripes (one address would serialise the blocks' atomics)
-    uint32_t n_cand2;      // the same two counts for the pass over the first-digit band, which runs when there is
-    uint32_t n_sure2[kSureStripes];  // no prediction or the predicted band failed (its own set, so that every
-                           // kernel can still tell from the first set that the row needed this pass)
-    uint32_t n_short;      // entries of the first list digit's bin collected into the row's short list
     uint32_t n_list;       // candidates that were listed when the search finished (random-k marks the kept ones)
     uint32_t dense;        // the row's candidate bitmap is not valid: test every column
     uint32_t prev_tau;     // tau of the step before (valid when have_prev)
@@ -69,27 +61,29 @@ struct RowDesc {
     uint32_t centre;       // where the last prediction expected tau
     uint32_t swing;        // decaying maximum of the distances between tau and that centre
     uint32_t was_cold;     // the last band came from the first-digit histogram, not from a prediction
+    // second line: what the blocks of the passes add to with atomics (kept off the line every block reads when
+    // it starts).  Counters of the pass over the predicted band, one 64-bit word that a block of the filter adds
+    // to with a single atomic.  Low half: candidates appended (may exceed the capacity: overflow); high half:
+    // keys at or above the band.
+    alignas(128) uint32_t n_cand;
+    uint32_t n_sure;
+    // the same for the pass over the first-digit band, which runs when there is no prediction or the predicted
+    // band failed (its own set, so that every kernel can still tell from the first set that the row needed it)
+    alignas(8) uint32_t n_cand2;
+    uint32_t n_sure2;
+    uint32_t n_short;      // entries of the first list digit's bin collected into the row's short list
+    uint32_t nonfinite_acc;   // this step's Inf / NaN sightings (moved to `nonfinite` when the search finishes)
 };
+static_assert(sizeof(RowDesc) == 256, "two lines per row");
 
-__host__ __device__ __forceinline__ uint32_t sure_count(const RowDesc& r) {
-    uint32_t n = 0;
-#pragma unroll
-    for (int q = 0; q < kSureStripes; ++q) n += r.n_sure[q];
-    return n;
-}
-__host__ __device__ __forceinline__ uint32_t sure_count2(const RowDesc& r) {
-    uint32_t n = 0;
-#pragma unroll
-    for (int q = 0; q < kSureStripes; ++q) n += r.n_sure2[q];
-    return n;
-}
+__host__ __device__ __forceinline__ uint32_t sure_count(const RowDesc& r) { return r.n_sure; }
+__host__ __device__ __forceinline__ uint32_t sure_count2(const RowDesc& r) { return r.n_sure2; }
 // Both passes' counters back to zero (whoever finishes a row's search calls it).
 __host__ __device__ __forceinline__ void clear_counts(RowDesc& r) {
     r.n_cand = 0;
     r.n_cand2 = 0;
     r.n_short = 0;
-#pragma unroll
-    for (int q = 0; q < kSureStripes; ++q) r.n_sure[q] = r.n_sure2[q] = 0;
+    r.n_sure = r.n_sure2 = 0;
 }
 
 // After a filter pass: the band is usable when its list did not overflow and rank k falls inside it.

@@ -1,6 +1,7 @@
 // Threshold search behind top-k (Definition 2) and random-k (Definition 3).
 #pragma once
 #include "common.hpp"
+#include <type_traits>
 
 namespace liec {
 
@@ -12,7 +13,7 @@ namespace liec {
 //      only counted, keys inside the band are appended to a candidate list (key, index), and a group
 //      bitmap is written for the aggregation kernel, in one of two forms the host picks from the row
 //      length.  Fine: 4 words of 64 bits per wave tile, bit l of word u set when any of the 4 columns
-//      1024t + 256u + 4l .. + 3 has key >= lo.  Coarse: one word per wave tile, bit 16u + m set when any
+//      1024t + 256u + 4l .. + 3 has key >= lo.  Coarse: one word per wave tile, bit 4m + u set when any
 //      of the 16 columns 1024t + 256u + 16m .. + 15 (one 64-byte line, the unit a gather fetches anyway)
 //      has one -- 8 bytes written per 4 KiB read (writes are what a read stream pays most for); measured
 //      faster for rows of 48M columns and more, slower for 25M.  The band is usable when the list did
@@ -35,28 +36,25 @@ namespace liec {
 // and its result are written only by k_list_select and k_slow_select.
 // `row0` is added to blockIdx.y to address per-row state (the server's vector uses row N).
 // ---------------------------------------------------------------------------------------------
-// Bit m of the result: some lane of 4m .. 4m + 3 has its bit set in the ballot (those four lanes own one
-// 64-byte line of the row).
+// Coarse group bitmap: bit 4m of the result is set when some lane of 4m .. 4m + 3 has its bit set in the
+// ballot (those four lanes own one 64-byte line of the row).  Chunk u of a wave tile shifts its result
+// left by u, so bit 4m + u of the tile's word stands for line m of chunk u.
 __device__ __forceinline__ uint64_t any_of_four_lanes(uint64_t b) {
     b |= b >> 1;
     b |= b >> 2;
-    b &= 0x1111111111111111ull;                                 // bit 4m: any lane of the m-th four
-    b = (b | (b >> 3)) & 0x0303030303030303ull;                 // then squeeze the 16 bits together
-    b = (b | (b >> 6)) & 0x000f000f000f000full;
-    b = (b | (b >> 12)) & 0x000000ff000000ffull;
-    return (b | (b >> 24)) & 0xffffull;
+    return b & 0x1111111111111111ull;
 }
 
 // One chunk (256 columns, 4 per lane) of the filter: updates the per-lane count of keys >= hi and the
-// running maximum key, returns the ballot of "any of my 4 columns has key >= lo" and, per component,
-// the ballots of the candidates lo <= key < hi.  FULL: every column of the chunk is below d.
-template <bool FULL>
+// running maximum key, returns the ballot of "any of my 4 columns has key >= lo" and, per component q,
+// the ballot bc[q] of the candidates lo <= key < hi.  The comparisons stay wave ballots (scalar
+// registers) and are combined there, which leaves the vector unit two compares, one add and half a
+// maximum per key.  FULL: every column of the chunk is below d.  BITS: also hi4, bit q set when my
+// column q has key >= hi.
+template <bool FULL, bool BITS>
 __device__ __forceinline__ uint64_t filter_chunk(const uint32_t (&keys)[4], uint32_t j, uint32_t d, uint32_t lo, uint32_t hi,
-                                                 uint32_t& cand4, uint64_t& any_cand,
-                                                 uint32_t& n_hi, uint32_t& kmax, uint32_t& hi4) {
-    // per lane: which of its 4 columns reach the band (lo4) and which lie above it (hi4); two ballots per
-    // chunk tell the wave whether anything has to be listed (the per-column ballots are made only then)
-    uint32_t lo4 = 0;
+                                                 uint64_t (&bc)[4], uint32_t& n_hi, uint32_t& kmax, uint32_t& hi4) {
+    uint64_t any_lo = 0;
     hi4 = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -65,12 +63,12 @@ __device__ __forceinline__ uint64_t filter_chunk(const uint32_t (&keys)[4], uint
         const bool ge_lo = valid && key >= lo, ge_hi = valid && key >= hi;
         kmax = max(kmax, valid ? key : 0u);
         n_hi += ge_hi ? 1u : 0u;
-        lo4 |= (ge_lo ? 1u : 0u) << q;
-        hi4 |= (ge_hi ? 1u : 0u) << q;
+        if (BITS) hi4 |= (ge_hi ? 1u : 0u) << q;
+        const uint64_t b_lo = __ballot(ge_lo);
+        bc[q] = b_lo & ~__ballot(ge_hi);
+        any_lo |= b_lo;
     }
-    cand4 = lo4 & ~hi4;
-    any_cand = __ballot(cand4 != 0);
-    return __ballot(lo4 != 0);
+    return any_lo;
 }
 
 // List select: the keys of a band are taken relative to its lower end and need b <= 26 bits.  The first
@@ -151,18 +149,20 @@ __device__ __forceinline__ void list_collect(RowDesc* __restrict__ desc, uint32_
 // needs 256 threads and 259 words of LDS), the second counter set.  False when the block has no work.
 struct FilterBand {
     uint32_t lo, hi;
-    uint32_t* n_cand;
-    uint32_t* n_sure;
+    uint2* out;                                  // the row's list and its capacity
+    uint32_t cap;
+    unsigned long long* counts;                  // the pass's counter word: candidates (low half), keys above the band (high half)
 };
 __device__ __forceinline__ bool filter_band(RowDesc* __restrict__ desc, uint32_t row, bool cold_pass,
-                                            const uint32_t* __restrict__ ghist, uint32_t cap, uint32_t k,
-                                            uint32_t* part, uint32_t* res, FilterBand& fb) {
+                                            const uint32_t* __restrict__ ghist, uint2* __restrict__ list, uint32_t cap,
+                                            uint32_t k, uint32_t* part, uint32_t* res, FilterBand& fb) {
+    fb.out = list + (size_t)row * cap;
+    fb.cap = cap;
     if (!cold_pass) {
         if (desc[row].mode != kWarm) return false;
         fb.lo = desc[row].lo;
         fb.hi = desc[row].hi;
-        fb.n_cand = &desc[row].n_cand;
-        fb.n_sure = desc[row].n_sure;
+        fb.counts = reinterpret_cast<unsigned long long*>(&desc[row].n_cand);
         return true;
     }
     if (!wants_cold(desc[row], cap, k)) return false;
@@ -170,9 +170,69 @@ __device__ __forceinline__ bool filter_band(RowDesc* __restrict__ desc, uint32_t
     if (p.count > cap) return false;             // the list cannot hold the bin: the row takes the general search
     fb.lo = p.bin << 19;
     fb.hi = (p.bin + 1) << 19;                   // 0x80000000 for the top bin: no key reaches it
-    fb.n_cand = &desc[row].n_cand2;
-    fb.n_sure = desc[row].n_sure2;
+    fb.counts = reinterpret_cast<unsigned long long*>(&desc[row].n_cand2);
     return true;
+}
+
+// Where the results of a filter block go.  Atomics on a row's counters are what the pass pays most for besides
+// its stores.  Measured alone on 16 rows of 138M columns: a pass that writes nothing runs at the read ceiling
+// (1.29 ms); one atomic per block, and nothing else written, takes it to 1.44 ms whether 2 000 or 15 000 blocks
+// do it; an atomic per wave for the list and one per block for the count gave 1.5-1.6 ms, and 3.7 ms with 2 800
+// blocks a row while the counters shared a line with the fields every block reads when it starts.  So the
+// block's waves append their candidates to one stage in LDS (an LDS counter hands out the positions), and when
+// the block is done a single 64-bit atomic adds its keys above the band to the high half of the row's counter
+// word and reserves, in the low half, the list slots of what was staged.  Entries beyond the stage (kStage per
+// block: wide bands, constant rows) go straight to list slots that the wave reserves with an atomic of its own.
+struct StagePos {
+    uint32_t pos;                                // block position of the wave's first entry
+    uint32_t first_spill;                        // first of its positions beyond the stage
+    uint32_t spill_base;                         // the list slot reserved for that entry
+};
+// The wave has m entries to append (wave-uniform, every lane calls).
+__device__ __forceinline__ StagePos reserve_stage(const FilterBand& fb, uint32_t m, uint32_t* staged_n, uint32_t lane) {
+    StagePos sp;
+    uint32_t pos = 0;
+    if (lane == 0) pos = atomicAdd(staged_n, m);                // LDS
+    sp.pos = __builtin_amdgcn_readfirstlane(pos);
+    sp.first_spill = max(sp.pos, (uint32_t)kStage);
+    sp.spill_base = 0;
+    if (sp.pos + m > (uint32_t)kStage) {                        // uniform
+        uint32_t at = 0;
+        if (lane == 0) at = (uint32_t)atomicAdd(fb.counts, (unsigned long long)(sp.pos + m - sp.first_spill));
+        sp.spill_base = __builtin_amdgcn_readfirstlane(at);
+    }
+    return sp;
+}
+// Entry number `ord` of those m (any subset of lanes).
+__device__ __forceinline__ void put_candidate(const FilterBand& fb, uint2* stage, const StagePos& sp, uint32_t ord, uint2 entry) {
+    const uint32_t p = sp.pos + ord;
+    if (p < (uint32_t)kStage) {
+        stage[p] = entry;
+    } else {
+        const uint32_t at = sp.spill_base + (p - sp.first_spill);
+        if (at < fb.cap) fb.out[at] = entry;
+    }
+}
+
+// End of a filter block.  n_hi: keys above the band, per lane.  Every thread of the block calls it.
+__device__ __forceinline__ void finish_filter_block(const FilterBand& fb, const uint2* stage, uint32_t n_hi,
+                                                    const uint32_t* staged_n, uint32_t* wsure /* 5 words */) {
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) n_hi += __shfl_down(n_hi, o, 64);
+    if (lane == 0) wsure[wave] = n_hi;
+    __syncthreads();
+    const uint32_t staged = min(*staged_n, (uint32_t)kStage);
+    if (threadIdx.x == 0) {
+        const uint32_t sure = wsure[0] + wsure[1] + wsure[2] + wsure[3];
+        uint32_t base = 0;
+        if (sure | staged) base = (uint32_t)atomicAdd(fb.counts, ((unsigned long long)sure << 32) | staged);
+        wsure[4] = base;
+    }
+    __syncthreads();
+    const uint32_t base = wsure[4];
+    for (uint32_t s = threadIdx.x; s < staged; s += kBlock)
+        if (base + s < fb.cap) fb.out[base + s] = stage[s];
 }
 
 // RK: the keys are the priorities of a random-k draw (nothing is read from src), and instead of the
@@ -185,8 +245,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
                                                     uint64_t* __restrict__ gbits,
                                                     uint16_t* __restrict__ kbits, uint2* __restrict__ list, uint32_t cap,
                                                     uint2* __restrict__ shortl, RkDraw rk, bool coarse, uint32_t run) {
-    __shared__ uint2 stage[4][kStage];
-    __shared__ uint32_t wsure[4];
+    __shared__ uint2 stage[kStage];
+    __shared__ uint32_t wsure[5], staged_n;
     __shared__ uint32_t part[256], res[3];
     const uint32_t row = row0 + blockIdx.y;
     if (cold_pass && desc[row].mode == kWarm && !wants_cold(desc[row], cap, k)) {   // uniform for the block
@@ -195,32 +255,38 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
         return;
     }
     FilterBand fb;
-    if (!filter_band(desc, row, cold_pass, ghist, cap, k, part, res, fb)) return;   // uniform for the block
+    if (!filter_band(desc, row, cold_pass, ghist, list, cap, k, part, res, fb)) return;   // uniform for the block
+    if (threadIdx.x == 0) staged_n = 0;
+    __syncthreads();
     const uint32_t lo = fb.lo, hi = fb.hi;
     const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
-    uint2* __restrict__ out = list + (size_t)row * cap;
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     uint32_t k0 = 0, k1 = 0;
     if (RK) {
         const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
         k0 = (uint32_t)stream;
         k1 = (uint32_t)(stream >> 32);
     }
-    uint2* st = stage[wave];
-    uint32_t cnt = 0;                                           // staged candidates (wave-uniform)
     uint32_t n_hi = 0, kmax = 0;                                // per lane: keys >= hi seen, largest key seen
-    // a wave takes `run` consecutive wave tiles at a time and a block 4 * run (long rows: 4, so that the
-    // group words one block writes fill whole lines of the bitmap; short rows: 1, more blocks in flight)
-    for (uint32_t tb = (blockIdx.x * 4 + wave) * run; tb < nwt; tb += gridDim.x * 4 * run)
-    for (uint32_t t = tb; t < min(tb + run, nwt); ++t) {
+    // the body for one wave tile; FULL (every column of the tile is below d) drops the bounds checks
+    uint64_t pend = 0;                                          // group words of the run so far: coarse, lane i holds tile i's;
+                                                                // fine, lane 4i + u holds word u of tile i
+    auto tile = [&](auto full_c, uint32_t t, uint32_t ti) {
+        constexpr bool FULL = decltype(full_c)::value;
         float4 a[4];
         if (!RK) {
+            if (VEC && FULL) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
+                for (int u = 0; u < 4; ++u) {
+                    const v4f w = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(g + (size_t)t * kWaveTile + u * kChunk + lane * 4));
+                    a[u] = make_float4(w.x, w.y, w.z, w.w);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) a[u] = ld4<VEC, true>(g, t * kWaveTile + u * kChunk + lane * 4, d);
+            }
         }
-        const bool full = (t + 1) * (uint32_t)kWaveTile <= d;  // wave-uniform
-        uint64_t word = 0;                                      // fine: lane u (< 4) ends up holding group word u;
-                                                                // coarse: the tile's one group word (wave-uniform)
+        uint64_t line_word = 0;                                 // the tile's one coarse group word (wave-uniform)
         uint32_t sure16 = 0;                                    // RK: bit 4u + q: my column q of chunk u has key >= hi
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -235,65 +301,50 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
                 keys[2] = key_of(a[u].z);
                 keys[3] = key_of(a[u].w);
             }
-            uint64_t any_cand;
-            uint32_t cand4, hi4;
-            const uint64_t any_lo = full ? filter_chunk<true>(keys, j, d, lo, hi, cand4, any_cand, n_hi, kmax, hi4)
-                                         : filter_chunk<false>(keys, j, d, lo, hi, cand4, any_cand, n_hi, kmax, hi4);
-            if (coarse) word |= any_of_four_lanes(any_lo) << (16 * u);
-            else word = lane == (uint32_t)u ? any_lo : word;
+            uint64_t bc[4];
+            uint32_t hi4;
+            const uint64_t any_lo = filter_chunk<FULL, RK>(keys, j, d, lo, hi, bc, n_hi, kmax, hi4);
+            if (!RK) {                                          // both forms, without a branch: a few scalar operations
+                line_word |= any_of_four_lanes(any_lo) << u;
+                if (!coarse) pend = lane == 4 * ti + (uint32_t)u ? any_lo : pend;
+            }
             sure16 |= hi4 << (4 * u);
+            const uint64_t any_cand = bc[0] | bc[1] | bc[2] | bc[3];
             if (any_cand) {                                     // wave-uniform
-                uint64_t bc[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) bc[q] = __ballot((cand4 >> q) & 1u);
                 const uint32_t m = __popcll(bc[0]) + __popcll(bc[1]) + __popcll(bc[2]) + __popcll(bc[3]);
-                if (cnt + m > kStage) {                         // flush the staged candidates
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    uint32_t base = 0;
-                    if (lane == 0) base = atomicAdd(fb.n_cand, cnt);
-                    base = __builtin_amdgcn_readfirstlane(base);
-                    for (uint32_t s = lane; s < cnt; s += 64)
-                        if (base + s < cap) out[base + s] = st[s];
-                    cnt = 0;
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                }
-                uint32_t off = cnt;
+                const StagePos sp = reserve_stage(fb, m, &staged_n, lane);
+                uint32_t off = 0;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    if ((bc[q] >> lane) & 1) st[off + lanes_below(bc[q])] = make_uint2(keys[q], j + q);
+                    if ((bc[q] >> lane) & 1) put_candidate(fb, stage, sp, off + lanes_below(bc[q]), make_uint2(keys[q], j + q));
                     off += __popcll(bc[q]);
                 }
-                cnt += m;
             }
         }
-        if (RK) {
-            kbits[((size_t)row * nwt + t) * 64 + lane] = (uint16_t)sure16;
-        } else {
-            if (gbits && coarse) {
-                if (lane == 0) gbits[(size_t)blockIdx.y * nwt + t] = word;
-            } else if (gbits && lane < 4) {
-                gbits[((size_t)blockIdx.y * nwt + t) * 4 + lane] = word;
+        if (RK) kbits[((size_t)row * nwt + t) * 64 + lane] = (uint16_t)sure16;
+        else if (coarse) pend = lane == ti ? line_word : pend;
+    };
+    // A wave takes `run` (at most 16) consecutive wave tiles at a time and stores their group words together
+    // (a block's four waves then fill whole 128-byte lines of the coarse bitmap with run = 4; measured equal to a
+    // store per tile, and to longer runs: what the bitmap costs the pass, a tenth of its time, goes with the
+    // bytes written, not with the number of stores).  Short rows keep run = 1, so that enough blocks are in flight.
+    for (uint32_t tb = (blockIdx.x * 4 + wave) * run; tb < nwt; tb += gridDim.x * 4 * run) {
+        const uint32_t te = min(tb + run, nwt);
+        for (uint32_t t = tb; t < te; ++t) {
+            if ((t + 1) * (uint32_t)kWaveTile <= d) tile(std::true_type{}, t, t - tb);    // wave-uniform
+            else tile(std::false_type{}, t, t - tb);
+        }
+        if (!RK && gbits) {
+            if (coarse) {
+                if (lane < te - tb) gbits[(size_t)blockIdx.y * nwt + tb + lane] = pend;
+            } else if (lane < 4 * (te - tb)) {
+                gbits[((size_t)blockIdx.y * nwt + tb) * 4 + lane] = pend;
             }
         }
     }
     // keys at or above 0x7f800000 are Inf / NaN (magnitude keys only: priorities use the whole range)
     if (!RK && __ballot(kmax >= 0x7f800000u) && lane == 0) atomicOr(&desc[row].nonfinite_acc, 1u);
-    if (cnt) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        uint32_t base = 0;
-        if (lane == 0) base = atomicAdd(fb.n_cand, cnt);
-        base = __builtin_amdgcn_readfirstlane(base);
-        for (uint32_t s = lane; s < cnt; s += 64)
-            if (base + s < cap) out[base + s] = st[s];
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) n_hi += __shfl_down(n_hi, o, 64);
-    if (lane == 0) wsure[wave] = n_hi;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const uint32_t n = wsure[0] + wsure[1] + wsure[2] + wsure[3];
-        if (n) atomicAdd(&fb.n_sure[blockIdx.x % kSureStripes], n);
-    }
+    finish_filter_block(fb, stage, n_hi, &staged_n, wsure);
 }
 
 // Random-k when the band is thin against the row (k * 2^32 / d well below d): instead of computing the
@@ -317,8 +368,8 @@ __global__ __launch_bounds__(kBlock) void k_rk_filter_inverse(uint32_t d, uint32
                                                                const uint32_t* __restrict__ ghist, uint32_t k,
                                                                uint16_t* __restrict__ kbits, uint2* __restrict__ list,
                                                                uint32_t cap, uint2* __restrict__ shortl, RkDraw rk) {
-    __shared__ uint2 stage[4][kStage];
-    __shared__ uint32_t wsure[4];
+    __shared__ uint2 stage[kStage];
+    __shared__ uint32_t wsure[5], staged_n;
     __shared__ uint32_t part[256], res[3];
     const uint32_t row = row0 + blockIdx.y;
     if (cold_pass && desc[row].mode == kWarm && !wants_cold(desc[row], cap, k)) {   // uniform for the block
@@ -327,16 +378,16 @@ __global__ __launch_bounds__(kBlock) void k_rk_filter_inverse(uint32_t d, uint32
         return;
     }
     FilterBand fb;
-    if (!filter_band(desc, row, cold_pass, ghist, cap, k, part, res, fb)) return;   // uniform for the block
+    if (!filter_band(desc, row, cold_pass, ghist, list, cap, k, part, res, fb)) return;   // uniform for the block
+    if (threadIdx.x == 0) staged_n = 0;
+    __syncthreads();
     const uint32_t lo = fb.lo, hi = fb.hi;
-    uint2* __restrict__ out = list + (size_t)row * cap;
     uint32_t* __restrict__ words = reinterpret_cast<uint32_t*>(kbits + (size_t)row * nwt * 64);
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
     const uint32_t k0 = (uint32_t)stream, k1 = (uint32_t)(stream >> 32);
     const uint64_t y_begin = 2ull * lo, y_end = 1ull << 32;    // words whose priority is at least lo
-    uint2* st = stage[wave];
-    uint32_t cnt = 0, n_hi = 0;
+    uint32_t n_hi = 0;
     for (uint64_t base = y_begin + ((uint64_t)blockIdx.x * 4 + wave) * 64; base < y_end; base += (uint64_t)gridDim.x * kBlock) {
         const uint64_t y64 = base + lane;
         const uint32_t y = (uint32_t)y64, key = y >> 1;
@@ -352,36 +403,11 @@ __global__ __launch_bounds__(kBlock) void k_rk_filter_inverse(uint32_t d, uint32
         const uint64_t bc = __ballot(ok && !ge_hi);             // candidates: lo <= key < hi
         if (bc) {                                               // wave-uniform
             const uint32_t m = __popcll(bc);
-            if (cnt + m > kStage) {
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                uint32_t at = 0;
-                if (lane == 0) at = atomicAdd(fb.n_cand, cnt);
-                at = __builtin_amdgcn_readfirstlane(at);
-                for (uint32_t s = lane; s < cnt; s += 64)
-                    if (at + s < cap) out[at + s] = st[s];
-                cnt = 0;
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            }
-            if ((bc >> lane) & 1) st[cnt + lanes_below(bc)] = make_uint2(key, j);
-            cnt += m;
+            const StagePos sp = reserve_stage(fb, m, &staged_n, lane);
+            if ((bc >> lane) & 1) put_candidate(fb, stage, sp, lanes_below(bc), make_uint2(key, j));
         }
     }
-    if (cnt) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        uint32_t at = 0;
-        if (lane == 0) at = atomicAdd(fb.n_cand, cnt);
-        at = __builtin_amdgcn_readfirstlane(at);
-        for (uint32_t s = lane; s < cnt; s += 64)
-            if (at + s < cap) out[at + s] = st[s];
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) n_hi += __shfl_down(n_hi, o, 64);
-    if (lane == 0) wsure[wave] = n_hi;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const uint32_t n = wsure[0] + wsure[1] + wsure[2] + wsure[3];
-        if (n) atomicAdd(&fb.n_sure[blockIdx.x % kSureStripes], n);
-    }
+    finish_filter_block(fb, stage, n_hi, &staged_n, wsure);
 }
 
 // First radix digit (12 bits) of every key of the rows that have no usable band; for the rows whose
@@ -401,7 +427,7 @@ __global__ __launch_bounds__(kBlock) void k_hist0(const float* __restrict__ src,
     const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
     for (int b = threadIdx.x; b < kHistBins; b += kBlock) h[b] = 0;
     __syncthreads();
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     uint32_t k0 = 0, k1 = 0;
     if (RK) {
         const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
@@ -1039,7 +1065,7 @@ __global__ __launch_bounds__(kBlock) void k_rk_mark(uint32_t d, uint32_t nwt, ui
     }
     const uint64_t stream = rk_stream(rk.state->seed, rk.state->draw, row);
     const uint32_t k0 = (uint32_t)stream, k1 = (uint32_t)(stream >> 32);
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
         uint32_t m = 0;
 #pragma unroll

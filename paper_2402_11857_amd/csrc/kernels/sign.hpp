@@ -18,7 +18,7 @@ __global__ __launch_bounds__(kBlock) void k_l1_bits(const float* __restrict__ sr
     __shared__ double lds_w[4];
     const uint32_t row = blockIdx.y;
     const float* __restrict__ g = src + (size_t)row * row_stride;
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     double acc = 0.0;
     for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
         float4 a[4];
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kBlock) void k_l1_items(const float* __restrict__ s
     __shared__ double lds_w[4];
     const L1Item it = items[blockIdx.x];
     const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const uint32_t t = it.tile * 4 + wave;
     double acc = 0.0;
     if (t < nwt) {

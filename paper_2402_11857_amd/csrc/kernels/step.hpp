@@ -115,7 +115,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
             float* my = accs + threadIdx.x;                    // slot b of this lane: my[b * kBlock]
 #pragma unroll
             for (int b = 0; b < 16; ++b) my[b * kBlock] = 0.f;
-            // the tile's group word(s) of row 0: one (coarse: a bit per 64-byte line) or four (a bit per lane)
+            // the tile's group word(s) of row 0: one (coarse: bit 4m + u for 64-byte line m of chunk u) or four (a bit per lane)
             const uint64_t* __restrict__ gw = gbits + (coarse ? (size_t)t : (size_t)t * 4);
             const size_t grow = coarse ? (size_t)nwt : (size_t)nwt * 4;
             const uint32_t four = lane >> 2;                   // my 64-byte line inside a chunk
@@ -124,9 +124,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
                 const uint32_t tau = desc[i].tau, cut = desc[i].cutoff;
                 uint32_t mask = 0xfu;                          // bit u: my line of chunk u holds a candidate
                 if (!desc[i].dense && coarse) {
-                    const uint64_t w = gw[(size_t)i * grow] >> four;
-                    mask = (uint32_t)(w & 1) | (uint32_t)((w >> 16) & 1) << 1 | (uint32_t)((w >> 32) & 1) << 2 |
-                           (uint32_t)((w >> 48) & 1) << 3;
+                    mask = (uint32_t)(gw[(size_t)i * grow] >> (4 * four)) & 0xfu;   // bit 4 * line + chunk
                 } else if (!desc[i].dense) {
                     const uint64_t* __restrict__ w = gw + (size_t)i * grow;
                     mask = (uint32_t)((w[0] >> lane) & 1) | (uint32_t)((w[1] >> lane) & 1) << 1 |

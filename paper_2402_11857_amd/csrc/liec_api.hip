@@ -284,7 +284,7 @@ void launch_select(Launcher& L, const float* src, size_t row_stride, uint32_t ro
     hipStream_t st = c->stream;
     const dim3 grid(blocks, rows), cold_grid(cold_blocks, rows);
     // random-k with a thin band: clear the kept bitmap, then walk the priorities above the band
-    // few, long-lived blocks (every wave ends with a list flush): one per 32768 words to invert
+    // few, long-lived blocks (every block ends with an atomic on the row's counters): one per 32768 words to invert
     const uint64_t inv_words = 2ull * (0x80000000ull - rk.fix_lo);
     const dim3 inv_grid((uint32_t)std::min<uint64_t>(std::max<uint64_t>(inv_words / 32768, 128), 1024), rows);
     const dim3 zero_grid(std::min<uint32_t>((c->nwt * 32 + kBlock - 1) / kBlock, 4096u), rows);
@@ -528,7 +528,7 @@ liec_status liec_create_ex(liec_ctx** out, int32_t N, int64_t d, liec_comp worke
     };
     // the scaled-sign pass streams best as one 4096-column iteration per block
     c->row_blocks = balanced(1u << 20);
-    // the filter pays one list flush (a global atomic) per wave: about 1024 long-lived blocks per row
+    // the filter pays one atomic on the row's counters per block: about 1024 long-lived blocks per row
     // (more when there are too few rows to fill the chip)
     // A wave of the filter takes 4 consecutive wave tiles at a time on long rows (a block then covers 16, and the
     // group words it writes fill whole 128-byte lines of the bitmap: measured 2 % faster than 1 on rows of 25M
