@@ -61,6 +61,18 @@ liec_status liec_set_search_wait(liec_ctx *ctx, int32_t polls);
 liec_status liec_set_group_bitmap(liec_ctx *ctx, int32_t per_line);
 
 /*
+ * Testing and tuning aid for top-k workers: how the aggregation (Algorithm 1,
+ * v = e + mean p^i) fetches the rows' candidates -- 0: row after row, 1: the
+ * candidates of 8 rows requested together, then added in worker order.
+ * liec_create* picks the second for rows under 2^23 columns, where the kernel is
+ * bound by the latency of its dependent loads and it measured a third faster (it
+ * is a fifth to a half slower on the long rows of the DNN-shaped workloads);
+ * results do not depend on it.  Takes effect with the next step.  LIEC_EINVAL for
+ * another value or when the workers' operator is not top-k.
+ */
+liec_status liec_set_gather_batching(liec_ctx *ctx, int32_t on);
+
+/*
  * Per-kernel timing with HIP events on the context's stream, for measurement.
  * liec_profile_begin(ctx, max_steps, update_only) makes every following
  * liec_step record an event before and after each kernel it launches, or, with

@@ -107,6 +107,8 @@ def lib():
         L.liec_get_search_state.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_uint32)]
         L.liec_set_group_bitmap.restype = ctypes.c_int
         L.liec_set_group_bitmap.argtypes = [vp, i32]
+        L.liec_set_gather_batching.restype = ctypes.c_int
+        L.liec_set_gather_batching.argtypes = [vp, i32]
         L.liec_get_info.restype = ctypes.c_int
         L.liec_get_info.argtypes = [vp, ctypes.POINTER(LiecInfo)]
         L.liec_get_worker_desc.restype = ctypes.c_int
@@ -337,6 +339,9 @@ class LiecContext:
 
     def set_group_bitmap(self, per_line: int) -> None:
         _check(lib().liec_set_group_bitmap(self._h, per_line), "liec_set_group_bitmap")
+
+    def set_gather_batching(self, on: int) -> None:
+        _check(lib().liec_set_gather_batching(self._h, on), "liec_set_gather_batching")
 
     def info(self) -> LiecInfo:
         return liec_get_info(self._h)[0]

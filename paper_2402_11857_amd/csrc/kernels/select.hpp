@@ -548,6 +548,28 @@ __device__ __forceinline__ void for_each_listed(const uint2* __restrict__ in, ui
 // by a three-digit radix select over those indices.  Then the row's counters and histogram are cleared, the
 // next step's band is predicted and the row is back in kWarm mode.  Rows whose list does not hold rank k
 // (overflow, a bin larger than the list, rank outside the band) are put into kSlow mode.
+// The same for a list of at most 16 * kSelectBlock entries that the block holds in registers (loaded once by
+// hold_listed, walked by every pass of the select instead of going back to memory).
+constexpr uint32_t kHeldMax = 16u * kSelectBlock;
+__device__ __forceinline__ void hold_listed(const uint2* __restrict__ in, uint32_t n, uint4 (&a)[8]) {
+    const uint4* __restrict__ in2 = reinterpret_cast<const uint4*>(in);
+    const uint32_t npairs = (n + 1) / 2;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const uint32_t e = q * kSelectBlock + threadIdx.x;
+        a[q] = e < npairs ? in2[e] : make_uint4(0u, 0u, 0u, 0u);
+    }
+}
+template <typename F>
+__device__ __forceinline__ void for_each_held(const uint4 (&a)[8], uint32_t n, F fn) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const uint32_t e = 2 * (q * kSelectBlock + threadIdx.x);
+        fn(make_uint2(a[q].x, a[q].y), e < n);
+        fn(make_uint2(a[q].z, a[q].w), e + 1 < n);
+    }
+}
+
 __global__ __launch_bounds__(kSelectBlock) void k_list_select(uint32_t row0, RowDesc* __restrict__ desc,
                                                                uint32_t* __restrict__ ghist,
                                                                const uint2* __restrict__ list, uint32_t cap,
@@ -602,17 +624,26 @@ __global__ __launch_bounds__(kSelectBlock) void k_list_select(uint32_t row0, Row
         return;
     }
     const uint32_t n_all = n;
+    if (!direct && ph.count <= (uint32_t)kShortCap && desc[row].n_short == ph.count) {
+        in = shortl + (size_t)row * kShortCap;                  // the bin's entries, collected by the second filter pass
+        n = ph.count;
+    }
+    // a list of up to kHeldMax entries is read once and kept in registers for all the passes below
+    const bool held = n <= kHeldMax;                            // uniform for the block
+    uint4 own[8];
+    if (held) hold_listed(in, n, own);
+    auto walk = [&](auto fn) {
+        if (held) for_each_held(own, n, fn);
+        else for_each_listed(in, n, fn);
+    };
     if (direct) {
         // first digit of every listed key, in LDS
         const uint32_t nbins = max(256u, 1u << (band_bits(hi - lo) - shift));
         for (uint32_t b = tid; b < nbins; b += kSelectBlock) h[b] = 0;
         __syncthreads();
-        for_each_listed(in, n, [&](uint2 kv, bool valid) { wave_count(h, valid, (kv.x - lo) >> shift, lane); });
+        walk([&](uint2 kv, bool valid) { wave_count(h, valid, (kv.x - lo) >> shift, lane); });
         __syncthreads();
         ph = block_pick(h, (int)nbins, k - n_sure, part, res);
-    } else if (ph.count <= (uint32_t)kShortCap && desc[row].n_short == ph.count) {
-        in = shortl + (size_t)row * kShortCap;                  // the bin's entries, collected by the second filter pass
-        n = ph.count;
     }
     // the following digits, over the entries that carry the digits found so far
     uint32_t prefix = ph.bin, want = ph.rank_in, ties = ph.count;
@@ -622,7 +653,7 @@ __global__ __launch_bounds__(kSelectBlock) void k_list_select(uint32_t row0, Row
         const uint32_t nbins = max(256u, 1u << bits), mask = (1u << bits) - 1u;
         for (uint32_t b = tid; b < nbins; b += kSelectBlock) h[b] = 0;
         __syncthreads();
-        for_each_listed(in, n, [&](uint2 kv, bool valid) {
+        walk([&](uint2 kv, bool valid) {
             const uint32_t rel = kv.x - lo;
             wave_count(h, valid && (rel >> shift) == prefix, (rel >> below) & mask, lane);
         });
@@ -640,7 +671,7 @@ __global__ __launch_bounds__(kSelectBlock) void k_list_select(uint32_t row0, Row
             s_cut = 0xffffffffu;
         }
         __syncthreads();
-        for_each_listed(in, n, [&](uint2 kv, bool valid) {
+        walk([&](uint2 kv, bool valid) {
             if (valid && kv.x == tau) {
                 const uint32_t pos = atomicAdd(&s_nties, 1u);
                 if (pos < (uint32_t)kTieCap) h[pos] = kv.y;
@@ -665,7 +696,7 @@ __global__ __launch_bounds__(kSelectBlock) void k_list_select(uint32_t row0, Row
             const int nbins = pass == 0 ? 2048 : 1024;
             for (int b = tid; b < nbins; b += kSelectBlock) h[b] = 0;
             __syncthreads();
-            for_each_listed(in, n, [&](uint2 kv, bool valid) {
+            walk([&](uint2 kv, bool valid) {
                 const uint32_t inv = 0x7fffffffu - kv.y;
                 wave_count(h, valid && kv.x == tau && (inv >> above) == prefix, (inv >> shift) & (uint32_t)(nbins - 1), lane);
             });

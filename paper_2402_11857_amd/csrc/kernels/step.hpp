@@ -50,7 +50,7 @@ __device__ __forceinline__ float message_of(float g, uint32_t j, float scale, ui
 // With `vbits` the kernel also leaves the sign bits of v (lane-major half-words like the workers' sign
 // bits) for the update kernel of a scaled-sign server.
 // ---------------------------------------------------------------------------------------------
-template <int WC, bool SRV_L1, bool VEC>
+template <int WC, bool SRV_L1, bool VEC, bool BATCH = false>
 __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ grads, const uint16_t* __restrict__ bits,
                                                        const uint64_t* __restrict__ gbits,
                                                        int N, uint32_t d, uint32_t nwt, float inv_n,
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
                                                        float* __restrict__ v_out, double* __restrict__ srv_partial,
                                                        BlockTable bt, bool coarse, uint16_t* __restrict__ vbits) {
     __shared__ double lds_w[4];
-    __shared__ float accs[(WC == kTopk || WC == kRandk) ? 16 * kBlock : 1];
+    __shared__ float accs[((WC == kTopk && !BATCH) || WC == kRandk) ? 16 * kBlock : 1];
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     double l1 = 0.0;
     for (uint32_t t = blockIdx.x * 4 + wave; t < nwt; t += gridDim.x * 4) {
@@ -111,6 +111,59 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
                     }
                 }
             }
+        } else if (WC == kTopk && BATCH) {
+            // Short rows: the kernel is bound by the latency of its dependent loads (group word, then gather, row
+            // after row), not by bytes.  So the group words of 8 rows are requested together, then, chunk by
+            // chunk, the flagged groups of those 8 rows, and only then are they added, in worker order.
+            const uint64_t* __restrict__ gw = gbits + (coarse ? (size_t)t : (size_t)t * 4);
+            const size_t grow = coarse ? (size_t)nwt : (size_t)nwt * 4;
+            const uint32_t four = lane >> 2;
+            for (int i0 = 0; i0 < N; i0 += 8) {
+                uint32_t mask[8], tau[8], cut[8];
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    const int i = i0 + r;
+                    mask[r] = 0;
+                    tau[r] = 0;
+                    cut[r] = 0;
+                    if (i < N) {                                // uniform
+                        tau[r] = desc[i].tau;
+                        cut[r] = desc[i].cutoff;
+                        if (desc[i].dense) {
+                            mask[r] = 0xfu;
+                        } else if (coarse) {
+                            mask[r] = (uint32_t)(gw[(size_t)i * grow] >> (4 * four)) & 0xfu;
+                        } else {
+                            const uint64_t* __restrict__ w = gw + (size_t)i * grow;
+                            mask[r] = (uint32_t)((w[0] >> lane) & 1) | (uint32_t)((w[1] >> lane) & 1) << 1 |
+                                      (uint32_t)((w[2] >> lane) & 1) << 2 | (uint32_t)((w[3] >> lane) & 1) << 3;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t j = j0 + u * kChunk;
+                    float4 gq[8];
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) {
+                        gq[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if ((mask[r] >> u) & 1u) gq[r] = ld4<VEC>(grads + (size_t)(i0 + r) * d, j, d);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) {
+                        if ((mask[r] >> u) & 1u) {
+                            const float gv[4] = {gq[r].x, gq[r].y, gq[r].z, gq[r].w};
+                            float* av[4] = {&acc[u].x, &acc[u].y, &acc[u].z, &acc[u].w};
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const uint32_t key = key_of(gv[q]);
+                                if (j + q < d && (key > tau[r] || (key == tau[r] && j + q <= cut[r])))
+                                    *av[q] = __fadd_rn(*av[q], gv[q]);
+                            }
+                        }
+                    }
+                }
+            }
         } else if (WC == kTopk) {
             float* my = accs + threadIdx.x;                    // slot b of this lane: my[b * kBlock]
 #pragma unroll
@@ -134,11 +187,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(const float* __restrict__ 
                     const int u = __builtin_ctz(mask);
                     mask &= mask - 1;
                     const uint32_t j = j0 + u * kChunk;
-#ifdef LIEC_AGG_NT_GATHER
-                    const float4 g = ld4<VEC, true>(gi, j, d);
-#else
                     const float4 g = ld4<VEC>(gi, j, d);
-#endif
                     const float gv[4] = {g.x, g.y, g.z, g.w};
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {

@@ -48,6 +48,7 @@ def test_random_shapes_and_operator_pairs(case):
         ctx.set_random(case, 5)
         if wc == "topk":
             ctx.set_group_bitmap((case // 5) & 1)    # both forms of the candidate bitmap
+            ctx.set_gather_batching((case // 10) & 1)   # both ways the aggregation fetches the candidates
         if "blocksign" in (wc, sc):
             ctx.set_blocks(off)
         for t in range(3):
@@ -112,6 +113,7 @@ def _random_chain(case, degenerate):
             ctx.set_search_wait(wait)
         if wc == "topk":
             ctx.set_group_bitmap(case & 1)           # both forms of the candidate bitmap
+            ctx.set_gather_batching((case >> 1) & 1)    # both ways the aggregation fetches the candidates
         if "blocksign" in (wc, sc):
             ctx.set_blocks(off)
         for t in range(steps):

@@ -9,7 +9,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADERS = [os.path.join(ROOT, "include", n) for n in ("liec.h", "liec_testing.h")]
-AIDS = ("liec_force_search_mode", "liec_get_search_state", "liec_set_search_wait", "liec_set_group_bitmap", "liec_profile_begin",
+AIDS = ("liec_force_search_mode", "liec_get_search_state", "liec_set_search_wait", "liec_set_group_bitmap", "liec_set_gather_batching", "liec_profile_begin",
         "liec_profile_end", "liec_device_copy")
 
 
@@ -85,6 +85,7 @@ def test_null_handles_are_rejected_or_ignored(lib):
     assert lib.liec_set_search_wait(None, 0) == 1
     assert lib.liec_get_search_state(None, 0, None) == 1
     assert lib.liec_set_group_bitmap(None, 0) == 1
+    assert lib.liec_set_gather_batching(None, 0) == 1
     assert lib.liec_l2_norm(None, None, 1, None) == 1
     assert lib.liec_iteration(None, 0, 4, None, None, None) == 1
     assert lib.liec_iteration(None, 0, 1, None, None, None) == 1      # a period of 1 would never compress
