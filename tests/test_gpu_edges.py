@@ -449,6 +449,38 @@ def test_predicted_band_narrows_while_the_predictions_hold_and_reopens_after_a_m
     assert min(listed[2:20]) < listed[1] // 2, f"fewer candidates are listed once the band has narrowed: {listed}"
 
 
+def test_more_candidates_in_one_block_than_its_stage_holds():
+    """A stretch of 6000 neighbouring columns whose magnitudes lie within 0.02 % of the threshold: the filter
+    blocks that cover it find far more candidates than their 2048-entry LDS stage holds, in the pass over the
+    first-digit band of the first step and, once the band is predicted, in the pass over the predicted band,
+    so the entries beyond the stage go to list slots reserved one wave at a time.  Checked against the oracle
+    every step; the predictions must hold and the lists must contain the whole stretch."""
+    import oracle
+    from paper_2402_11857_amd import LiecContext
+
+    N, d, k = 2, 150_000, 4000
+    say(f"case stage overflow N={N} d={d} k={k}")
+    rng = np.random.default_rng(77)
+    x = torch.zeros((N, d), dtype=torch.float32, device=DEV)
+    e = torch.zeros(d, dtype=torch.float32, device=DEV)
+    xo, eo = np.zeros((N, d), dtype=np.float32), np.zeros(d, dtype=np.float32)
+    with LiecContext(N, d, "topk", "sign", k, 0, 0.05) as ctx:
+        for t in range(5):
+            gh = (rng.standard_normal((N, d)) * 1e-3).astype(np.float32)
+            gh[:, 100:1100] = np.where(rng.random((N, 1000)) < 0.5, -8.0, 8.0) * (1 + rng.random((N, 1000)))   # 1000 above
+            near = 1.0 + 2e-4 * rng.random((N, 6000))                                                      # rank k falls in here
+            gh[:, 20_000:26_000] = (np.where(rng.random((N, 6000)) < 0.5, -1.0, 1.0) * near).astype(np.float32)
+            g = torch.from_numpy(gh).to(DEV)
+            ctx.step(g, x, e)
+            oracle.step(gh, xo, eo, "topk", "sign", 0.05, k, 0)
+            assert H.bit_equal(e.cpu().numpy(), eo) and H.bit_equal(x.cpu().numpy(), xo), f"step {t}"
+            for row in range(N):
+                st = ctx.search_state(row)
+                assert st["mode"] == 0 and st["general_search"] == 0
+                assert st["listed"] >= 6000, f"step {t} row {row}: the stretch must be listed: {st}"
+        assert ctx.info().band_misses == 0, "the threshold does not move: no prediction may fail"
+
+
 @pytest.mark.parametrize("frac,sc", [(0.10, "topk"), (0.5, "sign"), (0.006, "topk")])
 def test_long_candidate_lists_take_the_shared_passes(frac, sc):
     """Large k and the wide band of the first predicted steps give candidate lists far beyond what one block
