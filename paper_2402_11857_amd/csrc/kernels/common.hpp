@@ -22,7 +22,8 @@ constexpr int kColTile = 1024;          // columns per block of the update kerne
 constexpr int kHistBins = 4096;         // first radix digit of a whole row (12 bits)
 constexpr int kListBits = 13;           // widest radix digit of the list select (two digits cover a band of 2^26 keys)
 constexpr int kListBins = 1 << kListBits;
-constexpr int kStage = 2048;            // LDS staging slots of a block of the candidate filter
+constexpr int kStage = 1024;            // LDS staging slots of a block of the candidate filter
+constexpr int kWaveStage = 256;         // and of each of its waves once the block's are used up (a chunk lists at most 256)
 constexpr int kDirectList = 16384;      // candidate lists up to this length are selected by one block on its own
 constexpr int kShortCap = 4096;         // entries of the first list digit's bin that are handed to the list select on their own
 constexpr int kTieCap = 4096;           // ties at the threshold the fast path resolves

@@ -181,57 +181,82 @@ __device__ __forceinline__ bool filter_band(RowDesc* __restrict__ desc, uint32_t
 // blocks a row while the counters shared a line with the fields every block reads when it starts.  So the
 // block's waves append their candidates to one stage in LDS (an LDS counter hands out the positions), and when
 // the block is done a single 64-bit atomic adds its keys above the band to the high half of the row's counter
-// word and reserves, in the low half, the list slots of what was staged.  Entries beyond the stage (kStage per
-// block: wide bands, constant rows) go straight to list slots that the wave reserves with an atomic of its own.
+// word and reserves, in the low half, the list slots of what was staged.  Once that stage (kStage entries) is
+// full -- wide bands, candidates crowded into one stretch of the row -- every wave goes on into a small stage
+// of its own (kWaveStage entries) that it empties into list slots reserved with an atomic of its own.
 struct StagePos {
     uint32_t pos;                                // block position of the wave's first entry
-    uint32_t first_spill;                        // first of its positions beyond the stage
-    uint32_t spill_base;                         // the list slot reserved for that entry
+    uint32_t first_spill;                        // first of its positions beyond the block's stage
+    uint32_t wbase;                              // slot of that entry in the wave's own stage
+    bool drop;                                   // the list is full: nothing is kept any more
 };
-// The wave has m entries to append (wave-uniform, every lane calls).
-__device__ __forceinline__ StagePos reserve_stage(const FilterBand& fb, uint32_t m, uint32_t* staged_n, uint32_t lane) {
+// Empties the wave's own stage into the list.  staged[1] is set once a reservation of this block has gone past
+// the list's capacity: the row's count then stays above the capacity, which is all that anyone reads from an
+// overflowed list, and the block stops listing and counting candidates.
+__device__ __forceinline__ void flush_wave_stage(const FilterBand& fb, const uint2* wst, uint32_t cnt, uint32_t* staged,
+                                                 uint32_t lane) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    uint32_t base = 0;
+    if (lane == 0) {
+        base = (uint32_t)atomicAdd(fb.counts, (unsigned long long)cnt);
+        if ((uint64_t)base + cnt > fb.cap) staged[1] = 1;
+    }
+    base = __builtin_amdgcn_readfirstlane(base);
+    for (uint32_t s = lane; s < cnt; s += 64)
+        if (base + s < fb.cap) fb.out[base + s] = wst[s];
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+// The wave has m <= kWaveStage entries to append (wave-uniform, every lane calls).  staged[0]: the block's LDS
+// counter of stage positions handed out; wst / wcnt: the wave's own stage and how many entries it holds.
+__device__ __forceinline__ StagePos reserve_stage(const FilterBand& fb, uint32_t m, uint32_t* staged, const uint2* wst,
+                                                  uint32_t& wcnt, uint32_t lane) {
     StagePos sp;
+    sp.pos = sp.first_spill = sp.wbase = 0;
+    sp.drop = *reinterpret_cast<volatile uint32_t*>(&staged[1]) != 0;   // uniform
+    if (sp.drop) return sp;
     uint32_t pos = 0;
-    if (lane == 0) pos = atomicAdd(staged_n, m);                // LDS
+    if (lane == 0) pos = atomicAdd(&staged[0], m);              // LDS
     sp.pos = __builtin_amdgcn_readfirstlane(pos);
     sp.first_spill = max(sp.pos, (uint32_t)kStage);
-    sp.spill_base = 0;
     if (sp.pos + m > (uint32_t)kStage) {                        // uniform
-        uint32_t at = 0;
-        if (lane == 0) at = (uint32_t)atomicAdd(fb.counts, (unsigned long long)(sp.pos + m - sp.first_spill));
-        sp.spill_base = __builtin_amdgcn_readfirstlane(at);
+        const uint32_t nsp = sp.pos + m - sp.first_spill;
+        if (wcnt + nsp > (uint32_t)kWaveStage) {
+            flush_wave_stage(fb, wst, wcnt, staged, lane);
+            wcnt = 0;
+        }
+        sp.wbase = wcnt;
+        wcnt += nsp;
     }
     return sp;
 }
 // Entry number `ord` of those m (any subset of lanes).
-__device__ __forceinline__ void put_candidate(const FilterBand& fb, uint2* stage, const StagePos& sp, uint32_t ord, uint2 entry) {
+__device__ __forceinline__ void put_candidate(uint2* stage, uint2* wst, const StagePos& sp, uint32_t ord, uint2 entry) {
+    if (sp.drop) return;
     const uint32_t p = sp.pos + ord;
-    if (p < (uint32_t)kStage) {
-        stage[p] = entry;
-    } else {
-        const uint32_t at = sp.spill_base + (p - sp.first_spill);
-        if (at < fb.cap) fb.out[at] = entry;
-    }
+    if (p < (uint32_t)kStage) stage[p] = entry;
+    else wst[sp.wbase + (p - sp.first_spill)] = entry;
 }
 
-// End of a filter block.  n_hi: keys above the band, per lane.  Every thread of the block calls it.
-__device__ __forceinline__ void finish_filter_block(const FilterBand& fb, const uint2* stage, uint32_t n_hi,
-                                                    const uint32_t* staged_n, uint32_t* wsure /* 5 words */) {
+// End of a filter block.  n_hi: keys above the band, per lane; wst / wcnt: the wave's own stage.  Every thread of
+// the block calls it.
+__device__ __forceinline__ void finish_filter_block(const FilterBand& fb, const uint2* stage, const uint2* wst, uint32_t wcnt,
+                                                    uint32_t n_hi, uint32_t* staged, uint32_t* wsure /* 5 words */) {
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) n_hi += __shfl_down(n_hi, o, 64);
     if (lane == 0) wsure[wave] = n_hi;
+    if (wcnt) flush_wave_stage(fb, wst, wcnt, staged, lane);    // wave-uniform
     __syncthreads();
-    const uint32_t staged = min(*staged_n, (uint32_t)kStage);
+    const uint32_t n_staged = min(staged[0], (uint32_t)kStage);
     if (threadIdx.x == 0) {
         const uint32_t sure = wsure[0] + wsure[1] + wsure[2] + wsure[3];
         uint32_t base = 0;
-        if (sure | staged) base = (uint32_t)atomicAdd(fb.counts, ((unsigned long long)sure << 32) | staged);
+        if (sure | n_staged) base = (uint32_t)atomicAdd(fb.counts, ((unsigned long long)sure << 32) | n_staged);
         wsure[4] = base;
     }
     __syncthreads();
     const uint32_t base = wsure[4];
-    for (uint32_t s = threadIdx.x; s < staged; s += kBlock)
+    for (uint32_t s = threadIdx.x; s < n_staged; s += kBlock)
         if (base + s < fb.cap) fb.out[base + s] = stage[s];
 }
 
@@ -245,8 +270,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
                                                     uint64_t* __restrict__ gbits,
                                                     uint16_t* __restrict__ kbits, uint2* __restrict__ list, uint32_t cap,
                                                     uint2* __restrict__ shortl, RkDraw rk, bool coarse, uint32_t run) {
-    __shared__ uint2 stage[kStage];
-    __shared__ uint32_t wsure[5], staged_n;
+    __shared__ uint2 stage[kStage], wstage[4][kWaveStage];
+    __shared__ uint32_t wsure[5], staged[2];
     __shared__ uint32_t part[256], res[3];
     const uint32_t row = row0 + blockIdx.y;
     if (cold_pass && desc[row].mode == kWarm && !wants_cold(desc[row], cap, k)) {   // uniform for the block
@@ -256,7 +281,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
     }
     FilterBand fb;
     if (!filter_band(desc, row, cold_pass, ghist, list, cap, k, part, res, fb)) return;   // uniform for the block
-    if (threadIdx.x == 0) staged_n = 0;
+    if (threadIdx.x < 2) staged[threadIdx.x] = 0;
     __syncthreads();
     const uint32_t lo = fb.lo, hi = fb.hi;
     const float* __restrict__ g = src + (size_t)blockIdx.y * row_stride;
@@ -268,6 +293,8 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
         k1 = (uint32_t)(stream >> 32);
     }
     uint32_t n_hi = 0, kmax = 0;                                // per lane: keys >= hi seen, largest key seen
+    uint2* wst = wstage[wave];                                  // the wave's own stage and its fill (wave-uniform)
+    uint32_t wcnt = 0;
     // the body for one wave tile; FULL (every column of the tile is below d) drops the bounds checks
     uint64_t pend = 0;                                          // group words of the run so far: coarse, lane i holds tile i's;
                                                                 // fine, lane 4i + u holds word u of tile i
@@ -312,11 +339,11 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
             const uint64_t any_cand = bc[0] | bc[1] | bc[2] | bc[3];
             if (any_cand) {                                     // wave-uniform
                 const uint32_t m = __popcll(bc[0]) + __popcll(bc[1]) + __popcll(bc[2]) + __popcll(bc[3]);
-                const StagePos sp = reserve_stage(fb, m, &staged_n, lane);
+                const StagePos sp = reserve_stage(fb, m, staged, wst, wcnt, lane);
                 uint32_t off = 0;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    if ((bc[q] >> lane) & 1) put_candidate(fb, stage, sp, off + lanes_below(bc[q]), make_uint2(keys[q], j + q));
+                    if ((bc[q] >> lane) & 1) put_candidate(stage, wst, sp, off + lanes_below(bc[q]), make_uint2(keys[q], j + q));
                     off += __popcll(bc[q]);
                 }
             }
@@ -344,7 +371,7 @@ __global__ __launch_bounds__(kBlock) void k_filter(const float* __restrict__ src
     }
     // keys at or above 0x7f800000 are Inf / NaN (magnitude keys only: priorities use the whole range)
     if (!RK && __ballot(kmax >= 0x7f800000u) && lane == 0) atomicOr(&desc[row].nonfinite_acc, 1u);
-    finish_filter_block(fb, stage, n_hi, &staged_n, wsure);
+    finish_filter_block(fb, stage, wst, wcnt, n_hi, staged, wsure);
 }
 
 // Random-k when the band is thin against the row (k * 2^32 / d well below d): instead of computing the
@@ -368,8 +395,8 @@ __global__ __launch_bounds__(kBlock) void k_rk_filter_inverse(uint32_t d, uint32
                                                                const uint32_t* __restrict__ ghist, uint32_t k,
                                                                uint16_t* __restrict__ kbits, uint2* __restrict__ list,
                                                                uint32_t cap, uint2* __restrict__ shortl, RkDraw rk) {
-    __shared__ uint2 stage[kStage];
-    __shared__ uint32_t wsure[5], staged_n;
+    __shared__ uint2 stage[kStage], wstage[4][kWaveStage];
+    __shared__ uint32_t wsure[5], staged[2];
     __shared__ uint32_t part[256], res[3];
     const uint32_t row = row0 + blockIdx.y;
     if (cold_pass && desc[row].mode == kWarm && !wants_cold(desc[row], cap, k)) {   // uniform for the block
@@ -379,7 +406,7 @@ __global__ __launch_bounds__(kBlock) void k_rk_filter_inverse(uint32_t d, uint32
     }
     FilterBand fb;
     if (!filter_band(desc, row, cold_pass, ghist, list, cap, k, part, res, fb)) return;   // uniform for the block
-    if (threadIdx.x == 0) staged_n = 0;
+    if (threadIdx.x < 2) staged[threadIdx.x] = 0;
     __syncthreads();
     const uint32_t lo = fb.lo, hi = fb.hi;
     uint32_t* __restrict__ words = reinterpret_cast<uint32_t*>(kbits + (size_t)row * nwt * 64);
@@ -388,6 +415,8 @@ __global__ __launch_bounds__(kBlock) void k_rk_filter_inverse(uint32_t d, uint32
     const uint32_t k0 = (uint32_t)stream, k1 = (uint32_t)(stream >> 32);
     const uint64_t y_begin = 2ull * lo, y_end = 1ull << 32;    // words whose priority is at least lo
     uint32_t n_hi = 0;
+    uint2* wst = wstage[wave];
+    uint32_t wcnt = 0;
     for (uint64_t base = y_begin + ((uint64_t)blockIdx.x * 4 + wave) * 64; base < y_end; base += (uint64_t)gridDim.x * kBlock) {
         const uint64_t y64 = base + lane;
         const uint32_t y = (uint32_t)y64, key = y >> 1;
@@ -403,11 +432,11 @@ __global__ __launch_bounds__(kBlock) void k_rk_filter_inverse(uint32_t d, uint32
         const uint64_t bc = __ballot(ok && !ge_hi);             // candidates: lo <= key < hi
         if (bc) {                                               // wave-uniform
             const uint32_t m = __popcll(bc);
-            const StagePos sp = reserve_stage(fb, m, &staged_n, lane);
-            if ((bc >> lane) & 1) put_candidate(fb, stage, sp, lanes_below(bc), make_uint2(key, j));
+            const StagePos sp = reserve_stage(fb, m, staged, wst, wcnt, lane);
+            if ((bc >> lane) & 1) put_candidate(stage, wst, sp, lanes_below(bc), make_uint2(key, j));
         }
     }
-    finish_filter_block(fb, stage, n_hi, &staged_n, wsure);
+    finish_filter_block(fb, stage, wst, wcnt, n_hi, staged, wsure);
 }
 
 // First radix digit (12 bits) of every key of the rows that have no usable band; for the rows whose

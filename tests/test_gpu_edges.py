@@ -451,9 +451,9 @@ def test_predicted_band_narrows_while_the_predictions_hold_and_reopens_after_a_m
 
 def test_more_candidates_in_one_block_than_its_stage_holds():
     """A stretch of 6000 neighbouring columns whose magnitudes lie within 0.02 % of the threshold: the filter
-    blocks that cover it find far more candidates than their 2048-entry LDS stage holds, in the pass over the
+    blocks that cover it find four times as many candidates as their LDS stage holds, in the pass over the
     first-digit band of the first step and, once the band is predicted, in the pass over the predicted band,
-    so the entries beyond the stage go to list slots reserved one wave at a time.  Checked against the oracle
+    so the entries beyond the stage go through the waves' own stages to list slots reserved a batch at a time.  Checked against the oracle
     every step; the predictions must hold and the lists must contain the whole stretch."""
     import oracle
     from paper_2402_11857_amd import LiecContext
