@@ -298,7 +298,9 @@ void launch_select(Launcher& L, const float* src, size_t row_stride, uint32_t ro
         }
         L.begin(slot0 + (cold_pass ? 2 : 0));
         if (RK && rk_inverse) {
-            k_rk_zero<<<zero_grid, kBlock, 0, st>>>(c->nwt, row0, c->desc, cold_pass, c->cap, k, c->bits);
+            // (the second pass is rare: a small grid, so that its blocks' returning at once costs little)
+            const dim3 zg(cold_pass ? std::min(zero_grid.x, 256u) : zero_grid.x, rows);
+            k_rk_zero<<<zg, kBlock, 0, st>>>(c->nwt, row0, c->desc, cold_pass, c->cap, k, c->bits);
             k_rk_filter_inverse<<<inv_grid, kBlock, 0, st>>>(d, c->nwt, row0, c->desc, cold_pass, c->ghist, k, c->bits,
                                                              c->list, c->cap, c->shortl, rk);
         } else {
