@@ -244,19 +244,21 @@ __device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* lds_wave
 // Walks a histogram of nbins (a power of two from 256 to 8192) counts from the top bin down to the bin that
 // holds the entry of rank `rank` (1-based, largest first).  Needs blockDim.x >= 256; every thread
 // of the block must call it.  part: 256 words of LDS, res: 3 words of LDS.
+// Thread t < 256 adds up the nbins / 256 consecutive bins t * per .. t * per + per - 1, starting at a bin of its
+// own ((q + t) mod per: neighbouring threads then read different LDS banks -- read in the same order, the 32
+// bins per thread of an 8192-bin histogram all fell on one bank and the pick took 4 us); a suffix sum over the
+// threads finds the one whose bins hold the rank, and one wave walks that thread's bins.
 struct Pick {
     uint32_t bin, rank_in, count;
 };
 __device__ __forceinline__ Pick block_pick(const uint32_t* __restrict__ h, int nbins, uint32_t rank,
                                            uint32_t* part, uint32_t* res) {
-    const int per = nbins >> 8;   // 1 .. 32 bins per thread
+    const int per = nbins >> 8;   // 1 .. 32 bins per thread, a power of two
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    uint32_t local[32];
     uint32_t sum = 0;
-#pragma unroll
-    for (int q = 0; q < 32; ++q) {
-        local[q] = (tid < 256 && q < per) ? h[tid * per + q] : 0u;
-        sum += local[q];
+    if (tid < 256) {
+#pragma unroll 8
+        for (int q = 0; q < per; ++q) sum += h[tid * per + ((q + tid) & (per - 1))];
     }
     // count in the bins above this thread's range: suffix sum over the 256 threads (lanes, then waves)
     uint32_t incl = sum;
@@ -267,6 +269,7 @@ __device__ __forceinline__ Pick block_pick(const uint32_t* __restrict__ h, int n
     }
     if (tid < 256 && lane == 0) part[wave] = incl;             // total of wave `wave`
     if (tid == 0) {
+        part[8] = 0xffffffffu;                                  // the thread whose bins hold the rank: none yet
         res[0] = 0;
         res[1] = 1;
         res[2] = 0;
@@ -275,23 +278,28 @@ __device__ __forceinline__ Pick block_pick(const uint32_t* __restrict__ h, int n
     if (tid < 256) {
         uint32_t above = incl - sum;
         for (uint32_t w = wave + 1; w < 4; ++w) above += part[w];
-        if (above < rank && rank <= above + sum) {   // true for exactly one thread
-            uint32_t run = above, bin = tid * per, cnt = local[0];
-            bool done = false;
+        if (above < rank && rank <= above + sum) {   // true for at most one thread
+            part[8] = tid;
+            part[9] = above;
+        }
+    }
+    __syncthreads();
+    const uint32_t owner = part[8];
+    if (owner != 0xffffffffu && tid < 64) {                     // wave 0 walks the owner's bins from the top
+        const uint32_t above = part[9];
+        const uint32_t c = (int)lane < per ? h[owner * per + lane] : 0u;
+        uint32_t suf = c;                                       // sum over the lanes at and above mine
 #pragma unroll
-            for (int q = 31; q >= 0; --q) {
-                if (q < per) {
-                    if (!done && run + local[q] >= rank) {
-                        bin = tid * per + q;
-                        cnt = local[q];
-                        done = true;
-                    }
-                    if (!done) run += local[q];
-                }
-            }
-            res[0] = bin;
-            res[1] = rank - run;
-            res[2] = cnt;
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t up = __shfl_down(suf, o, 64);
+            if (lane + o < 64) suf += up;
+        }
+        const uint64_t reach = __ballot((int)lane < per && above + suf >= rank);    // lane 0 always does
+        const uint32_t top = 63u - (uint32_t)__clzll((long long)reach);
+        if (lane == top) {
+            res[0] = owner * per + lane;
+            res[1] = rank - (above + suf - c);
+            res[2] = c;
         }
     }
     __syncthreads();

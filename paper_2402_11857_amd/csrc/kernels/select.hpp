@@ -593,6 +593,7 @@ template <typename F>
 __device__ __forceinline__ void for_each_held(const uint4 (&a)[8], uint32_t n, F fn) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
+        if (2u * q * kSelectBlock >= n) break;                  // uniform for the block: nothing held from here on
         const uint32_t e = 2 * (q * kSelectBlock + threadIdx.x);
         fn(make_uint2(a[q].x, a[q].y), e < n);
         fn(make_uint2(a[q].z, a[q].w), e + 1 < n);
@@ -609,12 +610,17 @@ __global__ __launch_bounds__(kSelectBlock) void k_list_select(uint32_t row0, Row
     __shared__ uint32_t part[256], res[3];
     __shared__ uint32_t s_cut, s_nties;
     static_assert(kTieCap <= kListBins, "the tie indices reuse the histogram");
+    __shared__ RowDesc now;                                    // the row's descriptor as the kernel found it
     const uint32_t row = row0 + blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+    // one round trip for the whole descriptor instead of one per dependent field; nobody else writes it meanwhile
+    static_assert(sizeof(RowDesc) == 64 * sizeof(uint32_t), "64 lanes copy the descriptor");
+    if (tid < 64) reinterpret_cast<uint32_t*>(&now)[tid] = reinterpret_cast<const uint32_t*>(&desc[row])[tid];
     // the meeting counter and give-up flag of the general search that may follow start every step at zero
     if (slow_sync && tid < 2) slow_sync[(size_t)blockIdx.x * 2 + tid] = 0;
-    if (desc[row].mode == kSlow) return;
-    const bool cold = wants_cold(desc[row], cap, k);           // uniform for the block
-    const uint32_t missed = (cold && desc[row].mode == kWarm) ? 1u : 0u;    // there was a prediction and it failed
+    __syncthreads();
+    if (now.mode == kSlow) return;
+    const bool cold = wants_cold(now, cap, k);                  // uniform for the block
+    const uint32_t missed = (cold && now.mode == kWarm) ? 1u : 0u;    // there was a prediction and it failed
     uint32_t* __restrict__ hrow = ghist + (size_t)row * kHistBins;
     const uint2* __restrict__ in = list + (size_t)row * cap;
     uint32_t lo, hi, n, n_sure;
@@ -626,15 +632,15 @@ __global__ __launch_bounds__(kSelectBlock) void k_list_select(uint32_t row0, Row
         const Pick p = block_pick(hrow, kHistBins, k, part, res);
         lo = p.bin << 19;
         hi = (p.bin + 1) << 19;
-        n = desc[row].n_cand2;
-        n_sure = sure_count2(desc[row]);
+        n = now.n_cand2;
+        n_sure = sure_count2(now);
         ok = p.count <= cap && n <= cap && n_sure < k && (uint64_t)k <= (uint64_t)n_sure + n;
         shift = first_shift(hi - lo, kListBits);
     } else {                                                    // kWarm and band_ok
-        lo = desc[row].lo;
-        hi = desc[row].hi;
-        n = desc[row].n_cand;
-        n_sure = sure_count(desc[row]);
+        lo = now.lo;
+        hi = now.hi;
+        n = now.n_cand;
+        n_sure = sure_count(now);
         direct = n <= (uint32_t)kDirectList;
         shift = first_shift(hi - lo, direct ? kListBits : kFirstBits);
         if (!direct) ph = block_pick(hrow, 1 << kFirstBits, k - n_sure, part, res);
@@ -643,7 +649,7 @@ __global__ __launch_bounds__(kSelectBlock) void k_list_select(uint32_t row0, Row
         for (int b = tid; b < kHistBins; b += kSelectBlock) hrow[b] = 0;    // the row's histogram is ready for the next step
     if (!ok) {
         if (tid == 0) {
-            RowDesc r = desc[row];
+            RowDesc r = now;
             clear_counts(r);
             r.n_list = 0;
             r.misses += missed;
@@ -653,7 +659,7 @@ __global__ __launch_bounds__(kSelectBlock) void k_list_select(uint32_t row0, Row
         return;
     }
     const uint32_t n_all = n;
-    if (!direct && ph.count <= (uint32_t)kShortCap && desc[row].n_short == ph.count) {
+    if (!direct && ph.count <= (uint32_t)kShortCap && now.n_short == ph.count) {
         in = shortl + (size_t)row * kShortCap;                  // the bin's entries, collected by the second filter pass
         n = ph.count;
     }
@@ -738,7 +744,7 @@ __global__ __launch_bounds__(kSelectBlock) void k_list_select(uint32_t row0, Row
         __syncthreads();
     }
     if (tid == 0) {
-        RowDesc r = desc[row];
+        RowDesc r = now;
         r.n_list = n_all;
         clear_counts(r);
         r.tau = tau;
